@@ -1,0 +1,397 @@
+"""Pins for the CPU oracle: each test ties a piece of oracle/ to something the paper or the
+mathematics fixes independently of the oracle's own code (closed forms, invariants, a library
+routine on a special case, brute force on tiny inputs).  None of these touches the GPU path."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tkv_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng(1234)
+
+
+# ---------------------------------------------------------------- attention: closed forms
+def test_softmax_mass_is_one():
+    K = rng.normal(size=(37, 16)) * 3
+    q = rng.normal(size=16)
+    live = rng.random(37) > 0.3
+    a = O.attention_weights(q, K, live, 0.25)
+    assert abs(a.sum() - 1.0) < 1e-14
+    assert np.all(a[~live] == 0.0) and np.all(a[live] > 0.0)
+
+
+def test_identical_keys_give_uniform_weights_and_mean_value():
+    K = np.tile(rng.normal(size=(1, 8)), (11, 1))
+    V = rng.normal(size=(11, 8))
+    o, a = O.attend_head(rng.normal(size=8), K, V, np.ones(11, bool), 0.3)
+    assert np.allclose(a, 1.0 / 11, atol=1e-15)
+    assert np.allclose(o, V.mean(axis=0), atol=1e-14)
+
+
+def test_two_token_case_is_a_sigmoid():
+    # x_1 = a * scale, x_2 = 0  =>  alpha_1 = 1 / (1 + exp(-a * scale))
+    a_, scale = 2.7, 1.0 / math.sqrt(4)
+    q = np.array([a_, 0, 0, 0.0])
+    K = np.array([[1.0, 0, 0, 0], [0, 0, 0, 0]])
+    V = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0]])
+    o, a = O.attend_head(q, K, V, np.ones(2, bool), scale)
+    s = 1.0 / (1.0 + math.exp(-a_ * scale))
+    assert abs(a[0] - s) < 1e-15 and abs(a[1] - (1 - s)) < 1e-15
+    assert np.allclose(o, [s, 1 - s, 0, 0], atol=1e-15)
+
+
+def test_basis_probe_pins_operand_roles():
+    # keys = c_i * e_i, values = e_{pi(i)}: logits are q_i * c_i * scale and the output is a
+    # permuted softmax of them.  A transposed operand, a swapped K/V or a dropped scale fails.
+    d = 6
+    c = np.array([0.5, -1.0, 2.0, 1.5, -0.25, 3.0])
+    pi = np.array([3, 0, 5, 1, 4, 2])
+    K = np.diag(c)
+    V = np.eye(d)[pi]
+    q = rng.normal(size=d)
+    scale = 0.37
+    x = q * c * scale
+    want_a = np.exp(x) / np.exp(x).sum()
+    o, a = O.attend_head(q, K, V, np.ones(d, bool), scale)
+    assert np.allclose(a, want_a, atol=1e-15)
+    want_o = np.zeros(d)
+    want_o[pi] = want_a
+    assert np.allclose(o, want_o, atol=1e-15)
+
+
+def test_gqa_head_mapping_is_h_div_G():
+    B, Hq, Hkv, n, d = 1, 6, 2, 5, 4
+    K = rng.normal(size=(B, Hkv, n, d))
+    V = np.zeros((B, Hkv, n, d))
+    V[:, 0] = 1.0
+    V[:, 1] = 2.0
+    q = rng.normal(size=(B, Hq, d))
+    out, _ = O.attend_gqa(q, K, V, np.ones((B, n), bool), 0.5)
+    assert np.allclose(out[0, :3], 1.0) and np.allclose(out[0, 3:], 2.0)
+
+
+def test_full_cache_matches_float64_sdpa():
+    # special case with no eviction: a library routine (torch SDPA, float64, K/V expanded over the group)
+    B, Hq, Hkv, n, d = 2, 8, 2, 67, 32
+    G = Hq // Hkv
+    K = rng.normal(size=(B, Hkv, n, d)) * np.exp(rng.normal(size=(B, 1, n, 1)))
+    V = rng.normal(size=(B, Hkv, n, d))
+    q = rng.normal(size=(B, Hq, d))
+    out, alpha = O.attend_gqa(q, K, V, np.ones((B, n), bool), 1.0 / math.sqrt(d))
+    tq = torch.from_numpy(q)[:, :, None, :]
+    tk = torch.from_numpy(K).repeat_interleave(G, dim=1)
+    tv = torch.from_numpy(V).repeat_interleave(G, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[:, :, 0, :].numpy()
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
+    assert np.allclose(alpha.sum(-1), 1.0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- Eq. 3, Eq. 4, Prop. 1
+def test_eviction_is_softmax_over_survivors_eq3():
+    n, d = 40, 8
+    K, V, q = rng.normal(size=(n, d)) * 2, rng.normal(size=(n, d)), rng.normal(size=d)
+    live = np.ones(n, bool)
+    live[rng.choice(n, 9, replace=False)] = False
+    o, a = O.attend_head(q, K, V, live, 0.35)
+    o_ref, a_ref = O.attend_head(q, K[live], V[live], np.ones(live.sum(), bool), 0.35)
+    assert np.allclose(o, o_ref, atol=1e-15) and np.allclose(a[live], a_ref, atol=1e-16)
+    # and it is the full softmax renormalised by the surviving mass (Z'/Z)
+    _, a_full = O.attend_head(q, K, V, np.ones(n, bool), 0.35)
+    assert np.allclose(a[live], a_full[live] / a_full[live].sum(), atol=1e-15)
+
+
+def test_error_bound_eq4_holds():
+    for trial in range(50):
+        n, d = 60, 16
+        K, V, q = rng.normal(size=(n, d)) * 2, rng.normal(size=(n, d)) * 3, rng.normal(size=d)
+        ev = np.zeros(n, bool)
+        ev[rng.choice(n, rng.integers(1, 20), replace=False)] = True
+        o_full, a_full = O.attend_head(q, K, V, np.ones(n, bool), 0.25)
+        o_hat, _ = O.attend_head(q, K, V, ~ev, 0.25)
+        assert np.linalg.norm(o_hat - o_full) <= O.eviction_error_bound(a_full, V, ev) + 1e-14
+
+
+def _mk_cache(L=2, B=2, Hq=4, Hkv=2, d=16, n=48, **kw):
+    c = O.OracleCache(L, B, Hq, Hkv, d, max_tokens=n + 8, kv_dtype="f32", k_sink=2, k_window=4, **kw)
+    data = {}
+    for l in range(L):
+        k = rng.normal(size=(B, n, Hkv, d)).astype(np.float32)
+        v = rng.normal(size=(B, n, Hkv, d)).astype(np.float32)
+        c.append(l, k, v)
+        data[l] = (k, v)
+    return c, data
+
+
+def test_prop1_offloading_is_exact():
+    c1, data = _mk_cache()
+    c2 = O.OracleCache(2, 2, 4, 2, 16, max_tokens=56, kv_dtype="f32", k_sink=2, k_window=4)
+    for l, (k, v) in data.items():
+        c2.append(l, k, v)
+    tiers = np.zeros((2, 48), np.uint8)
+    tiers[:, 5:40:2] = O.T1
+    tiers[:, 7] = O.T3
+    all_t0 = np.where(tiers == O.T1, O.T0, tiers)
+    c1.set_tiers(tiers); c1.migrate()
+    c2.set_tiers(all_t0); c2.migrate()
+    for l in range(2):
+        q = rng.normal(size=(2, 4, 16))
+        assert np.array_equal(c1.attend_and_score(l, q), c2.attend_and_score(l, q))
+    assert np.array_equal(c1.score, c2.score)
+
+
+def test_score_total_closed_form():
+    # each head's weights sum to 1 over the live set, so every layer call adds Hq * score_scale
+    # to the sequence's total; with score_scale = 1/(L*Hq) a step adds exactly 1 (Eq. 1).
+    c, _ = _mk_cache()
+    tiers = np.zeros((2, 48), np.uint8)
+    tiers[:, 10:20] = O.T3
+    tiers[:, 20:30] = O.T2
+    c.set_tiers(tiers); c.migrate()
+    steps = 3
+    for _ in range(steps):
+        for l in range(2):
+            c.attend_and_score(l, rng.normal(size=(2, 4, 16)))
+    assert np.allclose(c.score.sum(axis=1), steps, atol=1e-12)
+    assert np.all(c.score[:, 10:20] == 0.0)
+    c2, _ = _mk_cache(score_scale=1.0)
+    c2.attend_and_score(0, rng.normal(size=(2, 4, 16)))
+    assert np.allclose(c2.score.sum(axis=1), 4.0, atol=1e-12)
+
+
+def test_score_uniform_case():
+    c = O.OracleCache(1, 1, 4, 2, 8, max_tokens=10, kv_dtype="f32", score_scale=1.0)
+    k = np.tile(rng.normal(size=(1, 1, 2, 8)), (1, 10, 1, 1)).astype(np.float32)
+    c.append(0, k, k)
+    c.attend_and_score(0, rng.normal(size=(1, 4, 8)))
+    assert np.allclose(c.score[0], 4.0 / 10, atol=1e-15)
+
+
+# ---------------------------------------------------------------- storage rounding, codec
+def test_bf16_rounding_matches_library_and_ties_to_even():
+    x = (rng.normal(size=5000) * np.exp(rng.normal(size=5000) * 4)).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.round_to_bf16(x), ref)
+    ties = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -(1 + 2.0 ** -8), 1 + 2.0 ** -8 + 2.0 ** -20], np.float32)
+    assert np.array_equal(O.round_to_bf16(ties), np.array([1.0, 1 + 2.0 ** -6, -1.0, 1 + 2.0 ** -7], np.float32))
+
+
+def test_int8_hand_example_ties_to_even():
+    x = np.zeros(16, np.float32)
+    x[:7] = [127.0, -63.5, 0.5, 1.5, 2.5, -126.6, 3.49]
+    codes, scale = O.quant_int8_row(x)
+    assert scale == np.float32(1.0)
+    assert list(codes[:7]) == [127, -64, 0, 2, 2, -127, 3]
+    assert np.array_equal(O.dequant_int8_row(codes, scale), codes.astype(np.float64))
+
+
+def test_int8_properties():
+    x = (rng.normal(size=(200, 128)) * np.exp(rng.normal(size=(200, 1)) * 3)).astype(np.float32)
+    x[17] = 0.0
+    codes, scale = O.quant_int8_row(x)
+    xh = O.dequant_int8_row(codes, scale)
+    assert codes.dtype == np.int8 and np.abs(codes.astype(int)).max() <= 127
+    assert scale[17] == 0 and np.all(codes[17] == 0) and np.all(xh[17] == 0)
+    rows = np.arange(200) != 17
+    amax = np.argmax(np.abs(x), axis=1)
+    assert np.all(np.abs(codes[np.arange(200), amax].astype(int))[rows] == 127)
+    assert np.all(np.abs(x - xh)[rows] <= (scale[rows, None].astype(np.float64) * (0.5 + 1e-6)))
+    assert np.all(np.sign(codes[rows]) * np.sign(x[rows]) >= 0)
+
+
+def test_int4_hand_example_and_fp16_scale():
+    x = np.zeros(64, np.float32)
+    x[:5] = [7.0, 3.5, -2.5, 0.49, -6.6]          # group 0: scale 1
+    x[32] = np.float32(7.0 * (1 + 2.0 ** -12))      # group 1: a/7 = 1 + 2^-12 -> binary16 1.0
+    x[33] = 0.5
+    codes, scale = O.quant_int4_g32(x)
+    assert list(scale) == [1.0, 1.0]
+    assert list(codes[:5]) == [7, 4, -2, 0, -7]
+    assert codes[32] == 7 and codes[33] == 0
+    p = O.pack_int4(codes)
+    assert p[0] == (7 | (4 << 4)) and p[1] == ((-2 & 0xF) | 0) and p[2] == ((-7 & 0xF))
+
+
+def test_int4_properties():
+    x = (rng.normal(size=(100, 128)) * np.exp(rng.normal(size=(100, 1)) * 2)).astype(np.float32)
+    x[3, 32:64] = 0.0
+    x[4, :32] = 1e-9                                   # scale underflows binary16 -> zero codes
+    codes, scale = O.quant_int4_g32(x)
+    assert np.abs(codes.astype(int)).max() <= 7
+    assert scale.shape == (100, 4)
+    assert np.array_equal(scale, scale.astype(np.float16).astype(np.float32))
+    assert np.all(codes[3, 32:64] == 0) and scale[3, 1] == 0
+    assert scale[4, 0] == 0 and np.all(codes[4, :32] == 0)
+    xh = O.dequant_int4_g32(codes, scale)
+    ok = np.repeat(scale > 0, 32, axis=1)
+    # |x/scale| can exceed 7 by the binary16 rounding of the scale (clipped), so the bound is
+    # scale/2 inside the range plus that rounding slack (2^-11 relative on 7*scale)
+    bound = np.repeat(scale, 32, axis=1).astype(np.float64) * (0.5 + 7 * 2.0 ** -11 + 1e-6)
+    assert np.all(np.abs(x - xh)[ok] <= bound[ok])
+
+
+def test_promotion_value_is_binary32_product_rounded_to_storage():
+    codes = np.array([[127, -3, 0, 55]], np.int8)
+    scale = np.array([0.0123456789], np.float32)
+    got = O.t2_decode_to_storage(codes, scale, "int8_row", "bf16")
+    want = torch.from_numpy(codes.astype(np.float32) * scale).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got, want)
+    got32 = O.t2_decode_to_storage(codes, scale, "int8_row", "f32")
+    assert np.array_equal(got32, codes.astype(np.float32) * scale)
+
+
+# ---------------------------------------------------------------- tier sizes and ranking
+def test_tier_counts_exact_floors():
+    for m in [0, 1, 7, 64, 999, 1000, 3964, 16268, 123457]:
+        for pol in [(300000, 520000, 150000, 30000), (500000, 300000, 150000, 50000), (333333, 333333, 333333, 1),
+                    (1000000, 0, 0, 0), (0, 0, 0, 1000000)]:
+            n0, n1, n2, n3 = O.tier_counts(m, pol)
+            assert n3 == math.floor(Fraction(pol[3], 10 ** 6) * m)
+            assert n2 == math.floor(Fraction(pol[2], 10 ** 6) * m)
+            assert n0 == math.floor(Fraction(pol[0], 10 ** 6) * m)
+            assert n0 + n1 + n2 + n3 == m and n1 >= 0
+
+
+def test_tier_counts_against_algorithm1_golden():
+    # The fixture holds Algorithm 1's own floors evaluated by hand.  This build expresses the
+    # bands as fractions of |U| (f0 = beta*(1-r), f3 = r, no T2): n_evict must agree exactly and
+    # n_hbm to within one token (floor(beta*(m - floor(r m))) vs floor(beta (1-r) m)).
+    with open(os.path.join(GOLDEN, "alg1_counts.txt")) as f:
+        rows = [tuple(int(t) for t in ln.split()) for ln in f if ln.strip() and not ln.startswith("#")]
+    assert len(rows) >= 8
+    for m, beta, r, n_hbm, n_ddr, n_evict in rows:
+        assert n_hbm + n_ddr + n_evict == m
+        f3 = r * 10000
+        f0 = beta * (100 - r) * 100
+        n0, n1, n2, n3 = O.tier_counts(m, (f0, 10 ** 6 - f0 - f3, 0, f3))
+        assert n3 == n_evict and n2 == 0
+        assert abs(n0 - n_hbm) <= 1 and abs(n1 - n_ddr) <= 1
+
+
+def test_tier_counts_keep_evicted():
+    assert O.tier_counts(100, (500000, 300000, 150000, 50000), n_already_evicted=3) == (50, 30, 15, 5)
+    assert O.tier_counts(100, (500000, 300000, 150000, 50000), n_already_evicted=12) == (50, 30, 8, 12)
+    assert O.tier_counts(100, (500000, 300000, 150000, 50000), n_already_evicted=25) == (50, 25, 0, 25)
+    assert O.tier_counts(100, (500000, 300000, 150000, 50000), n_already_evicted=70) == (30, 0, 0, 70)
+
+
+def _brute_force_tiers(score32, tier_prev, n, n_prompt, k_sink, k_window, pol):
+    """Rank of a candidate = number of candidates with a smaller (live, bits, position) key,
+    by O(m^2) counting -- no sort."""
+    lo, hi = n_prompt + k_sink, n - k_window
+    out = np.zeros(n, np.uint8)
+    if hi <= lo:
+        return out
+    m = hi - lo
+    bits = score32.view(np.uint32)
+    ev = int(sum(tier_prev[i] == 3 for i in range(lo, hi)))
+    n3 = max((pol[3] * m) // 10 ** 6, ev)
+    n2 = (pol[2] * m) // 10 ** 6
+    n0 = (pol[0] * m) // 10 ** 6
+    n1 = m - n0 - n2 - (pol[3] * m) // 10 ** 6
+    over = n3 - (pol[3] * m) // 10 ** 6
+    for name in ("n2", "n1", "n0"):
+        take = min(over, locals()[name])
+        if name == "n2": n2 -= take
+        elif name == "n1": n1 -= take
+        else: n0 -= take
+        over -= take
+    for i in range(lo, hi):
+        ki = (tier_prev[i] != 3, int(bits[i]), i)
+        rank = sum((tier_prev[j] != 3, int(bits[j]), j) < ki for j in range(lo, hi))
+        out[i] = 3 if rank < n3 else 2 if rank < n3 + n2 else 1 if rank < n3 + n2 + n1 else 0
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_classify_matches_brute_force_with_ties_and_evicted(seed):
+    r = np.random.default_rng(seed)
+    n = int(r.integers(20, 120))
+    n_prompt, k_sink, k_window = int(r.integers(0, 5)), int(r.integers(0, 5)), int(r.integers(0, 12))
+    score = r.choice(np.array([0.0, 0.125, 0.5, 0.5000001, 1.0, 3.25], np.float32), size=n)  # many ties
+    if seed % 2:
+        score = (r.random(n) ** 4).astype(np.float32)
+    tier_prev = np.zeros(n, np.uint8)
+    lo, hi = n_prompt + k_sink, n - k_window
+    if hi > lo and seed >= 2:
+        ev = r.choice(np.arange(lo, hi), size=min(hi - lo, int(r.integers(1, 15))), replace=False)
+        tier_prev[ev] = 3
+    pol = [(500000, 300000, 150000, 50000), (300000, 520000, 150000, 30000), (250000, 250000, 250000, 250000)][seed % 3]
+    got = O.classify_sequence(score, tier_prev, n, n_prompt, k_sink, k_window, pol)
+    want = _brute_force_tiers(score, tier_prev, n, n_prompt, k_sink, k_window, pol)
+    assert np.array_equal(got, want)
+    # structural facts: protected -> T0, evicted stay evicted, band sizes
+    if hi > lo:
+        assert np.all(got[:lo] == 0) and np.all(got[hi:] == 0)
+        assert np.all(got[tier_prev == 3] == 3)
+        n0, n1, n2, n3 = O.tier_counts(hi - lo, pol, int(np.sum(tier_prev[lo:hi] == 3)))
+        cand = got[lo:hi]
+        assert [(cand == t).sum() for t in range(4)] == [n0, n1, n2, n3]
+    else:
+        assert np.all(got == 0)
+
+
+def test_classify_ranks_by_score_and_lower_position_loses_ties():
+    # 10 candidates, no protection; scores ascending except a tie between positions 2 and 6
+    score = np.array([0.9, 0.1, 0.4, 0.8, 0.2, 0.7, 0.4, 0.3, 0.6, 0.5], np.float32)
+    pol = (300000, 300000, 200000, 200000)      # n0=3 n1=3 n2=2 n3=2
+    got = O.classify_sequence(score, np.zeros(10, np.uint8), 10, 0, 0, 0, pol)
+    # ascending: 1(.1) 4(.2) | 7(.3) 2(.4) | 6(.4) 9(.5) 8(.6) | 5(.7) 3(.8) 0(.9)
+    assert list(got) == [0, 3, 2, 0, 3, 0, 1, 2, 1, 1]
+
+
+def test_compact_lists_partition_and_order():
+    tier = rng.integers(0, 4, size=200).astype(np.uint8)
+    lists = O.compact_lists(tier, 150)
+    allpos = np.concatenate(lists)
+    assert sorted(allpos.tolist()) == list(range(150))
+    for t, lst in enumerate(lists):
+        assert np.all(np.diff(lst) > 0) and np.all(tier[lst] == t)
+
+
+# ---------------------------------------------------------------- migrate
+def test_migrate_round_trips_and_t2_semantics():
+    c, data = _mk_cache(L=1, B=1, n=32)
+    k0 = c.K[0].copy()
+    t = np.zeros((1, 32), np.uint8)
+    t[0, 5:15] = O.T1
+    c.set_tiers(t); c.migrate()
+    assert np.array_equal(c.K[0], k0)
+    c.set_tiers(np.zeros((1, 32), np.uint8)); c.migrate()
+    assert np.array_equal(c.K[0], k0)
+    t2 = np.zeros((1, 32), np.uint8)
+    t2[0, 8:12] = O.T2
+    c.set_tiers(t2); c.migrate()
+    kc, ks, vc, vs = c.t2[0][(0, 9)]
+    assert np.array_equal(c.K[0][0, :, 9], O.dequant_int8_row(kc, ks))
+    assert not np.array_equal(c.K[0][0, :, 9], k0[0, :, 9])
+    kq = c.K[0].copy()
+    c.set_tiers(t2); c.migrate()                      # T2 -> T2: codes kept, no re-quantisation
+    assert np.array_equal(c.K[0], kq)
+    c.set_tiers(np.zeros((1, 32), np.uint8)); c.migrate()   # promotion keeps the lossy value
+    assert np.array_equal(c.K[0][0, :, 9].astype(np.float32),
+                          (kc.astype(np.float32) * ks[:, None]).astype(np.float32))
+    t3 = np.zeros((1, 32), np.uint8)
+    t3[0, 20] = O.T3
+    c.set_tiers(t3); c.migrate()
+    assert np.all(c.K[0][0, :, 20] == 0)
+    c.set_tiers(np.zeros((1, 32), np.uint8))
+    with pytest.raises(RuntimeError):
+        c.migrate()
+
+
+def test_cache_classify_then_attend_skips_evicted():
+    c, _ = _mk_cache(L=1, B=1, n=40)
+    c.attend_and_score(0, rng.normal(size=(1, 4, 16)))
+    new = c.classify((400000, 300000, 200000, 100000))
+    c.migrate()
+    s_before = c.score.copy()
+    c.attend_and_score(0, rng.normal(size=(1, 4, 16)))
+    ev = new[0, :40] == O.T3
+    assert ev.sum() == (40 - 6) // 10
+    assert np.array_equal(c.score[0, :40][ev], s_before[0, :40][ev])
+    assert np.all(c.score[0, :40][~ev] > s_before[0, :40][~ev])
