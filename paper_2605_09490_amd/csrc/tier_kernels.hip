@@ -1,0 +1,529 @@
+// Tier management on the device (Sec. 3.3 / Algorithm 1 of the paper): append, rank-based tier assignment by
+// radix select, plan counting, plan commit (stream compaction of the tier lists by prefix sums, slot
+// allocation from per-pool free stacks), and the row movers (copy, encode, decode, gather, scatter).
+// One workgroup of PLAN_THREADS threads owns one sequence in the planning kernels; all work is integer.
+#include "tkv_internal.h"
+
+namespace tkv {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+struct Ppm { uint32_t f[4]; };
+
+// ---------------------------------------------------------------------------------------------------------
+__global__ void k_init_state(DevView v) {
+  const int b = blockIdx.x;
+  for (int i = threadIdx.x; i < v.Nmax; i += blockDim.x) {
+    const size_t o = (size_t)b * v.Nmax + i;
+    v.tier[o] = 0; v.tier_new[o] = 0; v.loc[o] = -1; v.hloc[o] = -1; v.score[o] = 0.f;
+  }
+  // stacks: the top (highest index) pops first, so slots come out in ascending order
+  for (int j = threadIdx.x; j < v.cap0; j += blockDim.x) v.free0[(size_t)b * v.cap0 + j] = v.cap0 - 1 - j;
+  for (int j = threadIdx.x; j < v.cap1; j += blockDim.x) v.free1[(size_t)b * v.cap1 + j] = v.cap0 + v.cap1 - 1 - j;
+  for (int j = threadIdx.x; j < v.cap2; j += blockDim.x) v.free2[(size_t)b * v.cap2 + j] = v.cap2 - 1 - j;
+  if (threadIdx.x < CNT_N) {
+    int val = 0;
+    if (threadIdx.x == C_FREE0) val = v.cap0;
+    if (threadIdx.x == C_FREE1) val = v.cap1;
+    if (threadIdx.x == C_FREE2) val = v.cap2;
+    v.cnt[b * CNT_N + threadIdx.x] = val;
+  }
+}
+hipError_t launch_init_state(const DevView& v, hipStream_t st) {
+  hipLaunchKernelGGL(k_init_state, dim3(v.B), dim3(256), 0, st, v);
+  return hipGetLastError();
+}
+
+// ---- append ------------------------------------------------------------------------------------------------
+// New positions enter T0 (Algorithm 1: the cache grows by the generated token; it is inside the recent window).
+__global__ void k_append_assign(DevView v, int pos0, int n_new) {
+  const int b = blockIdx.x;
+  int* cnt = v.cnt + b * CNT_N;
+  const int nfree = cnt[C_FREE0], nF = cnt[C_NF], n0 = cnt[C_N0], len = cnt[C_LEN];
+  __syncthreads();
+  for (int j = threadIdx.x; j < n_new; j += blockDim.x) {
+    const int p = pos0 + j;
+    if (nfree - 1 - j < 0 || p >= v.Nmax) continue;   // the host checks capacity before launching
+    const int slot = v.free0[(size_t)b * v.cap0 + nfree - 1 - j];
+    const size_t o = (size_t)b * v.Nmax;
+    v.tier[o + p] = 0; v.loc[o + p] = slot; v.hloc[o + p] = -1;
+    v.f_pos[o + nF + j] = p; v.f_loc[o + nF + j] = slot; v.f_loc_old[o + nF + j] = slot;
+    v.idx[((size_t)0 * v.B + b) * v.Nmax + n0 + j] = p;
+  }
+  if (threadIdx.x == 0) {
+    cnt[C_FREE0] = nfree - n_new; cnt[C_NF] = nF + n_new; cnt[C_N0] = n0 + n_new; cnt[C_LEN] = len + n_new;
+  }
+}
+
+// k, v: [B][n_new][Hkv][D]; one thread per 16-byte piece of a row
+__global__ void k_append_rows(DevView v, int layer, const char* __restrict__ k, const char* __restrict__ vv, int pos0, int n_new) {
+  const int row_bytes = v.D * v.es, cpr = row_bytes / 16;
+  const long long total = (long long)v.B * n_new * v.Hkv * cpr;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cpr);
+  long long r = i / cpr;
+  const int kvh = (int)(r % v.Hkv); r /= v.Hkv;
+  const int j = (int)(r % n_new);
+  const int b = (int)(r / n_new);
+  const int slot = v.loc[(size_t)b * v.Nmax + pos0 + j];
+  if (slot < 0 || slot >= v.capF) return;
+  const size_t dst = ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capF + slot) * row_bytes + (size_t)c * 16;
+  const size_t src = (size_t)i * 16;
+  *(u32x4*)(v.fpK + dst) = *(const u32x4*)(k + src);
+  *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + src);
+}
+
+hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new, bool assign,
+                         hipStream_t st) {
+  if (assign) hipLaunchKernelGGL(k_append_assign, dim3(v.B), dim3(256), 0, st, v, pos0, n_new);
+  const long long total = (long long)v.B * n_new * v.Hkv * (v.D * v.es / 16);
+  const int blocks = (int)((total + 255) / 256);
+  hipLaunchKernelGGL(k_append_rows, dim3(blocks), dim3(256), 0, st, v, layer, (const char*)k, (const char*)v_, pos0, n_new);
+  return hipGetLastError();
+}
+
+// ---- classify: radix select of the band boundaries ------------------------------------------------------
+// key = already-evicted-first | score bits | position : 1 + 31 + 24 bits, all distinct.
+__device__ __forceinline__ uint64_t rank_key(uint8_t tier_prev, float score, int pos) {
+  const uint64_t live = tier_prev == 3 ? 0ull : 1ull;
+  const uint64_t bits = __builtin_bit_cast(uint32_t, score) & 0x7fffffffu;
+  return (live << 55) | (bits << 24) | (uint64_t)pos;
+}
+
+__device__ void band_counts(const Ppm& p, long long m, long long evicted, long long out[4]) {
+  long long n3 = ((long long)p.f[3] * m) / 1000000, n2 = ((long long)p.f[2] * m) / 1000000;
+  long long n0 = ((long long)p.f[0] * m) / 1000000, n1 = m - n0 - n2 - n3;
+  long long extra = evicted - n3;
+  if (extra > 0) {
+    n3 += extra;
+    long long t = extra < n2 ? extra : n2; n2 -= t; extra -= t;
+    t = extra < n1 ? extra : n1; n1 -= t; extra -= t;
+    t = extra < n0 ? extra : n0; n0 -= t; extra -= t;
+  }
+  out[0] = n0; out[1] = n1; out[2] = n2; out[3] = n3;
+}
+
+__global__ __launch_bounds__(PLAN_THREADS) void k_classify(DevView v, int n, Ppm ppm) {
+  __shared__ int hist[256];
+  __shared__ int sh_e;
+  __shared__ unsigned long long sh_prefix;
+  __shared__ int sh_k;
+  __shared__ unsigned long long sh_thr[3];
+  const int b = blockIdx.x, t = threadIdx.x;
+  const uint8_t* tier = v.tier + (size_t)b * v.Nmax;
+  uint8_t* tnew = v.tier_new + (size_t)b * v.Nmax;
+  const float* score = v.score + (size_t)b * v.Nmax;
+  const int lo = v.n_prompt + v.k_sink;
+  const int hi = n - v.k_window;
+  if (hi <= lo) {
+    for (int i = t; i < n; i += PLAN_THREADS) tnew[i] = 0;
+    return;
+  }
+  const int m = hi - lo;
+  if (t == 0) sh_e = 0;
+  __syncthreads();
+  int e = 0;
+  for (int i = lo + t; i < hi; i += PLAN_THREADS) e += tier[i] == 3;
+  if (e) atomicAdd(&sh_e, e);
+  __syncthreads();
+  long long bc[4];
+  band_counts(ppm, m, sh_e, bc);
+  // 0-based ranks at which T2, T1 and T0 start
+  const long long ranks[3] = {bc[3], bc[3] + bc[2], bc[3] + bc[2] + bc[1]};
+  for (int q = 0; q < 3; ++q) {
+    const long long k = ranks[q];
+    if (k <= 0) { if (t == 0) sh_thr[q] = 0ull; continue; }
+    if (k >= m) { if (t == 0) sh_thr[q] = ~0ull; continue; }
+    if (t == 0) { sh_prefix = 0ull; sh_k = (int)k; }
+    for (int shift = 48; shift >= 0; shift -= 8) {
+      if (t < 256) hist[t] = 0;
+      __syncthreads();
+      const unsigned long long prefix = sh_prefix;
+      for (int i = lo + t; i < hi; i += PLAN_THREADS) {
+        const uint64_t key = rank_key(tier[i], score[i], i);
+        if (shift == 48 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(key >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (t == 0) {
+        int kk = sh_k, d = 0;
+        for (; d < 255; ++d) {
+          const int c = hist[d];
+          if (kk < c) break;
+          kk -= c;
+        }
+        sh_k = kk;
+        sh_prefix = prefix | ((unsigned long long)d << shift);
+      }
+      __syncthreads();
+    }
+    if (t == 0) sh_thr[q] = sh_prefix;   // the key with exactly k smaller keys
+  }
+  __syncthreads();
+  const uint64_t th3 = sh_thr[0], th2 = sh_thr[1], th1 = sh_thr[2];
+  for (int i = t; i < n; i += PLAN_THREADS) {
+    uint8_t c = 0;
+    if (i >= lo && i < hi) {
+      const uint64_t key = rank_key(tier[i], score[i], i);
+      c = key < th3 ? 3 : key < th2 ? 2 : key < th1 ? 1 : 0;
+    }
+    tnew[i] = c;
+  }
+}
+hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStream_t st) {
+  Ppm p; for (int i = 0; i < 4; ++i) p.f[i] = ppm[i];
+  hipLaunchKernelGGL(k_classify, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n, p);
+  return hipGetLastError();
+}
+
+// ---- plan counting (no state change) ---------------------------------------------------------------------
+__global__ __launch_bounds__(PLAN_THREADS) void k_plan_count(DevView v, int n) {
+  __shared__ int c[16];
+  const int b = blockIdx.x, t = threadIdx.x;
+  if (t < 16) c[t] = 0;
+  __syncthreads();
+  const uint8_t* tier = v.tier + (size_t)b * v.Nmax;
+  const uint8_t* tnew = v.tier_new + (size_t)b * v.Nmax;
+  // index: 0..8 = M01 M02 M03 M10 M12 M13 M20 M21 M23, 9 = bad, 10..13 = planned tier counts
+  int loc[14];
+  for (int k = 0; k < 14; ++k) loc[k] = 0;
+  for (int i = t; i < n; i += PLAN_THREADS) {
+    const int a = tier[i], d = tnew[i];
+    if (d > 3) { loc[9]++; continue; }
+    loc[10 + d]++;
+    if (a == d) continue;
+    if (a == 3) { loc[9]++; continue; }
+    const int k = a * 3 + (d > a ? d - 1 : d);   // (a,d) -> 0..8 in the order above
+    loc[k]++;
+  }
+  for (int k = 0; k < 14; ++k) if (loc[k]) atomicAdd(&c[k], loc[k]);
+  __syncthreads();
+  int* cnt = v.cnt + b * CNT_N;
+  if (t < 9) cnt[C_M01 + t] = c[t];
+  if (t == 9) cnt[C_BAD] = c[9];
+  if (t >= 10 && t < 14) cnt[C_P0 + (t - 10)] = c[t];
+}
+hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st) {
+  hipLaunchKernelGGL(k_plan_count, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
+  return hipGetLastError();
+}
+
+// ---- plan commit -------------------------------------------------------------------------------------------
+// Exclusive scan of four packed 4x16-bit counters over the workgroup (chunk counts never exceed 1024).
+struct Pack4 { unsigned long long p[4]; };
+
+__device__ __forceinline__ Pack4 block_excl_scan(const Pack4& in, Pack4& total, unsigned long long (*wsum)[4]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  Pack4 inc = in;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const unsigned long long u = __shfl_up(inc.p[k], o);
+      if (lane >= o) inc.p[k] += u;
+    }
+  }
+  if (lane == 63) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wsum[wave][k] = inc.p[k];
+  }
+  __syncthreads();
+  Pack4 ex;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    unsigned long long pre = 0, tot = 0;
+    for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+      const unsigned long long s = wsum[w][k];
+      if (w < wave) pre += s;
+      tot += s;
+    }
+    ex.p[k] = pre + inc.p[k] - in.p[k];
+    total.p[k] = tot;
+  }
+  __syncthreads();
+  return ex;
+}
+
+__device__ __forceinline__ int fld(unsigned long long p, int k) { return (int)((p >> (16 * k)) & 0xFFFFull); }
+
+__global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) {
+  __shared__ unsigned long long wsum[PLAN_THREADS / 64][4];
+  const int b = blockIdx.x, t = threadIdx.x;
+  int* cnt = v.cnt + b * CNT_N;
+  const size_t o = (size_t)b * v.Nmax;
+  int nfree0 = cnt[C_FREE0];
+  const int nfree1 = cnt[C_FREE1], nfree2 = cnt[C_FREE2], npend = cnt[C_PEND];
+  int* free0 = v.free0 + (size_t)b * v.cap0;
+  int* free1 = v.free1 + (size_t)b * v.cap1;
+  int* free2 = v.free2 + (size_t)b * v.cap2;
+  __syncthreads();
+  // HBM slots whose rows were offloaded at the previous migrate are free now (their staged copies have landed)
+  for (int j = t; j < npend; j += PLAN_THREADS) {
+    if (nfree0 + j < v.cap0) free0[nfree0 + j] = v.pend[o + j];
+  }
+  nfree0 += npend;
+  if (nfree0 > v.cap0) nfree0 = v.cap0;
+  __syncthreads();
+
+  // running totals: t0 t1 t2 t3 | e0 e1 e2 r0i | r0p r1 r2 m10 | md
+  int run[13];
+  for (int k = 0; k < 13; ++k) run[k] = 0;
+  const int hbase = v.host_base[b];
+  for (int base = 0; base < n; base += PLAN_THREADS) {
+    const int i = base + t;
+    const bool in = i < n;
+    const int a = in ? v.tier[o + i] : 0, c = in ? v.tier_new[o + i] : 0;
+    const bool ch = in && a != c;
+    const int e0 = ch && ((a == 1 && c == 0) || (a == 2 && (c == 0 || c == 1)));
+    const int e1 = ch && c == 1;
+    const int e2 = ch && c == 2;
+    const int r0i = ch && a == 0 && (c == 2 || c == 3);
+    const int r0p = ch && c == 1;                // (a == 0 or a == 2): the HBM slot read by the offload
+    const int r1 = ch && a == 1;
+    const int r2 = ch && a == 2;
+    const int m10 = ch && a == 1 && c == 0;
+    const int md = ch && a == 2 && (c == 0 || c == 1);
+    Pack4 pk;
+    pk.p[0] = (unsigned long long)(in && c == 0) | ((unsigned long long)(in && c == 1) << 16) |
+              ((unsigned long long)(in && c == 2) << 32) | ((unsigned long long)(in && c == 3) << 48);
+    pk.p[1] = (unsigned long long)e0 | ((unsigned long long)e1 << 16) | ((unsigned long long)e2 << 32) |
+              ((unsigned long long)r0i << 48);
+    pk.p[2] = (unsigned long long)r0p | ((unsigned long long)r1 << 16) | ((unsigned long long)r2 << 32) |
+              ((unsigned long long)m10 << 48);
+    pk.p[3] = (unsigned long long)md;
+    Pack4 tot;
+    const Pack4 ex = block_excl_scan(pk, tot, wsum);
+    int rk[13], tt[13];
+    for (int k = 0; k < 13; ++k) { rk[k] = run[k] + fld(ex.p[k >> 2], k & 3); tt[k] = fld(tot.p[k >> 2], k & 3); }
+    // a chunk total of exactly 1024 does not fit a 16-bit field only if > 65535: fine
+    if (in) {
+      const int old_loc = v.loc[o + i];
+      int new_loc = old_loc, new_hloc = v.hloc[o + i], loc_for_old_list = -2;
+      int slot0 = -1;
+      if (e0) { const int k = nfree0 - 1 - rk[4]; slot0 = (k >= 0) ? free0[k] : -1; }
+      if (ch) {
+        if (c == 0) {
+          new_loc = slot0; new_hloc = -1;
+        } else if (c == 1) {
+          const int src0 = (a == 0) ? old_loc : slot0;
+          const int k1 = nfree1 - 1 - rk[5];
+          const int s1 = (k1 >= 0) ? free1[k1] : -1;
+          const int hl = hbase + rk[5];
+          new_loc = s1; new_hloc = hl; loc_for_old_list = src0;
+          const int gi = hl - v.event_base;
+          v.g_seq[gi] = b; v.g_src[gi] = src0; v.g_dst[gi] = s1;
+          v.pend[o + rk[8]] = src0;
+        } else if (c == 2) {
+          const int k2 = nfree2 - 1 - rk[6];
+          const int s2 = (k2 >= 0) ? free2[k2] : -1;
+          v.mvq_src[o + rk[6]] = old_loc; v.mvq_dst[o + rk[6]] = s2;
+          new_loc = s2; new_hloc = -1;
+        } else {
+          new_loc = -1; new_hloc = -1;
+        }
+        if (r0i) v.rel0[o + rk[7]] = old_loc;
+        if (r1) v.rel1[o + rk[9]] = old_loc;
+        if (r2) v.rel2[o + rk[10]] = old_loc;
+        if (m10) { v.mv10_src[o + rk[11]] = old_loc; v.mv10_dst[o + rk[11]] = slot0; }
+        if (md) { v.mvd_src[o + rk[12]] = old_loc; v.mvd_dst[o + rk[12]] = slot0; }
+        v.loc[o + i] = new_loc; v.hloc[o + i] = new_hloc; v.tier[o + i] = (uint8_t)c;
+      }
+      v.idx[((size_t)c * v.B + b) * v.Nmax + rk[c]] = i;
+      if (c <= 1) {
+        const int j = rk[0] + rk[1];
+        v.f_pos[o + j] = i; v.f_loc[o + j] = new_loc;
+        v.f_loc_old[o + j] = (loc_for_old_list != -2) ? loc_for_old_list : new_loc;
+      } else if (c == 2) {
+        v.q_pos[o + rk[2]] = i; v.q_loc[o + rk[2]] = new_loc;
+      }
+    }
+    for (int k = 0; k < 13; ++k) run[k] += tt[k];
+  }
+  __syncthreads();
+  // push the released slots above what is left of each stack
+  const int h0 = nfree0 - run[4], h1 = nfree1 - run[5], h2 = nfree2 - run[6];
+  for (int j = t; j < run[7]; j += PLAN_THREADS) if (h0 + j >= 0 && h0 + j < v.cap0) free0[h0 + j] = v.rel0[o + j];
+  for (int j = t; j < run[9]; j += PLAN_THREADS) if (h1 + j >= 0 && h1 + j < v.cap1) free1[h1 + j] = v.rel1[o + j];
+  for (int j = t; j < run[10]; j += PLAN_THREADS) if (h2 + j >= 0 && h2 + j < v.cap2) free2[h2 + j] = v.rel2[o + j];
+  if (t == 0) {
+    cnt[C_NF] = run[0] + run[1]; cnt[C_NQ] = run[2];
+    cnt[C_N0] = run[0]; cnt[C_N1] = run[1]; cnt[C_N2] = run[2]; cnt[C_N3] = run[3];
+    cnt[C_FREE0] = h0 + run[7]; cnt[C_FREE1] = h1 + run[9]; cnt[C_FREE2] = h2 + run[10];
+    cnt[C_PEND] = run[8];
+  }
+}
+hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st) {
+  hipLaunchKernelGGL(k_plan_commit, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
+  return hipGetLastError();
+}
+
+// ---- row movers ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ size_t fp_row(const DevView& v, int layer, int b, int kvh, int slot) {
+  return ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capF + slot) * (size_t)(v.D * v.es);
+}
+__device__ __forceinline__ size_t t2_row(const DevView& v, int layer, int b, int kvh, int slot) {
+  return (((size_t)layer * v.B + b) * v.Hkv + kvh) * v.cap2 + slot;
+}
+
+// T1 -> T0: staging slot -> HBM slot, bits preserved.  grid (pieces, Hkv*2, L*B)
+__global__ void k_move_copy(DevView v) {
+  const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
+  const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
+  const int cpr = v.D * v.es / 16;
+  const int n = v.cnt[b * CNT_N + C_M10];
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int j = i / cpr, c = i % cpr;
+  if (j >= n) return;
+  const int src = v.mv10_src[(size_t)b * v.Nmax + j], dst = v.mv10_dst[(size_t)b * v.Nmax + j];
+  if (src < 0 || src >= v.capF || dst < 0 || dst >= v.capF) return;
+  char* base = which ? v.fpV : v.fpK;
+  *(u32x4*)(base + fp_row(v, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(base + fp_row(v, layer, b, kvh, src) + c * 16);
+}
+
+__device__ __forceinline__ float load_elem(const char* row, int d, int es) {
+  if (es == 4) return ((const float*)row)[d];
+  return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)row)[d] << 16);
+}
+__device__ __forceinline__ void store_elem(char* row, int d, int es, float x) {
+  if (es == 4) { ((float*)row)[d] = x; return; }
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  ((uint16_t*)row)[d] = (uint16_t)(u >> 16);
+}
+
+// -> T2: encode the current stored row.  One wave per (row, K|V); block = 256 threads = 4 rows.
+// grid (ceil(maxq/4), Hkv*2, L*B).  All arithmetic in binary32, round-to-nearest-even, true division.
+__global__ __launch_bounds__(256) void k_move_quant(DevView v) {
+  const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
+  const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int n = v.cnt[b * CNT_N + C_M02] + v.cnt[b * CNT_N + C_M12];
+  if (j >= n) return;
+  const int src = v.mvq_src[(size_t)b * v.Nmax + j], dst = v.mvq_dst[(size_t)b * v.Nmax + j];
+  if (src < 0 || src >= v.capF || dst < 0 || dst >= v.cap2) return;
+  const char* row = (which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, src);
+  const size_t r2 = t2_row(v, layer, b, kvh, dst);
+  char* codes = (which ? v.c2V : v.c2K) + r2 * v.cb;
+  char* scales = (which ? v.s2V : v.s2K) + r2 * v.sb;
+  const int ept = v.D / 64;   // 1 or 2 elements per lane
+  float x[2] = {0.f, 0.f};
+  for (int e = 0; e < ept; ++e) x[e] = load_elem(row, lane * ept + e, v.es);
+  float a = fmaxf(fabsf(x[0]), fabsf(x[1]));
+  if (v.t2fmt == 0) {
+    for (int o = 32; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+    const float scale = a / 127.0f;
+    for (int e = 0; e < ept; ++e) {
+      float r = 0.f;
+      if (scale > 0.f) r = fminf(fmaxf(rintf(x[e] / scale), -127.f), 127.f);
+      ((int8_t*)codes)[lane * ept + e] = (int8_t)(int)r;
+    }
+    if (lane == 0) *(float*)scales = scale;
+  } else {
+    const int gl = 32 / ept;   // lanes per 32-element group
+    for (int o = gl >> 1; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+    const _Float16 sh = (_Float16)(a / 7.0f);
+    const float scale = (float)sh;
+    int q[2] = {0, 0};
+    for (int e = 0; e < ept; ++e) {
+      float r = 0.f;
+      if (scale > 0.f) r = fminf(fmaxf(rintf(x[e] / scale), -7.f), 7.f);
+      q[e] = ((int)r) & 0xF;
+    }
+    if (ept == 2) {
+      ((uint8_t*)codes)[lane] = (uint8_t)(q[0] | (q[1] << 4));
+    } else {
+      const int hi = __shfl_down(q[0], 1);
+      if ((lane & 1) == 0) ((uint8_t*)codes)[lane >> 1] = (uint8_t)(q[0] | (hi << 4));
+    }
+    if ((lane % gl) == 0) ((uint16_t*)scales)[lane / gl] = __builtin_bit_cast(uint16_t, sh);
+  }
+}
+
+// T2 -> T0 (and the HBM stop-over of T2 -> T1): binary32 product code*scale, rounded to the KV dtype.
+__global__ __launch_bounds__(256) void k_move_dequant(DevView v) {
+  const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
+  const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int n = v.cnt[b * CNT_N + C_M20] + v.cnt[b * CNT_N + C_M21];
+  if (j >= n) return;
+  const int src = v.mvd_src[(size_t)b * v.Nmax + j], dst = v.mvd_dst[(size_t)b * v.Nmax + j];
+  if (src < 0 || src >= v.cap2 || dst < 0 || dst >= v.capF) return;
+  char* row = (which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, dst);
+  const size_t r2 = t2_row(v, layer, b, kvh, src);
+  const char* codes = (which ? v.c2V : v.c2K) + r2 * v.cb;
+  const char* scales = (which ? v.s2V : v.s2K) + r2 * v.sb;
+  const int ept = v.D / 64;
+  for (int e = 0; e < ept; ++e) {
+    const int d = lane * ept + e;
+    float val;
+    if (v.t2fmt == 0) {
+      val = (float)((const int8_t*)codes)[d] * *(const float*)scales;
+    } else {
+      const uint8_t byte = ((const uint8_t*)codes)[d >> 1];
+      int c = (d & 1) ? (byte >> 4) : (byte & 0xF);
+      c = (c ^ 8) - 8;
+      const _Float16 sh = __builtin_bit_cast(_Float16, ((const uint16_t*)scales)[d >> 5]);
+      val = (float)c * (float)sh;
+    }
+    store_elem(row, d, v.es, val);
+  }
+}
+
+hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st) {
+  const int cpr = v.D * v.es / 16;
+  if (maxd > 0)
+    hipLaunchKernelGGL(k_move_dequant, dim3((maxd + 3) / 4, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+  if (max10 > 0)
+    hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+  if (maxq > 0)
+    hipLaunchKernelGGL(k_move_quant, dim3((maxq + 3) / 4, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+  return hipGetLastError();
+}
+
+// T0 -> T1, device side of the offload: pack rows [r0, r0+nrows) of this migrate's host-row order into a
+// contiguous bounce piece laid out [row][kv head][K|V][D]; the D2H copy then lands them in the pinned store.
+__global__ void k_gather(DevView v, int layer, int r0, int nrows, char* __restrict__ bounce) {
+  const int row_bytes = v.D * v.es, cpr = row_bytes / 16;
+  const long long total = (long long)nrows * v.Hkv * 2 * cpr;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cpr);
+  long long r = i / cpr;
+  const int which = (int)(r & 1); r >>= 1;
+  const int kvh = (int)(r % v.Hkv);
+  const int row = (int)(r / v.Hkv);
+  const int b = v.g_seq[r0 + row], src = v.g_src[r0 + row];
+  if (b < 0 || b >= v.B || src < 0 || src >= v.capF) return;
+  const char* base = which ? v.fpV : v.fpK;
+  *(u32x4*)(bounce + (size_t)i * 16) = *(const u32x4*)(base + fp_row(v, layer, b, kvh, src) + c * 16);
+}
+// staging side of the prefetch: unpack a bounce piece (same layout) into the rows' staging slots
+__global__ void k_scatter(DevView v, int layer, int r0, int nrows, const char* __restrict__ bounce) {
+  const int row_bytes = v.D * v.es, cpr = row_bytes / 16;
+  const long long total = (long long)nrows * v.Hkv * 2 * cpr;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cpr);
+  long long r = i / cpr;
+  const int which = (int)(r & 1); r >>= 1;
+  const int kvh = (int)(r % v.Hkv);
+  const int row = (int)(r / v.Hkv);
+  const int b = v.g_seq[r0 + row], dst = v.g_dst[r0 + row];
+  if (b < 0 || b >= v.B || dst < 0 || dst >= v.capF) return;
+  char* base = which ? v.fpV : v.fpK;
+  *(u32x4*)(base + fp_row(v, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
+}
+hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st) {
+  const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);
+  hipLaunchKernelGGL(k_gather, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, layer, r0, nrows, bounce);
+  return hipGetLastError();
+}
+hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st) {
+  const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);
+  hipLaunchKernelGGL(k_scatter, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, layer, r0, nrows, bounce);
+  return hipGetLastError();
+}
+
+}  // namespace tkv

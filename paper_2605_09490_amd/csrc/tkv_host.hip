@@ -1,0 +1,613 @@
+// Host runtime of libtkv: the C ABI of include/tkv.h.  Owns the pools, the per-sequence state, the pinned T1
+// store, two side streams (offload: gather + D2H; prefetch: H2D + scatter) and the events that order them
+// against attention (Sec. 3.4 of the paper).  All numerical work happens in the kernels; this file only
+// validates, sizes, launches and copies.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/tkv.h"
+#include "tkv_internal.h"
+
+using namespace tkv;
+
+namespace {
+
+constexpr int RING = 4;
+
+struct EvPair { hipEvent_t a, b; int64_t bytes; int dir; };  // dir 0 = D2H, 1 = H2D
+
+}  // namespace
+
+struct tkv_cache {
+  tkv_config cfg{};
+  DevView dv{};
+  std::string err;
+  std::vector<void*> dev_allocs, pin_allocs;
+  int G = 0, es = 0;
+  bool bf16 = false;
+  float score_scale = 0.f, softmax_scale = 0.f;
+  // host mirrors
+  std::vector<int> len;            // tokens appended per layer
+  int n_assigned = 0;              // positions that own a slot
+  std::vector<int> nF, nQ, free0, free1, free2, pend;  // per sequence
+  std::vector<int64_t> ntier;      // [4] summed over sequences
+  bool plan_pending = false;
+  // attention scratch
+  float* xs = nullptr; float* part_ml = nullptr; float* part_o = nullptr;
+  int S_alloc = 0, xs_stride = 0;
+  // T1 store and transport
+  char* hstore = nullptr;
+  int64_t host_rows = 0, host_next = 0;
+  size_t tok_bytes = 0;            // bytes of one position in one layer: Hkv * 2 * D * es
+  hipStream_t sA = nullptr, sB = nullptr;
+  hipEvent_t ev_plan = nullptr, ev_piece[RING] = {};
+  std::vector<hipEvent_t> ev_ready;
+  std::vector<char> layer_wait;
+  char* bounceA = nullptr; char* bounceB = nullptr;
+  size_t bounce_bytes = 0;
+  bool transfers_in_flight = false;
+  int* pin_cnt = nullptr;          // pinned [B][CNT_N]
+  int* pin_base = nullptr;         // pinned [B]
+  int* d_host_base = nullptr;
+  std::vector<EvPair> copy_events; size_t copy_events_used = 0;
+  std::vector<EvPair> prof_events; size_t prof_used = 0;
+  tkv_stats st{};
+};
+
+namespace {
+
+const char* g_static_err = "tkv: NULL handle";
+
+tkv_status fail(tkv_cache* c, tkv_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  return s;
+}
+
+#define HIPCHK(c, call)                                                                         \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail((c), TKV_EDEVICE, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+void* dev_alloc(tkv_cache* c, size_t bytes) {
+  void* p = nullptr;
+  if (bytes == 0) bytes = 256;
+  if (c->cfg.dev_alloc) p = c->cfg.dev_alloc(bytes, c->cfg.alloc_ctx);
+  else if (hipMalloc(&p, bytes) != hipSuccess) p = nullptr;
+  if (p) c->dev_allocs.push_back(p);
+  return p;
+}
+void* pin_alloc(tkv_cache* c, size_t bytes) {
+  void* p = nullptr;
+  if (bytes == 0) bytes = 256;
+  if (c->cfg.pin_alloc) p = c->cfg.pin_alloc(bytes, c->cfg.alloc_ctx);
+  else if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) p = nullptr;
+  if (p) c->pin_allocs.push_back(p);
+  return p;
+}
+
+template <typename T>
+bool dalloc(tkv_cache* c, T*& p, size_t count) {
+  p = (T*)dev_alloc(c, count * sizeof(T));
+  return p != nullptr;
+}
+
+bool policy_ok(const tkv_policy* p) {
+  return p && (uint64_t)p->f_t0_ppm + p->f_t1_ppm + p->f_t2_ppm + p->f_t3_ppm == 1000000ull;
+}
+
+void band_counts_host(const tkv_policy* p, int64_t m, int64_t evicted, int64_t out[4]) {
+  int64_t n3 = ((int64_t)p->f_t3_ppm * m) / 1000000, n2 = ((int64_t)p->f_t2_ppm * m) / 1000000;
+  int64_t n0 = ((int64_t)p->f_t0_ppm * m) / 1000000, n1 = m - n0 - n2 - n3;
+  int64_t extra = evicted - n3;
+  if (extra > 0) {
+    n3 += extra;
+    int64_t t = std::min(extra, n2); n2 -= t; extra -= t;
+    t = std::min(extra, n1); n1 -= t; extra -= t;
+    t = std::min(extra, n0); n0 -= t; extra -= t;
+  }
+  out[0] = n0; out[1] = n1; out[2] = n2; out[3] = n3;
+}
+
+int common_length(const tkv_cache* c) {
+  int n = c->len[0];
+  for (int l = 1; l < c->cfg.n_layers; ++l) if (c->len[l] != n) return -1;
+  return n;
+}
+
+EvPair* next_pair(std::vector<EvPair>& pool, size_t& used) {
+  if (used == pool.size()) {
+    EvPair p{};
+    if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) return nullptr;
+    pool.push_back(p);
+  }
+  return &pool[used++];
+}
+
+// waits for the side streams and folds the copy timings into the stats
+tkv_status drain_transfers(tkv_cache* c) {
+  if (c->transfers_in_flight) {
+    HIPCHK(c, hipStreamSynchronize(c->sA));
+    HIPCHK(c, hipStreamSynchronize(c->sB));
+    c->transfers_in_flight = false;
+  }
+  for (size_t i = 0; i < c->copy_events_used; ++i) {
+    float ms = 0.f;
+    EvPair& p = c->copy_events[i];
+    if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+      if (p.dir == 0) { c->st.d2h_ms += ms; } else { c->st.h2d_ms += ms; }
+    }
+  }
+  c->copy_events_used = 0;
+  std::fill(c->layer_wait.begin(), c->layer_wait.end(), 0);
+  return TKV_OK;
+}
+
+tkv_status harvest_profile(tkv_cache* c) {
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    float ms = 0.f;
+    HIPCHK(c, hipEventSynchronize(c->prof_events[i].b));
+    if (hipEventElapsedTime(&ms, c->prof_events[i].a, c->prof_events[i].b) == hipSuccess) {
+      c->st.attn_kernel_ms += ms;
+      c->st.attn_kernel_launches += 1;
+    }
+  }
+  c->prof_used = 0;
+  return TKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tkv_last_error(const tkv_cache* c) { return c ? c->err.c_str() : g_static_err; }
+
+tkv_status tkv_tier_counts(const tkv_policy* policy, int64_t m, int64_t n_already_evicted, int64_t out[4]) {
+  if (!policy_ok(policy) || !out || m < 0 || n_already_evicted < 0 || n_already_evicted > m) return TKV_EINVAL;
+  band_counts_host(policy, m, n_already_evicted, out);
+  return TKV_OK;
+}
+
+tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) { g_static_err = "tkv_create: NULL argument"; return TKV_EINVAL; }
+  auto bad = [&](const char* m) { g_static_err = m; return TKV_EINVAL; };
+  if (cfg->n_layers < 1 || cfg->batch < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return bad("tkv_create: sizes must be positive");
+  if (cfg->batch * (int64_t)cfg->n_layers > 65535) return bad("tkv_create: n_layers*batch must be <= 65535");
+  if (cfg->n_q_heads % cfg->n_kv_heads) return bad("tkv_create: n_q_heads must be a multiple of n_kv_heads");
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  if (G > MAX_G) return bad("tkv_create: group size n_q_heads/n_kv_heads must be <= 8");
+  if (cfg->n_q_heads > 128) return bad("tkv_create: n_q_heads must be <= 128");
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return bad("tkv_create: head_dim must be 64 or 128");
+  if (cfg->max_tokens < 1 || cfg->max_tokens >= (1 << 24)) return bad("tkv_create: max_tokens must be in [1, 2^24)");
+  if (cfg->kv_dtype != TKV_F32 && cfg->kv_dtype != TKV_BF16) return bad("tkv_create: kv_dtype");
+  if (cfg->out_dtype != TKV_F32 && cfg->out_dtype != TKV_BF16) return bad("tkv_create: out_dtype");
+  if (cfg->t2_format != TKV_T2_INT8_ROW && cfg->t2_format != TKV_T2_INT4_G32) return bad("tkv_create: t2_format");
+  if (cfg->n_prompt < 0 || cfg->k_sink < 0 || cfg->k_window < 0) return bad("tkv_create: protected sizes must be >= 0");
+  if (cfg->t0_rows < 0 || cfg->staging_rows < 0 || cfg->t2_rows < 0 || cfg->host_rows < 0 || cfg->bounce_bytes < 0)
+    return bad("tkv_create: capacities must be >= 0");
+  if (cfg->prefetch_mode != TKV_PREFETCH_WAIT && cfg->prefetch_mode != TKV_PREFETCH_LAZY) return bad("tkv_create: prefetch_mode");
+  if (!(cfg->score_scale >= 0.f) || !(cfg->softmax_scale >= 0.f)) return bad("tkv_create: scales must be >= 0");
+  if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr) || (cfg->pin_alloc == nullptr) != (cfg->pin_free == nullptr))
+    return bad("tkv_create: allocator callbacks must come in alloc/free pairs");
+
+  tkv_cache* c = new tkv_cache();
+  c->cfg = *cfg;
+  c->G = G;
+  c->bf16 = cfg->kv_dtype == TKV_BF16;
+  c->es = c->bf16 ? 2 : 4;
+  c->score_scale = cfg->score_scale > 0.f ? cfg->score_scale : 1.0f / ((float)cfg->n_layers * (float)cfg->n_q_heads);
+  c->softmax_scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+  auto die = [&](tkv_status s, const char* m) {
+    g_static_err = m;
+    tkv_destroy(c);
+    return s;
+  };
+  if (hipSetDevice(cfg->device) != hipSuccess) return die(TKV_EDEVICE, "tkv_create: hipSetDevice failed");
+
+  DevView& v = c->dv;
+  const int L = cfg->n_layers, B = cfg->batch, Hkv = cfg->n_kv_heads, D = cfg->head_dim, N = cfg->max_tokens;
+  v.L = L; v.B = B; v.Hq = cfg->n_q_heads; v.Hkv = Hkv; v.G = G; v.D = D; v.Nmax = N;
+  v.cap0 = cfg->t0_rows ? cfg->t0_rows : N;
+  v.cap1 = cfg->staging_rows ? cfg->staging_rows : N;
+  v.cap2 = cfg->t2_rows ? cfg->t2_rows : N;
+  v.capF = v.cap0 + v.cap1;
+  v.es = c->es;
+  v.t2fmt = cfg->t2_format;
+  v.cb = cfg->t2_format == TKV_T2_INT8_ROW ? D : D / 2;
+  v.sb = cfg->t2_format == TKV_T2_INT8_ROW ? 4 : (D / 32) * 2;
+  v.n_prompt = cfg->n_prompt; v.k_sink = cfg->k_sink; v.k_window = cfg->k_window;
+  if ((int64_t)v.capF * D * c->es >= (1ll << 31) || (int64_t)v.cap2 * v.cb >= (1ll << 31))
+    return die(TKV_EINVAL, "tkv_create: a per-(sequence, kv head) pool must stay below 2 GiB");
+
+  const size_t rows = (size_t)L * B * Hkv;
+  const size_t BN = (size_t)B * N;
+  bool ok = true;
+  ok = ok && dalloc(c, v.fpK, rows * v.capF * D * c->es) && dalloc(c, v.fpV, rows * v.capF * D * c->es);
+  ok = ok && dalloc(c, v.c2K, rows * v.cap2 * v.cb) && dalloc(c, v.c2V, rows * v.cap2 * v.cb);
+  ok = ok && dalloc(c, v.s2K, rows * v.cap2 * v.sb) && dalloc(c, v.s2V, rows * v.cap2 * v.sb);
+  ok = ok && dalloc(c, v.tier, BN) && dalloc(c, v.tier_new, BN) && dalloc(c, v.loc, BN) && dalloc(c, v.hloc, BN);
+  ok = ok && dalloc(c, v.score, BN) && dalloc(c, v.f_pos, BN) && dalloc(c, v.f_loc, BN) && dalloc(c, v.f_loc_old, BN);
+  ok = ok && dalloc(c, v.q_pos, BN) && dalloc(c, v.q_loc, BN) && dalloc(c, v.idx, 4 * BN) && dalloc(c, v.cnt, (size_t)B * CNT_N);
+  ok = ok && dalloc(c, v.free0, (size_t)B * v.cap0) && dalloc(c, v.free1, (size_t)B * v.cap1) && dalloc(c, v.free2, (size_t)B * v.cap2);
+  ok = ok && dalloc(c, v.pend, BN) && dalloc(c, v.rel0, BN) && dalloc(c, v.rel1, BN) && dalloc(c, v.rel2, BN);
+  ok = ok && dalloc(c, v.mv10_src, BN) && dalloc(c, v.mv10_dst, BN) && dalloc(c, v.mvq_src, BN) && dalloc(c, v.mvq_dst, BN);
+  ok = ok && dalloc(c, v.mvd_src, BN) && dalloc(c, v.mvd_dst, BN);
+  ok = ok && dalloc(c, v.g_seq, BN) && dalloc(c, v.g_src, BN) && dalloc(c, v.g_dst, BN);
+  ok = ok && dalloc(c, c->d_host_base, (size_t)B);
+  v.host_base = c->d_host_base;
+  c->S_alloc = N / TOK_PER_BLOCK + 2;
+  c->xs_stride = c->S_alloc * TOK_PER_BLOCK;
+  ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
+  ok = ok && dalloc(c, c->part_ml, (size_t)B * Hkv * c->S_alloc * 2 * G);
+  ok = ok && dalloc(c, c->part_o, (size_t)B * Hkv * c->S_alloc * G * D);
+  c->tok_bytes = (size_t)Hkv * 2 * D * c->es;
+  c->bounce_bytes = cfg->bounce_bytes ? (size_t)cfg->bounce_bytes : ((size_t)64 << 20);
+  if (c->bounce_bytes < RING * c->tok_bytes) c->bounce_bytes = RING * c->tok_bytes;
+  ok = ok && dalloc(c, c->bounceA, c->bounce_bytes) && dalloc(c, c->bounceB, c->bounce_bytes);
+  c->host_rows = cfg->host_rows ? cfg->host_rows : (int64_t)B * N;
+  if (ok) {
+    c->hstore = (char*)pin_alloc(c, (size_t)L * c->host_rows * c->tok_bytes);
+    c->pin_cnt = (int*)pin_alloc(c, (size_t)B * CNT_N * sizeof(int));
+    c->pin_base = (int*)pin_alloc(c, (size_t)B * sizeof(int));
+    ok = c->hstore && c->pin_cnt && c->pin_base;
+  }
+  if (!ok) return die(TKV_ENOMEM, "tkv_create: an allocation failed");
+
+  c->len.assign(L, 0);
+  c->nF.assign(B, 0); c->nQ.assign(B, 0);
+  c->free0.assign(B, v.cap0); c->free1.assign(B, v.cap1); c->free2.assign(B, v.cap2); c->pend.assign(B, 0);
+  c->ntier.assign(4, 0);
+  c->ev_ready.assign(L, nullptr);
+  c->layer_wait.assign(L, 0);
+  // default-priority streams only
+  if (hipStreamCreateWithFlags(&c->sA, hipStreamNonBlocking) != hipSuccess ||
+      hipStreamCreateWithFlags(&c->sB, hipStreamNonBlocking) != hipSuccess)
+    return die(TKV_EDEVICE, "tkv_create: hipStreamCreate failed");
+  bool evok = hipEventCreateWithFlags(&c->ev_plan, hipEventDisableTiming) == hipSuccess;
+  for (int i = 0; i < RING && evok; ++i) evok = hipEventCreateWithFlags(&c->ev_piece[i], hipEventDisableTiming) == hipSuccess;
+  for (int l = 0; l < L && evok; ++l) evok = hipEventCreateWithFlags(&c->ev_ready[l], hipEventDisableTiming) == hipSuccess;
+  if (!evok) return die(TKV_EDEVICE, "tkv_create: hipEventCreate failed");
+  if (launch_init_state(v, nullptr) != hipSuccess || hipStreamSynchronize(nullptr) != hipSuccess)
+    return die(TKV_EDEVICE, "tkv_create: state initialisation failed");
+  *out = c;
+  return TKV_OK;
+}
+
+void tkv_destroy(tkv_cache* c) {
+  if (!c) return;
+  (void)hipDeviceSynchronize();
+  if (c->sA) (void)hipStreamDestroy(c->sA);
+  if (c->sB) (void)hipStreamDestroy(c->sB);
+  if (c->ev_plan) (void)hipEventDestroy(c->ev_plan);
+  for (auto e : c->ev_piece) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_ready) if (e) (void)hipEventDestroy(e);
+  for (auto& p : c->copy_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (auto& p : c->prof_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (void* p : c->dev_allocs) { if (c->cfg.dev_free) c->cfg.dev_free(p, c->cfg.alloc_ctx); else (void)hipFree(p); }
+  for (void* p : c->pin_allocs) { if (c->cfg.pin_free) c->cfg.pin_free(p, c->cfg.alloc_ctx); else (void)hipHostFree(p); }
+  delete c;
+}
+
+int32_t tkv_layer_length(const tkv_cache* c, int32_t layer) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return -1;
+  return c->len[layer];
+}
+
+tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v, int32_t n_new, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers || !k || !v || n_new < 1) return fail(c, TKV_EINVAL, "tkv_append: bad argument");
+  if (c->plan_pending) return fail(c, TKV_ESTATE, "tkv_append: a tier plan is pending; call tkv_migrate first");
+  const int pos0 = c->len[layer];
+  if ((int64_t)pos0 + n_new > c->cfg.max_tokens) return fail(c, TKV_ECAPACITY, "tkv_append: %d + %d exceeds max_tokens %d", pos0, n_new, c->cfg.max_tokens);
+  bool assign = false;
+  if (pos0 + n_new > c->n_assigned) {
+    if (pos0 != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_append: layer %d at length %d would overlap the assigned range %d", layer, pos0, c->n_assigned);
+    for (int b = 0; b < c->cfg.batch; ++b)
+      if (c->free0[b] < n_new) return fail(c, TKV_ECAPACITY, "tkv_append: HBM pool of sequence %d has %d free slots, need %d", b, c->free0[b], n_new);
+    assign = true;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIPCHK(c, launch_append(c->dv, layer, k, v, pos0, n_new, assign, st));
+  if (assign) {
+    for (int b = 0; b < c->cfg.batch; ++b) { c->free0[b] -= n_new; c->nF[b] += n_new; }
+    c->ntier[0] += (int64_t)n_new * c->cfg.batch;
+    c->n_assigned += n_new;
+  }
+  c->len[layer] = pos0 + n_new;
+  return TKV_OK;
+}
+
+tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers || !q || !out) return fail(c, TKV_EINVAL, "tkv_attend_and_score: bad argument");
+  if (c->len[layer] == 0) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d is empty", layer);
+  if (c->len[layer] != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d has %d tokens, %d are assigned; append first", layer, c->len[layer], c->n_assigned);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const DevView& v = c->dv;
+  bool use_old = false;
+  if (c->layer_wait[layer]) {
+    if (c->cfg.prefetch_mode == TKV_PREFETCH_WAIT) {
+      HIPCHK(c, hipStreamWaitEvent(st, c->ev_ready[layer], 0));
+      c->layer_wait[layer] = 0;
+      c->st.attend_waits++;
+    } else {
+      hipError_t e = hipEventQuery(c->ev_ready[layer]);
+      if (e == hipSuccess) c->layer_wait[layer] = 0;
+      else if (e == hipErrorNotReady) { use_old = true; c->st.lazy_old_reads++; }
+      else return fail(c, TKV_EDEVICE, "hipEventQuery failed: %s", hipGetErrorString(e));
+    }
+  }
+  int S = 1;
+  for (int b = 0; b < v.B; ++b)
+    S = std::max(S, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK + (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
+  if (S > c->S_alloc) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal split count %d > %d", S, c->S_alloc);
+  AttnArgs a{};
+  const size_t lrows = (size_t)layer * v.B * v.Hkv;
+  a.fpK = v.fpK + lrows * v.capF * v.D * v.es; a.fpV = v.fpV + lrows * v.capF * v.D * v.es;
+  a.c2K = v.c2K + lrows * v.cap2 * v.cb; a.c2V = v.c2V + lrows * v.cap2 * v.cb;
+  a.s2K = v.s2K + lrows * v.cap2 * v.sb; a.s2V = v.s2V + lrows * v.cap2 * v.sb;
+  a.q = q; a.out = out;
+  a.f_loc = use_old ? v.f_loc_old : v.f_loc; a.f_pos = v.f_pos; a.q_loc = v.q_loc; a.q_pos = v.q_pos;
+  a.cnt = v.cnt; a.score = v.score; a.xs = c->xs; a.part_ml = c->part_ml; a.part_o = c->part_o;
+  a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capF; a.cap2 = v.cap2;
+  a.S = S; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
+  a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
+  EvPair* pe = nullptr;
+  if (c->cfg.profile) {
+    pe = next_pair(c->prof_events, c->prof_used);
+    if (!pe) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+    HIPCHK(c, hipEventRecord(pe->a, st));
+  }
+  HIPCHK(c, launch_attn_split(a, v.D, c->G, c->bf16, st));
+  if (pe) HIPCHK(c, hipEventRecord(pe->b, st));
+  HIPCHK(c, launch_attn_finish(a, v.D, c->G, c->bf16, S, st));
+  return TKV_OK;
+}
+
+tkv_status tkv_classify(tkv_cache* c, const tkv_policy* policy, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (!policy_ok(policy)) return fail(c, TKV_EINVAL, "tkv_classify: policy fractions must sum to 1000000 ppm");
+  const int n = common_length(c);
+  if (n < 0 || n != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_classify: layers differ in length");
+  if (n == 0) return fail(c, TKV_ESTATE, "tkv_classify: cache is empty");
+  const auto t0 = std::chrono::steady_clock::now();
+  hipStream_t st = (hipStream_t)hip_stream;
+  const uint32_t ppm[4] = {policy->f_t0_ppm, policy->f_t1_ppm, policy->f_t2_ppm, policy->f_t3_ppm};
+  HIPCHK(c, launch_classify(c->dv, n, ppm, st));
+  c->plan_pending = true;
+  c->st.n_classify++;
+  c->st.classify_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return TKV_OK;
+}
+
+tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (!c->plan_pending) return fail(c, TKV_ESTATE, "tkv_migrate: no pending plan");
+  const int n = common_length(c);
+  if (n < 0 || n != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_migrate: layers differ in length");
+  const auto t0 = std::chrono::steady_clock::now();
+  hipStream_t st = (hipStream_t)hip_stream;
+  DevView& v = c->dv;
+  const int B = v.B, L = v.L;
+  // the previous migrate's transfers must have landed before its HBM slots are recycled
+  tkv_status s = drain_transfers(c);
+  if (s != TKV_OK) return s;
+  HIPCHK(c, launch_plan_count(v, n, st));
+  HIPCHK(c, hipMemcpyAsync(c->pin_cnt, v.cnt, (size_t)B * CNT_N * sizeof(int), hipMemcpyDeviceToHost, st));
+  HIPCHK(c, hipStreamSynchronize(st));
+  int64_t total_new_t1 = 0;
+  int max10 = 0, maxq = 0, maxd = 0;
+  for (int b = 0; b < B; ++b) {
+    const int* k = c->pin_cnt + b * CNT_N;
+    if (k[C_BAD]) return fail(c, TKV_ESTATE, "tkv_migrate: the plan moves %d position(s) of sequence %d out of T3 or names an invalid tier", k[C_BAD], b);
+    const int e0 = k[C_M10] + k[C_M20] + k[C_M21], e1 = k[C_M01] + k[C_M21], e2 = k[C_M02] + k[C_M12];
+    if (e0 > k[C_FREE0] + k[C_PEND]) return fail(c, TKV_ECAPACITY, "tkv_migrate: HBM pool of sequence %d: %d rows enter, %d slots free", b, e0, k[C_FREE0] + k[C_PEND]);
+    if (e1 > k[C_FREE1]) return fail(c, TKV_ECAPACITY, "tkv_migrate: staging buffer of sequence %d: %d rows enter, %d slots free", b, e1, k[C_FREE1]);
+    if (e2 > k[C_FREE2]) return fail(c, TKV_ECAPACITY, "tkv_migrate: compressed pool of sequence %d: %d rows enter, %d slots free", b, e2, k[C_FREE2]);
+    c->pin_base[b] = (int)(c->host_next + total_new_t1);
+    total_new_t1 += e1;
+    max10 = std::max(max10, k[C_M10]); maxq = std::max(maxq, e2); maxd = std::max(maxd, k[C_M20] + k[C_M21]);
+  }
+  if (c->host_next + total_new_t1 > c->host_rows)
+    return fail(c, TKV_ECAPACITY, "tkv_migrate: pinned T1 store: %lld rows enter, %lld of %lld left",
+                (long long)total_new_t1, (long long)(c->host_rows - c->host_next), (long long)c->host_rows);
+  HIPCHK(c, hipMemcpyAsync(c->d_host_base, c->pin_base, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
+  v.event_base = (int)c->host_next;
+  HIPCHK(c, launch_plan_commit(v, n, st));
+  HIPCHK(c, launch_moves(v, max10, maxq, maxd, st));
+  // host mirrors of what plan_commit leaves on the device
+  for (int t = 0; t < 4; ++t) c->ntier[t] = 0;
+  for (int b = 0; b < B; ++b) {
+    const int* k = c->pin_cnt + b * CNT_N;
+    c->nF[b] = k[C_P0] + k[C_P1]; c->nQ[b] = k[C_P2];
+    for (int t = 0; t < 4; ++t) c->ntier[t] += k[C_P0 + t];
+    const int e0 = k[C_M10] + k[C_M20] + k[C_M21], e1 = k[C_M01] + k[C_M21], e2 = k[C_M02] + k[C_M12];
+    c->free0[b] = k[C_FREE0] + k[C_PEND] - e0 + k[C_M02] + k[C_M03];
+    c->pend[b] = e1;
+    c->free1[b] = k[C_FREE1] - e1 + k[C_M10] + k[C_M12] + k[C_M13];
+    c->free2[b] = k[C_FREE2] - e2 + k[C_M20] + k[C_M21] + k[C_M23];
+  }
+  if (total_new_t1 > 0) {
+    // offload stream: gather -> D2H into the pinned store; prefetch stream: H2D -> scatter into the staging slots
+    HIPCHK(c, hipEventRecord(c->ev_plan, st));
+    HIPCHK(c, hipStreamWaitEvent(c->sA, c->ev_plan, 0));
+    HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_plan, 0));
+    const size_t slot_bytes = c->bounce_bytes / RING;
+    const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
+    int piece = 0;
+    for (int l = 0; l < L; ++l) {
+      for (int64_t r0 = 0; r0 < total_new_t1; r0 += piece_rows, ++piece) {
+        const int nrows = (int)std::min<int64_t>(piece_rows, total_new_t1 - r0);
+        const size_t bytes = (size_t)nrows * c->tok_bytes;
+        char* ba = c->bounceA + (size_t)(piece % RING) * slot_bytes;
+        char* bb = c->bounceB + (size_t)(piece % RING) * slot_bytes;
+        char* hp = c->hstore + ((size_t)l * c->host_rows + (size_t)(c->host_next + r0)) * c->tok_bytes;
+        if (!next_pair(c->copy_events, c->copy_events_used) || !next_pair(c->copy_events, c->copy_events_used))
+          return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+        EvPair* ea = &c->copy_events[c->copy_events_used - 2];
+        EvPair* eb = &c->copy_events[c->copy_events_used - 1];
+        ea->dir = 0; eb->dir = 1; ea->bytes = eb->bytes = (int64_t)bytes;
+        HIPCHK(c, launch_gather(v, l, (int)r0, nrows, ba, c->sA));
+        HIPCHK(c, hipEventRecord(ea->a, c->sA));
+        HIPCHK(c, hipMemcpyAsync(hp, ba, bytes, hipMemcpyDeviceToHost, c->sA));
+        HIPCHK(c, hipEventRecord(ea->b, c->sA));
+        HIPCHK(c, hipEventRecord(c->ev_piece[piece % RING], c->sA));
+        HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_piece[piece % RING], 0));
+        HIPCHK(c, hipEventRecord(eb->a, c->sB));
+        HIPCHK(c, hipMemcpyAsync(bb, hp, bytes, hipMemcpyHostToDevice, c->sB));
+        HIPCHK(c, hipEventRecord(eb->b, c->sB));
+        HIPCHK(c, launch_scatter(v, l, (int)r0, nrows, bb, c->sB));
+        c->st.d2h_bytes += (int64_t)bytes; c->st.h2d_bytes += (int64_t)bytes;
+        c->st.d2h_copies++; c->st.h2d_copies++;
+      }
+      HIPCHK(c, hipEventRecord(c->ev_ready[l], c->sB));
+      c->layer_wait[l] = 1;
+    }
+    c->transfers_in_flight = true;
+    c->host_next += total_new_t1;
+  }
+  c->plan_pending = false;
+  c->st.n_migrate++;
+  c->st.migrate_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return TKV_OK;
+}
+
+tkv_status tkv_wait_prefetch(tkv_cache* c) {
+  if (!c) return TKV_EINVAL;
+  return drain_transfers(c);
+}
+
+// ---- inspection -------------------------------------------------------------------------------------------
+static tkv_status sync_all(tkv_cache* c) {
+  HIPCHK(c, hipDeviceSynchronize());
+  return TKV_OK;
+}
+
+tkv_status tkv_get_scores(tkv_cache* c, float* host_out) {
+  if (!c || !host_out) return c ? fail(c, TKV_EINVAL, "tkv_get_scores: NULL") : TKV_EINVAL;
+  tkv_status s = sync_all(c); if (s) return s;
+  HIPCHK(c, hipMemcpy(host_out, c->dv.score, (size_t)c->dv.B * c->dv.Nmax * sizeof(float), hipMemcpyDeviceToHost));
+  return TKV_OK;
+}
+tkv_status tkv_set_scores(tkv_cache* c, const float* host_in) {
+  if (!c || !host_in) return c ? fail(c, TKV_EINVAL, "tkv_set_scores: NULL") : TKV_EINVAL;
+  const size_t n = (size_t)c->dv.B * c->dv.Nmax;
+  for (size_t i = 0; i < n; ++i) if (!(host_in[i] >= 0.f) || std::signbit(host_in[i])) return fail(c, TKV_EINVAL, "tkv_set_scores: scores must be >= +0");
+  tkv_status s = sync_all(c); if (s) return s;
+  HIPCHK(c, hipMemcpy(c->dv.score, host_in, n * sizeof(float), hipMemcpyHostToDevice));
+  return TKV_OK;
+}
+tkv_status tkv_get_tiers(tkv_cache* c, uint8_t* host_out) {
+  if (!c || !host_out) return c ? fail(c, TKV_EINVAL, "tkv_get_tiers: NULL") : TKV_EINVAL;
+  tkv_status s = sync_all(c); if (s) return s;
+  HIPCHK(c, hipMemcpy(host_out, c->dv.tier, (size_t)c->dv.B * c->dv.Nmax, hipMemcpyDeviceToHost));
+  return TKV_OK;
+}
+tkv_status tkv_get_pending_tiers(tkv_cache* c, uint8_t* host_out) {
+  if (!c || !host_out) return c ? fail(c, TKV_EINVAL, "tkv_get_pending_tiers: NULL") : TKV_EINVAL;
+  if (!c->plan_pending) return fail(c, TKV_ESTATE, "tkv_get_pending_tiers: no pending plan");
+  tkv_status s = sync_all(c); if (s) return s;
+  HIPCHK(c, hipMemcpy(host_out, c->dv.tier_new, (size_t)c->dv.B * c->dv.Nmax, hipMemcpyDeviceToHost));
+  return TKV_OK;
+}
+tkv_status tkv_set_tiers(tkv_cache* c, const uint8_t* host_in) {
+  if (!c || !host_in) return c ? fail(c, TKV_EINVAL, "tkv_set_tiers: NULL") : TKV_EINVAL;
+  const int n = common_length(c);
+  if (n < 0 || n != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_set_tiers: layers differ in length");
+  for (int b = 0; b < c->dv.B; ++b)
+    for (int i = 0; i < n; ++i)
+      if (host_in[(size_t)b * c->dv.Nmax + i] > 3) return fail(c, TKV_EINVAL, "tkv_set_tiers: tier > 3 at (%d, %d)", b, i);
+  tkv_status s = sync_all(c); if (s) return s;
+  HIPCHK(c, hipMemcpy(c->dv.tier_new, host_in, (size_t)c->dv.B * c->dv.Nmax, hipMemcpyHostToDevice));
+  c->plan_pending = true;
+  return TKV_OK;
+}
+tkv_status tkv_get_index_list(tkv_cache* c, int32_t tier, int32_t seq, int32_t* host_out, int32_t* count) {
+  if (!c || !host_out || !count) return c ? fail(c, TKV_EINVAL, "tkv_get_index_list: NULL") : TKV_EINVAL;
+  if (tier < 0 || tier > 3 || seq < 0 || seq >= c->dv.B) return fail(c, TKV_EINVAL, "tkv_get_index_list: bad tier or sequence");
+  tkv_status s = sync_all(c); if (s) return s;
+  int n = 0;
+  HIPCHK(c, hipMemcpy(&n, c->dv.cnt + seq * CNT_N + C_N0 + tier, sizeof(int), hipMemcpyDeviceToHost));
+  if (n < 0 || n > c->dv.Nmax) return fail(c, TKV_EDEVICE, "tkv_get_index_list: corrupt count %d", n);
+  if (n) HIPCHK(c, hipMemcpy(host_out, c->dv.idx + ((size_t)tier * c->dv.B + seq) * c->dv.Nmax, (size_t)n * sizeof(int), hipMemcpyDeviceToHost));
+  *count = n;
+  return TKV_OK;
+}
+
+static tkv_status row_lookup(tkv_cache* c, const char* who, int32_t layer, int32_t seq, int32_t kvh, int32_t pos, int32_t which,
+                             int* tier, int* loc, int* hloc) {
+  const DevView& v = c->dv;
+  if (layer < 0 || layer >= v.L || seq < 0 || seq >= v.B || kvh < 0 || kvh >= v.Hkv || pos < 0 || pos >= c->len[layer] ||
+      pos >= c->n_assigned || which < 0 || which > 1)
+    return fail(c, TKV_EINVAL, "%s: bad index", who);
+  tkv_status s = sync_all(c); if (s) return s;
+  uint8_t t8 = 0;
+  const size_t o = (size_t)seq * v.Nmax + pos;
+  HIPCHK(c, hipMemcpy(&t8, v.tier + o, 1, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(loc, v.loc + o, sizeof(int), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(hloc, v.hloc + o, sizeof(int), hipMemcpyDeviceToHost));
+  *tier = t8;
+  return TKV_OK;
+}
+
+tkv_status tkv_get_t2_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head, int32_t pos, int32_t which,
+                          void* host_codes, void* host_scales) {
+  if (!c || !host_codes || !host_scales) return c ? fail(c, TKV_EINVAL, "tkv_get_t2_row: NULL") : TKV_EINVAL;
+  int tier, loc, hloc;
+  tkv_status s = row_lookup(c, "tkv_get_t2_row", layer, seq, kv_head, pos, which, &tier, &loc, &hloc);
+  if (s) return s;
+  const DevView& v = c->dv;
+  if (tier != 2 || loc < 0 || loc >= v.cap2) return fail(c, TKV_ESTATE, "tkv_get_t2_row: position %d is in tier %d", pos, tier);
+  const size_t r = (((size_t)layer * v.B + seq) * v.Hkv + kv_head) * v.cap2 + loc;
+  HIPCHK(c, hipMemcpy(host_codes, (which ? v.c2V : v.c2K) + r * v.cb, v.cb, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(host_scales, (which ? v.s2V : v.s2K) + r * v.sb, v.sb, hipMemcpyDeviceToHost));
+  return TKV_OK;
+}
+
+tkv_status tkv_get_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head, int32_t pos, int32_t which, void* host_out) {
+  if (!c || !host_out) return c ? fail(c, TKV_EINVAL, "tkv_get_row: NULL") : TKV_EINVAL;
+  int tier, loc, hloc;
+  tkv_status s = row_lookup(c, "tkv_get_row", layer, seq, kv_head, pos, which, &tier, &loc, &hloc);
+  if (s) return s;
+  const DevView& v = c->dv;
+  const size_t rb = (size_t)v.D * v.es;
+  if (tier == 0) {
+    if (loc < 0 || loc >= v.capF) return fail(c, TKV_EDEVICE, "tkv_get_row: corrupt slot %d", loc);
+    const size_t off = ((((size_t)layer * v.B + seq) * v.Hkv + kv_head) * v.capF + loc) * rb;
+    HIPCHK(c, hipMemcpy(host_out, (which ? v.fpV : v.fpK) + off, rb, hipMemcpyDeviceToHost));
+    return TKV_OK;
+  }
+  if (tier == 1) {
+    s = drain_transfers(c); if (s) return s;
+    if (hloc < 0 || hloc >= c->host_rows) return fail(c, TKV_EDEVICE, "tkv_get_row: corrupt host row %d", hloc);
+    const char* p = c->hstore + ((size_t)layer * c->host_rows + hloc) * c->tok_bytes + ((size_t)kv_head * 2 + which) * rb;
+    memcpy(host_out, p, rb);
+    return TKV_OK;
+  }
+  return fail(c, TKV_ESTATE, "tkv_get_row: position %d is in tier %d", pos, tier);
+}
+
+tkv_status tkv_get_stats(tkv_cache* c, tkv_stats* out) {
+  if (!c || !out) return c ? fail(c, TKV_EINVAL, "tkv_get_stats: NULL") : TKV_EINVAL;
+  tkv_status s = harvest_profile(c); if (s) return s;
+  for (int t = 0; t < 4; ++t) c->st.tier_count[t] = c->ntier[t];
+  *out = c->st;
+  return TKV_OK;
+}
+
+}  // extern "C"

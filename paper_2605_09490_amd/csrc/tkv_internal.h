@@ -1,0 +1,92 @@
+// Internal declarations shared by the host runtime and the gfx950 kernels of libtkv.
+// Nothing here is part of the public ABI (see include/tkv.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tkv {
+
+// ---- per-sequence counters kept on the device: cnt[b * CNT_N + k] -------------------------------
+enum Cnt : int {
+  C_NF = 0,      // entries of the full-precision list F = T0 u T1, ascending position
+  C_NQ,          // entries of the compressed list Q = T2, ascending position
+  C_N0, C_N1, C_N2, C_N3,   // positions per tier
+  C_FREE0, C_FREE1, C_FREE2, // free slots on the stacks of the HBM pool, the staging buffer, the T2 pool
+  C_PEND,        // HBM slots of rows that went T0->T1 at the last migrate; released at the next one
+  // plan counts (written by plan_count, read by the host and by plan_commit)
+  C_M01, C_M02, C_M03, C_M10, C_M12, C_M13, C_M20, C_M21, C_M23,
+  C_BAD,         // positions that would leave T3 (invalid plan)
+  C_LEN,         // positions assigned so far
+  C_P0, C_P1, C_P2, C_P3,   // planned positions per tier (plan_count)
+  CNT_N = 28
+};
+
+constexpr int TOK_PER_BLOCK = 256;  // list entries one attention block owns (split granularity)
+constexpr int ATTN_THREADS = 256;
+constexpr int PLAN_THREADS = 1024;
+constexpr int MAX_G = 8;
+
+// Device view of one cache, passed by value to the tier-management kernels.
+struct DevView {
+  int L, B, Hq, Hkv, G, D;
+  int Nmax;                 // max_tokens
+  int cap0, cap1, cap2;     // slots per (layer, seq, kv head): HBM pool, staging buffer, compressed pool
+  int capF;                 // cap0 + cap1: one slot space, staging slots are cap0 .. capF-1
+  int es;                   // bytes per K/V element
+  int t2fmt;                // 0 int8 row, 1 int4 g32
+  int cb, sb;               // bytes of codes / of scales per T2 row
+  int n_prompt, k_sink, k_window;
+  char* fpK; char* fpV;     // [L][B][Hkv][capF][D*es]
+  char* c2K; char* c2V;     // [L][B][Hkv][cap2][cb]
+  char* s2K; char* s2V;     // [L][B][Hkv][cap2][sb]
+  uint8_t* tier;            // [B][Nmax] current
+  uint8_t* tier_new;        // [B][Nmax] pending
+  int* loc;                 // [B][Nmax] slot in the pool of the position's tier (T0/T1: unified F slot; T2: T2 slot; T3: -1)
+  int* hloc;                // [B][Nmax] row in the pinned host store (T1 only), else -1
+  float* score;             // [B][Nmax]
+  int* f_pos; int* f_loc;   // [B][Nmax] list F: position, slot
+  int* f_loc_old;           // [B][Nmax] list F with the pre-offload slot of rows whose staged copy is still in flight
+  int* q_pos; int* q_loc;   // [B][Nmax] list Q
+  int* idx;                 // [4][B][Nmax] per-tier ascending position lists
+  int* cnt;                 // [B][CNT_N]
+  int* free0; int* free1; int* free2;  // [B][cap] stacks of free slots (free0/free1 hold unified F slots)
+  int* pend;                // [B][Nmax]
+  int* rel0; int* rel1; int* rel2;     // [B][Nmax] scratch: slots released by the plan being committed
+  // move lists written by plan_commit (per sequence, [B][Nmax] each, counts in cnt)
+  int* mv10_src; int* mv10_dst;    // staging slot -> HBM slot
+  int* mvq_src; int* mvq_dst;      // F slot -> T2 slot (encode)
+  int* mvd_src; int* mvd_dst;      // T2 slot -> HBM slot (decode)
+  // rows going to the host store at this migrate, global order = host row order
+  int* g_seq; int* g_src; int* g_dst;   // [host_rows_per_event]: sequence, HBM slot to read, staging slot to fill
+  const int* host_base;     // [B] first host row of the sequence's rows at this migrate
+  int event_base;           // first host row of this migrate
+};
+
+struct AttnArgs {
+  const char* fpK; const char* fpV;   // layer bases
+  const char* c2K; const char* c2V; const char* s2K; const char* s2V;
+  const void* q; void* out;
+  const int* f_loc; const int* f_pos; const int* q_loc; const int* q_pos;
+  const int* cnt;
+  float* score;
+  float* xs;        // [B][Hkv][G][xs_stride] scaled logits by list index (F entries, then Q entries from f_pad)
+  float* part_ml;   // [B][Hkv][S][2][G]  (m, l) of each split
+  float* part_o;    // [B][Hkv][S][G][D]
+  int B, Hq, Hkv, Nmax, capF, cap2, S, xs_stride, cb, sb, t2fmt, out_bf16;
+  float softmax_scale, score_scale;
+};
+
+// launchers (defined in the .hip files)
+hipError_t launch_attn_split(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st);
+hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, bool bf16, int n_tiles, hipStream_t st);
+hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
+                         bool assign, hipStream_t st);
+hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStream_t st);
+hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st);
+hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st);
+hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st);
+hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st);
+hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st);
+hipError_t launch_init_state(const DevView& v, hipStream_t st);
+
+}  // namespace tkv

@@ -1,0 +1,77 @@
+"""Helpers for the GPU parity tests: run the HIP path (through the C ABI) and the CPU oracle side by side
+on the same seeded synthetic inputs, and the tolerance definitions."""
+import numpy as np
+import torch
+
+import paper_2605_09490_amd as tkv
+from oracle import tkv_oracle as O
+from tkv_synth import Workload
+
+TOL_OUT = {"bf16": 2e-3, "f32": 1e-5}
+TOL_SCORE_REL = 1e-4
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class Pair:
+    """One GPU cache and one oracle cache fed with identical stored values."""
+
+    def __init__(self, cfg, prefetch_mode="wait", preload=True, **gpu_kw):
+        self.cfg = cfg
+        self.wl = Workload(cfg, device="cuda")
+        self.score_scale = cfg.score_scale if cfg.score_scale is not None else 1.0 / (cfg.n_layers * cfg.n_q_heads)
+        self.gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
+                                kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt,
+                                k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale,
+                                prefetch_mode=prefetch_mode, **gpu_kw)
+        self.orc = O.OracleCache(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
+                                 kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt,
+                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale)
+        self.steps_done = 0
+        if preload:
+            for l in range(cfg.n_layers):
+                k, v = self.wl.context_kv(l)
+                self.append(l, k, v)
+
+    def append(self, layer, k, v):
+        self.gpu.append(layer, k, v)
+        self.orc.append(layer, to_f64(k), to_f64(v))
+
+    def attend(self, layer, q):
+        out = self.gpu.attend_and_score(layer, q)
+        ref = self.orc.attend_and_score(layer, to_f64(q))
+        return to_f64(out), ref
+
+    def force_tiers(self, tiers):
+        self.gpu.set_tiers(tiers)
+        self.gpu.migrate()
+        self.orc.set_tiers(tiers)
+        self.orc.migrate()
+
+    def close(self):
+        self.gpu.close()
+
+
+def assert_out_close(got, ref, kv_dtype, what="", out_dtype="f32"):
+    """max |o_gpu - o_ref| <= tol * max-norm of the head's reference vector; a bf16 *output* adds its own
+    round-to-nearest step (half a bf16 ulp, 2^-8 of the element)."""
+    tol = TOL_OUT[kv_dtype]
+    scale = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1e-6)
+    bound = tol * scale + (2.0 ** -8 * np.abs(ref) if out_dtype == "bf16" else 0.0)
+    err = np.abs(got - ref)
+    worst = (err / scale).max()
+    assert np.all(err <= bound), f"{what}: attention output off by {worst:.3e} of the head max-norm (tol {tol})"
+    return worst
+
+
+def assert_scores_close(got32, ref64, n, total_mass, what=""):
+    """|s_gpu - s_ref| <= 1e-4 * s_ref + 1e-9 * (total mass added so far) / n  (the floor only guards
+    weights that underflowed)."""
+    got = got32[:, :n].astype(np.float64)
+    ref = ref64[:, :n]
+    bound = TOL_SCORE_REL * ref + 1e-9 * total_mass / max(n, 1)
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), (f"{what}: {bad.sum()} scores off, worst rel "
+                           f"{(np.abs(got - ref) / np.maximum(ref, 1e-300)).max():.3e}")

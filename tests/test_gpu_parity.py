@@ -1,0 +1,288 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same seeded inputs.
+Tolerances: attention output 2e-3 (bf16 KV) / 1e-5 (fp32 KV) of each head vector's max-norm; cumulative scores
+1e-4 relative; tier assignment, compaction, T2 codes and moved row bits exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tkv_oracle as O
+from tkv_synth import CONFIGS, small_config
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(cfg, **kw):
+    from gpu_common import Pair
+    print(f"[case] {cfg.name} L={cfg.n_layers} B={cfg.batch} Hq={cfg.n_q_heads} Hkv={cfg.n_kv_heads} D={cfg.head_dim} "
+          f"{cfg.kv_dtype} ctx={cfg.context} {kw}", flush=True)
+    return Pair(cfg, **kw)
+
+
+def _mass(cfg, calls):
+    ss = cfg.score_scale if cfg.score_scale is not None else 1.0 / (cfg.n_layers * cfg.n_q_heads)
+    return calls * cfg.n_q_heads * ss
+
+
+@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,ctx", [
+    ("f32", 64, 8, 2, 512),      # group 4, the tiny config's shape
+    ("f32", 128, 4, 4, 130),     # group 1, ragged
+    ("bf16", 128, 10, 2, 700),   # group 5 (14B/32B shape), several splits + tail
+    ("bf16", 128, 14, 2, 257),   # group 7 (7B shape), one entry past a split boundary
+    ("bf16", 64, 16, 2, 256),    # group 8, exactly one split
+    ("bf16", 128, 6, 2, 1),      # single token
+    ("bf16", 64, 6, 3, 255),     # group 2
+])
+def test_all_t0_attention_and_scores(kv_dtype, D, Hq, Hkv, ctx):
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=2, batch=3, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+                       context=ctx, decode_steps=3, sigma=1.0)
+    p = _pair(cfg)
+    calls = 0
+    for step in range(cfg.decode_steps):
+        for l in range(cfg.n_layers):
+            k, v = p.wl.step_kv(step, l)
+            p.append(l, k, v)
+            got, ref = p.attend(l, p.wl.step_q(step, l))
+            calls += 1
+            assert_out_close(got, ref, kv_dtype, f"step {step} layer {l}")
+    n = ctx + cfg.decode_steps
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _mass(cfg, calls))
+    # closed form: every layer call adds Hq * score_scale to each sequence's total
+    assert np.allclose(p.gpu.get_scores()[:, :n].astype(np.float64).sum(1), _mass(cfg, calls), rtol=1e-4)
+    p.close()
+
+
+def test_bf16_output_rounding():
+    """out_dtype = bf16 adds exactly one round-to-nearest-even of the binary32 result."""
+    from gpu_common import Pair, to_f64
+    cfg = small_config(n_layers=1, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=333,
+                       decode_steps=0)
+    a, b = Pair(cfg), Pair(cfg, out_dtype="bf16")
+    q = a.wl.step_q(0, 0)
+    o32 = a.gpu.attend_and_score(0, q)
+    o16 = b.gpu.attend_and_score(0, q)
+    assert o16.dtype == torch.bfloat16
+    assert torch.equal(o32.to(torch.bfloat16), o16)
+    a.close(); b.close()
+
+
+def _random_tiers(rng, B, n, frac=(0.4, 0.3, 0.2, 0.1), protect=(4, 16)):
+    t = rng.choice(4, size=(B, n), p=frac).astype(np.uint8)
+    t[:, :protect[0]] = 0
+    t[:, n - protect[1]:] = 0
+    return t
+
+
+@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,t2", [
+    ("f32", 64, 8, 2, "int8_row"),
+    ("bf16", 128, 10, 2, "int8_row"),
+    ("bf16", 128, 14, 2, "int4_g32"),
+    ("bf16", 64, 8, 2, "int4_g32"),
+    ("f32", 128, 8, 2, "int4_g32"),
+])
+@pytest.mark.parametrize("mode", ["wait", "lazy"])
+def test_forced_tiers_attention_codes_and_lists(kv_dtype, D, Hq, Hkv, t2, mode):
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+                       context=600, decode_steps=4, t2_format=t2, sigma=1.0)
+    p = _pair(cfg, prefetch_mode=mode)
+    rng = np.random.default_rng(5)
+    n = cfg.context
+    tiers = _random_tiers(rng, cfg.batch, n)
+    p.force_tiers(tiers)
+    assert np.array_equal(p.gpu.get_tiers()[:, :n], tiers)
+    # compaction: per tier the ascending positions
+    for b in range(cfg.batch):
+        for t in range(4):
+            assert np.array_equal(p.gpu.get_index_list(t, b), np.nonzero(tiers[b] == t)[0])
+    # T2 codes and scales are bit-exact against the binary32 definition
+    for (b, pos) in [(0, int(np.nonzero(tiers[0] == 2)[0][0])), (1, int(np.nonzero(tiers[1] == 2)[0][-1]))]:
+        for l in range(cfg.n_layers):
+            for which in (0, 1):
+                for kvh in range(Hkv):
+                    codes, scales = p.gpu.get_t2_row(l, b, kvh, pos, which)
+                    oc = p.orc.t2[l][(b, pos)]
+                    ref_codes, ref_scale = oc[2 * which][kvh], oc[2 * which + 1][kvh]
+                    if t2 == "int8_row":
+                        assert np.array_equal(codes, ref_codes) and scales[0] == ref_scale
+                    else:
+                        assert np.array_equal(codes, O.pack_int4(ref_codes))
+                        assert np.array_equal(scales.view(np.float16).astype(np.float32), ref_scale)
+    # a T1 row reads back from the pinned host store with the bits it was appended with
+    b, pos = 0, int(np.nonzero(tiers[0] == 1)[0][3])
+    k_ctx, v_ctx = p.wl.context_kv(1)
+    row = p.gpu.get_row(1, b, 1, pos, 0)
+    want = k_ctx[b, pos, 1].cpu()
+    want = want.numpy() if kv_dtype == "f32" else want.view(torch.uint16).numpy()
+    assert np.array_equal(row, want)
+    calls = 0
+    for step in range(cfg.decode_steps):
+        for l in range(cfg.n_layers):
+            k, v = p.wl.step_kv(step, l)
+            p.append(l, k, v)
+            got, ref = p.attend(l, p.wl.step_q(step, l))
+            calls += 1
+            assert_out_close(got, ref, kv_dtype, f"step {step} layer {l}")
+    nn = n + cfg.decode_steps
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, nn, _mass(cfg, calls))
+    s = p.gpu.get_scores()
+    assert np.all(s[:, :n][tiers == 3] == 0.0)
+    # second plan: promotions out of T2 (lossy value kept), T1 -> T0, T1 -> T2, more evictions
+    tiers2 = np.zeros((cfg.batch, nn), np.uint8)
+    tiers2[:, :n] = tiers
+    move = rng.random((cfg.batch, n)) < 0.5
+    newt = _random_tiers(rng, cfg.batch, n, frac=(0.35, 0.35, 0.2, 0.1))
+    tiers2[:, :n] = np.where((tiers != 3) & move, newt, tiers)
+    p.force_tiers(tiers2)
+    assert np.array_equal(p.gpu.get_tiers()[:, :nn], tiers2)
+    for b in range(cfg.batch):
+        for t in range(4):
+            assert np.array_equal(p.gpu.get_index_list(t, b), np.nonzero(tiers2[b] == t)[0])
+    for step in range(cfg.decode_steps, cfg.decode_steps + 2):
+        for l in range(cfg.n_layers):
+            got, ref = p.attend(l, p.wl.step_q(step, l))
+            calls += 1
+            assert_out_close(got, ref, kv_dtype, f"after 2nd plan, step {step} layer {l}")
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, nn, _mass(cfg, calls))
+    st = p.gpu.get_stats()
+    assert st["d2h_bytes"] == st["h2d_bytes"] > 0
+    p.close()
+
+
+@pytest.mark.parametrize("mode", ["wait", "lazy"])
+@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv", [("bf16", 128, 10, 2), ("f32", 64, 8, 2)])
+def test_prop1_t1_placement_is_bit_invisible(mode, kv_dtype, D, Hq, Hkv):
+    """Zero-error offloading: the run with rows in T1 (round trip through pinned host memory and the
+    staging buffer) gives the same bits as the run with those rows left in T0 -- outputs and scores."""
+    from gpu_common import Pair
+    cfg = small_config(n_layers=3, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+                       context=900, decode_steps=6, sigma=1.2)
+    rng = np.random.default_rng(9)
+    n = cfg.context
+    tiers = _random_tiers(rng, cfg.batch, n, frac=(0.3, 0.5, 0.15, 0.05))
+    twin = np.where(tiers == 1, 0, tiers).astype(np.uint8)
+    outs = []
+    for tt in (tiers, twin):
+        print(f"[case] prop1 {mode} {kv_dtype} t1_rows={(tt == 1).sum()}", flush=True)
+        p = Pair(cfg, prefetch_mode=mode)
+        p.gpu.set_tiers(tt)
+        p.gpu.migrate()
+        res = []
+        for step in range(cfg.decode_steps):
+            for l in range(cfg.n_layers):
+                k, v = p.wl.step_kv(step, l)
+                p.gpu.append(l, k, v)
+                res.append(p.gpu.attend_and_score(l, p.wl.step_q(step, l)).cpu())
+        outs.append((torch.stack(res), p.gpu.get_scores().copy()))
+        p.close()
+    assert torch.equal(outs[0][0].view(torch.uint8), outs[1][0].view(torch.uint8))
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_classify_bit_exact_given_scores(seed):
+    """Tier assignment is an integer function of the binary32 score array: the GPU's radix select must
+    reproduce the oracle's explicit sort, ties and already-evicted positions included."""
+    from gpu_common import Pair
+    rng = np.random.default_rng(seed)
+    ctx = int(rng.integers(300, 2500))
+    cfg = small_config(n_layers=1, batch=4, n_q_heads=4, n_kv_heads=2, head_dim=64, kv_dtype="bf16", context=ctx,
+                       decode_steps=0, k_sink=int(rng.integers(0, 6)), k_window=int(rng.integers(0, 200)),
+                       n_prompt=int(rng.integers(0, 50)))
+    p = _pair(cfg)
+    n = ctx
+    s = (rng.random((cfg.batch, cfg.max_tokens)) ** 6).astype(np.float32)
+    s[1] = rng.choice(np.array([0, 1e-3, 0.5, 0.5000001, 2.0], np.float32), size=cfg.max_tokens)   # heavy ties
+    s[2, : n // 2] = 0.0
+    p.gpu.set_scores(s)
+    pols = [(300000, 520000, 150000, 30000), (500000, 300000, 150000, 50000), (100000, 100000, 100000, 700000),
+            (0, 0, 0, 1000000)]
+    tier_prev = np.zeros((cfg.batch, n), np.uint8)
+    for pol in pols[: 3 if seed % 2 else 4]:
+        p.gpu.classify(pol)
+        got = p.gpu.get_pending_tiers()[:, :n]
+        for b in range(cfg.batch):
+            want = O.classify_sequence(s[b], tier_prev[b], n, cfg.n_prompt, cfg.k_sink, cfg.k_window, pol)
+            assert np.array_equal(got[b], want), f"seq {b} policy {pol}: {(got[b] != want).sum()} positions differ"
+        p.gpu.migrate()
+        tier_prev = p.gpu.get_tiers()[:, :n].copy()
+        assert np.array_equal(tier_prev, got)
+        for b in range(cfg.batch):
+            lists = O.compact_lists(tier_prev[b], n)
+            for t in range(4):
+                assert np.array_equal(p.gpu.get_index_list(t, b), lists[t])
+    p.close()
+
+
+def test_tiny_config_teacher_forced():
+    """BASELINE config 0: 1 layer, 8/2 heads, d 64, fp32, 512-token context, 32 steps, re-tiering every 8 steps
+    (plus once before the first step).  At each event the oracle's ranking of the GPU's score array must equal
+    the GPU's plan bit for bit; the oracle then adopts that plan (teacher forcing)."""
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = CONFIGS["tiny"]
+    p = _pair(cfg)
+    calls = 0
+
+    def retier():
+        n = p.gpu.layer_length(0)
+        p.gpu.classify(cfg.policy_ppm)
+        plan = p.gpu.get_pending_tiers()[:, :n]
+        s_gpu = p.gpu.get_scores()
+        want = p.orc.classify(cfg.policy_ppm, score_f32=s_gpu)[:, :n]
+        assert np.array_equal(plan, want)
+        free = p.orc.classify(cfg.policy_ppm)[:, :n]
+        print(f"[tiny] n={n} free-running oracle differs from the GPU plan at {(free != plan).sum()} positions", flush=True)
+        p.gpu.migrate()
+        p.orc.set_tiers(plan)
+        p.orc.migrate()
+
+    retier()   # all scores are zero: ties broken by position
+    for step in range(cfg.decode_steps):
+        k, v = p.wl.step_kv(step, 0)
+        p.append(0, k, v)
+        got, ref = p.attend(0, p.wl.step_q(step, 0))
+        calls += 1
+        assert_out_close(got, ref, "f32", f"step {step}")
+        if (step + 1) % cfg.reclassify_every == 0:
+            assert_scores_close(p.gpu.get_scores(), p.orc.score, p.gpu.layer_length(0), _mass(cfg, calls), f"step {step}")
+            retier()
+    st = p.gpu.get_stats()
+    assert sum(st["tier_count"]) == cfg.context + cfg.decode_steps
+    p.close()
+
+
+def test_error_paths_leave_the_gpu_alone():
+    import paper_2605_09490_amd as tkv
+    from gpu_common import Pair
+    cfg = small_config(n_layers=2, batch=1, context=40, decode_steps=2)
+    p = Pair(cfg)
+    q = p.wl.step_q(0, 0)
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.migrate()
+    assert e.value.status == tkv.TKV_ESTATE
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.classify((1, 2, 3, 4))
+    assert e.value.status == tkv.TKV_EINVAL
+    k, v = p.wl.step_kv(0, 0)
+    p.gpu.append(0, k, v)
+    with pytest.raises(tkv.TkvError) as e:      # layer 1 is one token short
+        p.gpu.classify(cfg.policy_ppm)
+    assert e.value.status == tkv.TKV_ESTATE
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.attend_and_score(1, q)
+    assert e.value.status == tkv.TKV_ESTATE
+    p.gpu.append(1, *p.wl.step_kv(0, 1))
+    p.gpu.append(0, *p.wl.step_kv(1, 0))
+    p.gpu.append(1, *p.wl.step_kv(1, 1))
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.append(0, k, v)
+    assert e.value.status == tkv.TKV_ECAPACITY
+    t = np.zeros((1, 42), np.uint8)
+    t[0, 10] = 3
+    p.gpu.set_tiers(t); p.gpu.migrate()
+    t[0, 10] = 0
+    p.gpu.set_tiers(t)
+    with pytest.raises(tkv.TkvError) as e:      # an evicted position cannot come back
+        p.gpu.migrate()
+    assert e.value.status == tkv.TKV_ESTATE
+    p.close()
