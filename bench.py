@@ -1,0 +1,274 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiered decode-attention hot path on one MI355X.
+
+One "step" is one pass of the whole path over a batch of synthetic input: for every layer, append the new
+token's K/V rows and run tiered attention with score accumulation; every Delta steps, classify and migrate
+(T1 offload + prefetch on the side streams).  Inputs are resident in HBM before the timed region starts.
+Prints one JSON line (metric: KV GB/s of the whole job, with the HBM-roofline figure of the attention kernel,
+the T1 prefetch overhead against the all-in-HBM twin, and the CPU oracle timed on a bounded sample).
+"""
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+LINK_PEAK_GBPS = 64.0       # PCIe Gen5 x16, one direction
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def call_bytes(cfg, n_full, n_t2, out_es=4):
+    """Algorithmic bytes of one layer call: every live row once (K and V), q and out, score read-modify-write.
+    n_full, n_t2 are position counts summed over the batch."""
+    es = 2 if cfg.kv_dtype == "bf16" else 4
+    D, Hkv, Hq, B = cfg.head_dim, cfg.n_kv_heads, cfg.n_q_heads, cfg.batch
+    t2_row = (D + 4) if cfg.t2_format == "int8_row" else (D // 2 + (D // 32) * 2)
+    kv = Hkv * (n_full * 2 * D * es + n_t2 * 2 * t2_row)
+    return kv + B * Hq * D * (es + out_es) + (n_full + n_t2) * 4 * 2
+
+
+def run_job(cfg, policy, mode, steps, warmup, profile_steps, label):
+    import torch
+    import paper_2605_09490_amd as tkv
+    from tkv_synth import Workload
+
+    wl = Workload(cfg, device="cuda")
+    gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
+                       kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt, k_sink=cfg.k_sink,
+                       k_window=cfg.k_window, prefetch_mode=mode)
+    for l in range(cfg.n_layers):
+        k, v = wl.context_kv(l)
+        gpu.append(l, k, v)
+    del k, v
+    total = warmup + steps + profile_steps
+    k_all, v_all, q_all = wl.decode_inputs(0, total)
+    out_all = torch.empty((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+    # one attention pass so the first ranking is not all ties, then the initial tiering + cold fill
+    gpu.decode_step(k_all[0], v_all[0], q_all[0], out_all)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    gpu.classify(policy)
+    gpu.migrate()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    gpu.wait_prefetch()
+    t2 = time.perf_counter()
+    st0 = gpu.get_stats()
+    res = {"label": label, "first_migrate_ms": (t1 - t0) * 1e3, "cold_fill_ms": (t2 - t0) * 1e3,
+           "cold_fill_bytes": st0["h2d_bytes"]}
+    delta = cfg.reclassify_every
+
+    def loop(first, n, count_bytes):
+        nbytes = 0
+        for s in range(first, first + n):
+            if count_bytes:
+                tc = gpu_counts[0]
+                nbytes += cfg.n_layers * call_bytes(cfg, tc[0] + tc[1] + cfg.batch, tc[2])
+                tc[0] += cfg.batch
+            gpu.decode_step(k_all[s], v_all[s], q_all[s], out_all)
+            if (s + 1) % delta == 0:
+                gpu.classify(policy)
+                gpu.migrate()
+                if count_bytes:
+                    gpu_counts[0] = list(gpu.get_stats()["tier_count"])
+        return nbytes
+
+    gpu_counts = [None]
+    loop(1, warmup - 1, False)
+    torch.cuda.synchronize()
+    gpu.wait_prefetch()
+    gpu_counts[0] = list(gpu.get_stats()["tier_count"])
+    st1 = gpu.get_stats()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    nbytes = loop(warmup, steps, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    gpu.wait_prefetch()
+    st2 = gpu.get_stats()
+    res.update({"wall_s": t1 - t0, "bytes": nbytes, "ms_per_step": (t1 - t0) * 1e3 / steps,
+                "tier_count": st2["tier_count"], "events": st2["n_migrate"] - st1["n_migrate"],
+                "h2d_bytes": st2["h2d_bytes"] - st1["h2d_bytes"], "h2d_ms": st2["h2d_ms"] - st1["h2d_ms"],
+                "d2h_bytes": st2["d2h_bytes"] - st1["d2h_bytes"], "d2h_ms": st2["d2h_ms"] - st1["d2h_ms"],
+                "classify_ms": st2["classify_ms"] - st1["classify_ms"], "migrate_ms": st2["migrate_ms"] - st1["migrate_ms"],
+                "attend_waits": st2["attend_waits"] - st1["attend_waits"],
+                "lazy_old_reads": st2["lazy_old_reads"] - st1["lazy_old_reads"]})
+    if profile_steps:
+        gpu.set_profile(True)
+        b0 = loop(warmup + steps, profile_steps, True)
+        torch.cuda.synchronize()
+        st3 = gpu.get_stats()
+        gpu.set_profile(False)
+        launches = st3["attn_kernel_launches"] - st2["attn_kernel_launches"]
+        kms = st3["attn_kernel_ms"] - st2["attn_kernel_ms"]
+        res.update({"kernel_launches": launches, "kernel_avg_us": kms * 1e3 / max(launches, 1),
+                    "kernel_bytes_per_launch": b0 / max(launches, 1)})
+        import numpy as np
+        n = gpu.layer_length(0)
+        sc = np.sort(gpu.get_scores()[:, :n].astype(np.float64), axis=1)[:, ::-1]
+        res["top20_share"] = float((sc[:, : n // 5].sum(1) / sc.sum(1)).mean())
+        res["bottom50_share"] = float((sc[:, n // 2:].sum(1) / sc.sum(1)).mean())
+    res["gpu"] = gpu
+    res["wl"] = wl
+    return res
+
+
+def cpu_baseline(cfg, res, budget_s=20.0):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload: the first two layers, all
+    sequences, the GPU run's final tier assignment, a few attention-and-score calls."""
+    import numpy as np
+    import torch
+    from oracle import tkv_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    gpu, wl = res["gpu"], res["wl"]
+    layers = [0, 1][: cfg.n_layers]
+    n = gpu.layer_length(0)
+    tiers = gpu.get_tiers()[:, :n]
+    orc = O.OracleCache(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, n,
+                        kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, k_sink=cfg.k_sink, k_window=cfg.k_window,
+                        layers=layers)
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    # rows as the GPU holds them are not needed for timing: same shapes and distributions, drawn again
+    for l in layers:
+        k, v = wl.context_kv(l)
+        pad = n - k.shape[1]
+        kk, vv = f64(k), f64(v)
+        if pad > 0:
+            kk = np.concatenate([kk, kk[:, :pad]], axis=1)
+            vv = np.concatenate([vv, vv[:, :pad]], axis=1)
+        orc.append(l, kk, vv)
+    orc.tier[:, :n] = tiers            # placement only; T2 rows keep full-precision values for the timing run
+    q = f64(wl.step_q(0, 0))
+    n_full = int(((tiers == 0) | (tiers == 1)).sum())
+    n_t2 = int((tiers == 2).sum())
+    per_call = call_bytes(cfg, n_full, n_t2)
+    calls, t0 = 0, time.perf_counter()
+    while True:
+        for l in layers:
+            orc.attend_and_score(l, q)
+            calls += 1
+        if time.perf_counter() - t0 > budget_s or calls >= 64:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": per_call * calls / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{calls} attend_and_score calls on layers {layers} of the {cfg.name} workload "
+                      f"(batch {cfg.batch}, {n} tokens, final GPU tier assignment), {dt:.1f} s, numpy fp64",
+            "s_per_layer_call": dt / calls, "s_per_step_extrapolated": dt / calls * cfg.n_layers}
+
+
+def link_probe():
+    import torch
+    n = 256 << 20
+    d = torch.empty(n, dtype=torch.uint8, device="cuda")
+    d2 = torch.empty_like(d)
+    h = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    out = {}
+    for name, fn in (("d2d_copy", lambda: d2.copy_(d)), ("h2d_pinned", lambda: d.copy_(h, non_blocking=True)),
+                     ("d2h_pinned", lambda: h.copy_(d, non_blocking=True))):
+        fn(); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+        gb = 4 * n / (time.perf_counter() - t0) / 1e9
+        out[name + "_GBps"] = round(gb * (2 if name == "d2d_copy" else 1), 1)   # d2d: read + write
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="14b")
+    ap.add_argument("--mode", default="lazy", choices=["lazy", "wait"])
+    ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-twin", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from tkv_synth import CONFIGS
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    base = CONFIGS[args.workload]
+    warmup = max(args.warmup, 1)
+    cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps)
+    pol = cfg.policy_ppm
+    twin_pol = (pol[0] + pol[1], 0, pol[2], pol[3])
+    log(f"[bench] workload {cfg.name}: L={cfg.n_layers} B={cfg.batch} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} D={cfg.head_dim} "
+        f"{cfg.kv_dtype} ctx={cfg.context} policy={pol} t2={cfg.t2_format} mode={args.mode}")
+    main_res = run_job(cfg, pol, args.mode, args.steps, warmup, args.profile_steps, "tiered")
+    log(f"[bench] tiered: {main_res['ms_per_step']:.3f} ms/step, cold fill {main_res['cold_fill_ms']:.1f} ms")
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(cfg, main_res)
+        log(f"[bench] oracle: {cpu['s_per_layer_call']*1e3:.1f} ms per layer call on {cpu['cores']} threads")
+    main_res.pop("gpu").close(); main_res.pop("wl")
+    other_mode = "wait" if args.mode == "lazy" else "lazy"
+    extra = {}
+    if not args.no_twin:
+        twin = run_job(cfg, twin_pol, args.mode, args.steps, warmup, 0, "all-T0 twin")
+        twin.pop("gpu").close(); twin.pop("wl")
+        log(f"[bench] twin: {twin['ms_per_step']:.3f} ms/step")
+        alt = run_job(cfg, pol, other_mode, args.steps, warmup, 0, f"tiered-{other_mode}")
+        alt.pop("gpu").close(); alt.pop("wl")
+        log(f"[bench] {other_mode}: {alt['ms_per_step']:.3f} ms/step")
+        extra = {
+            "prefetch_overhead_pct": round(100.0 * (main_res["wall_s"] - twin["wall_s"]) / twin["wall_s"], 2),
+            f"prefetch_overhead_pct_{other_mode}": round(100.0 * (alt["wall_s"] - twin["wall_s"]) / twin["wall_s"], 2),
+            "twin_ms_per_step": round(twin["ms_per_step"], 4),
+            f"{other_mode}_ms_per_step": round(alt["ms_per_step"], 4),
+        }
+    value = main_res["bytes"] / main_res["wall_s"] / 1e9
+    kernel_GBps = main_res["kernel_bytes_per_launch"] / (main_res["kernel_avg_us"] * 1e-6) / 1e9 if main_res.get("kernel_avg_us") else None
+    h2d_GBps = main_res["h2d_bytes"] / (main_res["h2d_ms"] * 1e-3) / 1e9 if main_res["h2d_ms"] > 0 else None
+    d2h_GBps = main_res["d2h_bytes"] / (main_res["d2h_ms"] * 1e-3) / 1e9 if main_res["d2h_ms"] > 0 else None
+    line = {
+        "metric": "tiered decode-attn KV GB/s & % of HBM peak; T1 prefetch overhead % of step",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg.kv_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}-shaped: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d {cfg.head_dim}, "
+                               f"{cfg.kv_dtype} KV, batch {cfg.batch}, {cfg.context}-token context, tiers ppm {list(pol)}, "
+                               f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"},
+        "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),
+        "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
+        "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(kernel_GBps / HBM_PEAK_GBPS, 4) if kernel_GBps else None,
+                     "traffic": None, "kernel": "k_attn_split", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
+                     "algorithmic_bytes_per_launch": int(main_res.get("kernel_bytes_per_launch", 0)),
+                     "launches_timed": main_res.get("kernel_launches")},
+        "cpu_baseline": cpu,
+        "t1": {"events_in_timed_region": main_res["events"], "h2d_bytes": main_res["h2d_bytes"], "d2h_bytes": main_res["d2h_bytes"],
+               "h2d_GBps": round(h2d_GBps, 1) if h2d_GBps else None, "d2h_GBps": round(d2h_GBps, 1) if d2h_GBps else None,
+               "h2d_link_frac": round(h2d_GBps / LINK_PEAK_GBPS, 3) if h2d_GBps else None,
+               "cold_fill_ms": round(main_res["cold_fill_ms"], 1), "cold_fill_bytes": main_res["cold_fill_bytes"],
+               "classify_ms_per_event": round(main_res["classify_ms"] / max(main_res["events"], 1), 3),
+               "migrate_ms_per_event": round(main_res["migrate_ms"] / max(main_res["events"], 1), 3),
+               "attend_waits": main_res["attend_waits"], "lazy_old_reads": main_res["lazy_old_reads"], **extra},
+        "tier_count": main_res["tier_count"],
+        "score_top20_share": round(main_res.get("top20_share", 0), 3), "score_bottom50_share": round(main_res.get("bottom50_share", 0), 3),
+        "probe": link_probe(), "host_cores": os.cpu_count(),
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -130,6 +130,14 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
  * ESTATE on an empty layer. */
 tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream);
 
+/* One decode step of Algorithm 1's loop body for all layers, in layer order: for every layer l,
+ * tkv_append(l, k_all[l], v_all[l], 1) then tkv_attend_and_score(l, q_all[l], out_all[l]).  Device pointers:
+ * k_all, v_all [n_layers, batch, 1, n_kv_heads, head_dim] kv_dtype; q_all [n_layers, batch, n_q_heads, head_dim]
+ * kv_dtype; out_all [n_layers, batch, n_q_heads, head_dim] out_dtype.  Same errors as the two calls; a failure
+ * at layer l leaves layers < l appended and attended. */
+tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, const void* q_all, void* out_all,
+                           void* hip_stream);
+
 /* Sec. 3.3 / Algorithm 1 "tier management", device only: ranks the candidates of every sequence by
  * (already evicted first, score bits, position) and writes the pending tier array; no KV row moves.
  * ESTATE if layers differ in length; EINVAL if the policy does not sum to 10^6. */
@@ -163,6 +171,8 @@ tkv_status tkv_get_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head
 /* Blocks until every T1 transfer started by tkv_migrate has landed in the staging buffer. */
 tkv_status tkv_wait_prefetch(tkv_cache* c);
 tkv_status tkv_get_stats(tkv_cache* c, tkv_stats* out);
+/* Switches the per-kernel HIP-event timing of the attention kernels on or off (see tkv_config.profile). */
+tkv_status tkv_set_profile(tkv_cache* c, int32_t on);
 int32_t tkv_layer_length(const tkv_cache* c, int32_t layer); /* -1 on bad arguments */
 const char* tkv_last_error(const tkv_cache* c);
 

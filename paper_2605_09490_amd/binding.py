@@ -60,6 +60,8 @@ SYMBOLS = {
     "tkv_destroy": (None, [_VP]),
     "tkv_append": (C.c_int, [_VP, _I32, _VP, _VP, _I32, _VP]),
     "tkv_attend_and_score": (C.c_int, [_VP, _I32, _VP, _VP, _VP]),
+    "tkv_decode_step": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _VP]),
+    "tkv_set_profile": (C.c_int, [_VP, _I32]),
     "tkv_classify": (C.c_int, [_VP, C.POINTER(tkv_policy), _VP]),
     "tkv_migrate": (C.c_int, [_VP, _VP]),
     "tkv_get_scores": (C.c_int, [_VP, _VP]),
@@ -212,6 +214,20 @@ class TieredKV:
                                                   self._dev_tensor(out, (B, Hq, D), self.out_torch_dtype),
                                                   self._stream(stream)))
         return out
+
+    def decode_step(self, k_all, v_all, q_all, out_all=None, stream=None):
+        L, B, Hq, Hkv, D = self.shape
+        if out_all is None:
+            out_all = torch.empty((L, B, Hq, D), dtype=self.out_torch_dtype, device=self.device)
+        self._check(self.lib.tkv_decode_step(self._h, self._dev_tensor(k_all, (L, B, 1, Hkv, D)),
+                                             self._dev_tensor(v_all, (L, B, 1, Hkv, D)),
+                                             self._dev_tensor(q_all, (L, B, Hq, D)),
+                                             self._dev_tensor(out_all, (L, B, Hq, D), self.out_torch_dtype),
+                                             self._stream(stream)))
+        return out_all
+
+    def set_profile(self, on):
+        self._check(self.lib.tkv_set_profile(self._h, 1 if on else 0))
 
     def classify(self, policy_ppm, stream=None):
         pol = tkv_policy(*[int(x) for x in policy_ppm])

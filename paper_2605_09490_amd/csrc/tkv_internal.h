@@ -72,13 +72,15 @@ struct AttnArgs {
   float* xs;        // [B][Hkv][G][xs_stride] scaled logits by list index (F entries, then Q entries from f_pad)
   float* part_ml;   // [B][Hkv][S][2][G]  (m, l) of each split
   float* part_o;    // [B][Hkv][S][G][D]
-  int B, Hq, Hkv, Nmax, capF, cap2, S, xs_stride, cb, sb, t2fmt, out_bf16;
+  float* ml_final;  // [B][Hq][2] global (m, 1/l) of every head, written by the last workgroup of each (b, kv head)
+  int* counter;     // [B][Hkv] arrival counters of the split workgroups; zero between launches
+  int B, Hq, Hkv, Nmax, capF, cap2, S, xs_stride, cb, sb, t2fmt, out_bf16, q_es;
   float softmax_scale, score_scale;
 };
 
 // launchers (defined in the .hip files)
-hipError_t launch_attn_split(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st);
-hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, bool bf16, int n_tiles, hipStream_t st);
+hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st);
+hipError_t launch_attn_scores(const AttnArgs& a, hipStream_t st);
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
 hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStream_t st);

@@ -121,6 +121,28 @@ class Workload:
         return q.to(cfg.torch_dtype).contiguous()
 
 
+    def decode_inputs(self, first_step, n_steps):
+        """Bulk draw for a benchmark loop: k_all, v_all [n_steps, L, B, 1, Hkv, D] and q_all [n_steps, L, B, Hq, D]
+        (same distributions as step_kv / step_q, drawn per layer in one go)."""
+        cfg = self.cfg
+        p0 = cfg.context + first_step
+        fac = self.key_factor[:, p0:p0 + n_steps].t().contiguous()       # [n_steps, B]
+        k_all = torch.empty((n_steps, cfg.n_layers, cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim),
+                            dtype=cfg.torch_dtype, device=self.device)
+        v_all = torch.empty_like(k_all)
+        q_all = torch.empty((n_steps, cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim),
+                            dtype=cfg.torch_dtype, device=self.device)
+        for l in range(cfg.n_layers):
+            g = _gen(self.device, cfg.seed, 4, l, first_step)
+            shape = (n_steps, cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim)
+            k = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32)
+            k_all[:, l] = (k * fac[:, :, None, None, None]).to(cfg.torch_dtype)
+            v_all[:, l] = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32).to(cfg.torch_dtype)
+            q_all[:, l] = torch.randn((n_steps, cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=g,
+                                      device=self.device, dtype=torch.float32).to(cfg.torch_dtype)
+        return k_all, v_all, q_all
+
+
 def small_config(name="small", **kw) -> WorkloadConfig:
     """A free-form config for parity tests (sizes the oracle finishes in seconds)."""
     base = dict(name=name, n_layers=2, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=64,
