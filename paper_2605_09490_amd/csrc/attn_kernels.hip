@@ -3,15 +3,19 @@
 //   attn_tiered : grid (S, Hkv, B), 4 waves per workgroup.  Workgroup (s, kvh, b) owns TOK_PER_BLOCK consecutive
 //                 entries of one of the two per-sequence lists -- F (T0 u T1 rows at full precision, ascending
 //                 position) or Q (T2 rows, int8 / int4 codes dequantised in registers); T3 positions are in
-//                 neither list.  Every wave is autonomous: it takes 64-entry tiles, streams their K rows
-//                 (16-byte loads, one row per group of lanes), reduces the G logits of each row inside the lane
-//                 group so that lane i ends up holding the logits of tile entry i, runs an online softmax with
-//                 one entry per lane, then streams the V rows into per-lane output slices.  The four waves are
-//                 merged through LDS into one split partial (m, l, o[G][D]); the scaled logits go to a scratch
-//                 array.  The last workgroup of a (b, kvh) to finish (device-scope counter) merges that pair's
-//                 split partials into out[b, kvh*G .. kvh*G+G) and publishes the global (m, 1/l) of its heads.
-//   attn_scores : turns the stored logits into softmax weights with the global (m, 1/l), summed over all query
-//                 heads in a fixed order, into score[b, pos].
+//                 neither list.  Every wave is autonomous and works on 64-entry tiles:
+//                   K rows  - 8 lanes per row (each lane 1/8 of the row), 8 rows per wave-wide load; the G logits
+//                             of a row are reduced over its 8 lanes by DPP and kept by the lane whose index
+//                             equals the entry's index in the tile, so after 8 loads lane i holds entry i;
+//                   softmax - online, one entry per lane (exact tile maximum, exp2, running m and l);
+//                   V rows  - 16 bytes per lane, 64/LPR rows per wave-wide load, probabilities broadcast from
+//                             LDS, per-lane fp32 output slices.
+//                 The four waves are merged through LDS into one split partial (m, l, o[G][D]); the scaled
+//                 logits go to a scratch array.
+//   attn_finish : grid (tiles + Hkv, B).  Every workgroup first merges the (m, l) of all splits of its sequence
+//                 into the global (m, 1/l) of every query head.  Tile workgroups then turn the stored logits
+//                 into softmax weights, summed over all query heads in a fixed order, into score[b, pos]; the
+//                 Hkv remaining workgroups merge the split outputs into out[b, kvh*G .. kvh*G+G).
 // The split boundaries and the fp32 summation order depend only on the lists' logical order, never on whether a
 // row lives in the HBM pool or the staging buffer (both are one slot space), which is what makes T1 placement
 // bit-invisible (Prop. 1).  No MFMA: the path is bound by HBM, and the per-row work is G dot products.
@@ -30,6 +34,18 @@ constexpr int TPW = TB / NWAVE;   // list entries per wave
 constexpr int NTILE = TPW / 64;   // 64-entry tiles per wave
 static_assert(TPW % 64 == 0 && NTILE >= 1, "a wave works in tiles of 64 entries");
 
+#ifndef TKV_UK
+#define TKV_UK 2      // K rows per batch and lane group (two batches are in flight)
+#endif
+#ifndef TKV_UV
+#define TKV_UV 4      // V rows per batch and lane group (two batches are in flight)
+#endif
+#ifdef TKV_ATTN_WAVES_PER_EU
+#define TKV_WPE __attribute__((amdgpu_waves_per_eu(TKV_ATTN_WAVES_PER_EU, TKV_ATTN_WAVES_PER_EU)))
+#else
+#define TKV_WPE
+#endif
+
 enum Mode : int { F_BF16 = 0, F_F32 = 1, Q_INT8 = 2, Q_INT4 = 3 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
@@ -39,6 +55,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float x) {
   return __builtin_amdgcn_update_dpp(0.f, x, CTRL, 0xf, 0xf, false);
+}
+// rows listed in ROW_MASK receive the DPP source, the others keep x
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_rows(float x) {
+  return __builtin_amdgcn_update_dpp(x, x, CTRL, ROW_MASK, 0xf, false);
 }
 
 // sum over aligned groups of LPR consecutive lanes; every lane of the group receives the result
@@ -54,25 +75,19 @@ __device__ __forceinline__ float group_sum(float x) {
 __device__ __forceinline__ float rdlane(float x, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
 }
-// Split partials travel between workgroups inside one launch.  They are written and read with relaxed
-// device-scope atomics (coherent across the chip's L2 slices by themselves), the writer waits for its stores to
-// complete before it takes a ticket, and the reader only starts after it has seen the last ticket; no
-// cache-wide release/acquire fence is needed for data that is only ever touched this way.
-__device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// a value every lane holds identically, moved to a scalar register
-__device__ __forceinline__ float uniform(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
-}
-// whole-wave reductions: 16-lane rows by DPP, then the four row results through scalar registers
+// whole-wave reductions: 16-lane rows by DPP, rows 0/1 and 2/3 by row_bcast15, halves by row_bcast31; lane 63 has
+// the result, which is returned in a scalar register
 __device__ __forceinline__ float wave_max(float x) {
   x = fmaxf(x, dpp_f<0xB1>(x)); x = fmaxf(x, dpp_f<0x4E>(x)); x = fmaxf(x, dpp_f<0x141>(x)); x = fmaxf(x, dpp_f<0x140>(x));
-  return fmaxf(fmaxf(rdlane(x, 0), rdlane(x, 16)), fmaxf(rdlane(x, 32), rdlane(x, 48)));
+  x = fmaxf(x, dpp_rows<0x142, 0xA>(x));
+  x = fmaxf(x, dpp_rows<0x143, 0xC>(x));
+  return rdlane(x, 63);
 }
 __device__ __forceinline__ float wave_sum(float x) {
   x = group_sum<16>(x);
-  return (rdlane(x, 0) + rdlane(x, 16)) + (rdlane(x, 32) + rdlane(x, 48));
+  const float a = rdlane(x, 0) + rdlane(x, 16), b = rdlane(x, 32) + rdlane(x, 48);
+  return a + b;
 }
 
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
@@ -82,24 +97,26 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+// two code values (exact in bf16: at most 8 significant bits) packed as a bf16 pair
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
+  return (__builtin_bit_cast(uint32_t, hi) & 0xffff0000u) | (__builtin_bit_cast(uint32_t, lo) >> 16);
+}
 
 template <int G>
 struct GPad { static constexpr int v = (G <= 4) ? 4 : 8; };
 
-// one row's worth of registers for one lane
-template <Mode M> struct RowRegs;
-template <> struct RowRegs<F_BF16> { u32x4 d; };
-template <> struct RowRegs<F_F32> { u32x4 d; };
-template <> struct RowRegs<Q_INT8> { u32x2 d; float sc; };
-template <> struct RowRegs<Q_INT4> { uint32_t d; float sc; };
-
+// ---- geometry ------------------------------------------------------------------------------------------------
 template <int D, Mode M>
 struct Geo {
   static constexpr bool IS_Q = (M == Q_INT8 || M == Q_INT4);
-  static constexpr int EPL = (M == F_F32) ? 4 : 8;   // elements of a row per lane
-  static constexpr int LPR = D / EPL;                // lanes per row
-  static constexpr int NIT = LPR;                    // wave-wide loads per 64-entry tile (64/LPR rows each)
-  static constexpr float OFF = (M == Q_INT4) ? 8.f : 128.f;
+  // K side: 8 lanes per row
+  static constexpr int EK = D / 8;                                            // elements of a K row per lane
+  static constexpr int KDW = (M == F_BF16) ? EK / 2 : (M == F_F32) ? EK : (M == Q_INT8) ? EK / 4 : EK / 8;  // dwords per lane
+  // V side: one 16-byte piece (F modes) / 8 codes (Q modes) per lane
+  static constexpr int EV = (M == F_F32) ? 4 : 8;
+  static constexpr int LPRV = D / EV;                                         // lanes per V row
+  static constexpr int NITV = LPRV;                                           // wave-wide V loads per tile
+  static constexpr float OFF = (M == Q_INT4) ? 8.f : 128.f;                   // codes are read as code + OFF
 };
 
 struct RowSrc {
@@ -107,125 +124,161 @@ struct RowSrc {
   uint32_t row_bytes, scale_bytes;
 };
 
-// loc == -1 gives an offset beyond the buffer: such loads return zeros
-template <int D, Mode M>
-__device__ __forceinline__ RowRegs<M> load_row(const RowSrc& s, int loc, int r) {
-  RowRegs<M> out;
-  if constexpr (M == F_BF16 || M == F_F32) {
-    out.d = __builtin_amdgcn_raw_buffer_load_b128(s.data, (uint32_t)loc * s.row_bytes + r * 16, 0, 2);
-  } else if constexpr (M == Q_INT8) {
-    out.d = __builtin_amdgcn_raw_buffer_load_b64(s.data, (uint32_t)loc * s.row_bytes + r * 8, 0, 2);
-    out.sc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(s.scale, (uint32_t)loc * s.scale_bytes, 0, 0));
+template <int NDW>
+__device__ __forceinline__ void load_dwords(const __amdgpu_buffer_rsrc_t& rs, uint32_t off, uint32_t (&w)[NDW]) {
+  if constexpr (NDW >= 4) {
+#pragma unroll
+    for (int i = 0; i < NDW / 4; ++i) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 16 * i, 0, 2);
+      w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+    }
+  } else if constexpr (NDW == 2) {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, 2);
+    w[0] = v.x; w[1] = v.y;
   } else {
-    out.d = __builtin_amdgcn_raw_buffer_load_b32(s.data, (uint32_t)loc * s.row_bytes + r * 4, 0, 2);
-    const uint16_t hb = __builtin_amdgcn_raw_buffer_load_b16(s.scale, (uint32_t)loc * s.scale_bytes + (uint32_t)(r >> 2) * 2, 0, 0);
-    out.sc = (float)__builtin_bit_cast(_Float16, hb);
+    w[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 2);
   }
+}
+
+// scale of a T2 row (INT8) or of the 32-code group that starts at element e0 (INT4).  loc == -1 is out of range: 0
+template <Mode M>
+__device__ __forceinline__ float load_scale(const RowSrc& s, int loc, int e0) {
+  if constexpr (M == Q_INT8) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(s.scale, (uint32_t)loc * s.scale_bytes, 0, 0));
+  } else if constexpr (M == Q_INT4) {
+    const uint16_t hb = __builtin_amdgcn_raw_buffer_load_b16(s.scale, (uint32_t)loc * s.scale_bytes + (uint32_t)(e0 >> 5) * 2, 0, 0);
+    return (float)__builtin_bit_cast(_Float16, hb);
+  } else {
+    return 0.f;
+  }
+}
+
+template <int D, Mode M>
+struct KRow { uint32_t w[Geo<D, M>::KDW]; float sc; };
+template <int D, Mode M>
+struct VRow { uint32_t w[(M == Q_INT8) ? 2 : (M == Q_INT4) ? 1 : 4]; float sc; };
+
+// loc == -1 gives offsets beyond the buffer: such loads return zeros
+template <int D, Mode M>
+__device__ __forceinline__ KRow<D, M> load_krow(const RowSrc& s, int loc, int r8) {
+  KRow<D, M> out;
+  load_dwords<Geo<D, M>::KDW>(s.data, (uint32_t)loc * s.row_bytes + (uint32_t)r8 * (Geo<D, M>::KDW * 4), out.w);
+  out.sc = load_scale<M>(s, loc, r8 * Geo<D, M>::EK);
+  return out;
+}
+template <int D, Mode M>
+__device__ __forceinline__ VRow<D, M> load_vrow(const RowSrc& s, int loc, int r) {
+  VRow<D, M> out;
+  constexpr int NDW = (M == Q_INT8) ? 2 : (M == Q_INT4) ? 1 : 4;
+  load_dwords<NDW>(s.data, (uint32_t)loc * s.row_bytes + (uint32_t)r * (NDW * 4), out.w);
+  out.sc = load_scale<M>(s, loc, r * 8);
   return out;
 }
 
-// codes as unsigned values with an offset (128 / 8) that is removed once per row: sum q*(u-off) = sum q*u - off*sum q
-template <Mode M>
-__device__ __forceinline__ void unpack_codes(const RowRegs<M>& rr, float (&f)[8]) {
+// codes as unsigned values code + OFF; the offset is removed once per row: sum q*(u-OFF) = sum q*u - OFF*sum q
+template <Mode M, int NDW>
+__device__ __forceinline__ void unpack_codes(const uint32_t (&w)[NDW], float (&f)[(M == Q_INT8) ? NDW * 4 : NDW * 8]) {
   if constexpr (M == Q_INT8) {
-    const uint32_t w[2] = {rr.d.x ^ 0x80808080u, rr.d.y ^ 0x80808080u};
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NDW; ++i) {
+      const uint32_t u = w[i] ^ 0x80808080u;
 #pragma unroll
-      for (int n = 0; n < 4; ++n) f[i * 4 + n] = (float)((w[i] >> (8 * n)) & 0xFFu);
-  } else if constexpr (M == Q_INT4) {
-    const uint32_t w = rr.d ^ 0x88888888u;
+      for (int n = 0; n < 4; ++n) f[i * 4 + n] = (float)((u >> (8 * n)) & 0xFFu);
+    }
+  } else {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) f[n] = (float)((w >> (4 * n)) & 0xFu);
+    for (int i = 0; i < NDW; ++i) {
+      const uint32_t u = w[i] ^ 0x88888888u;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) f[i * 8 + n] = (float)((u >> (4 * n)) & 0xFu);
+    }
   }
 }
 
-// The lane's slice of the G query vectors.  F modes and Q modes with bf16 queries keep the raw 16 bytes (bf16 pairs,
-// or 4 floats in F_F32); Q modes with binary32 queries keep 8 floats.  qs is the slice's sum (Q modes).
-template <int G, Mode M, bool QBF>
+// The lane's 1/8 slice of the G query vectors.  bf16 queries stay packed (EK/2 dwords per head, fed to the bf16
+// dot instruction); binary32 queries are kept as EK floats.  qs is the slice's sum (Q modes only).
+template <int D, int G, bool QBF>
 struct QRegs {
-  uint32_t qp[G][4];
-  float qf[(M == Q_INT8 || M == Q_INT4) && !QBF ? G : 1][8];
+  static constexpr int EK = D / 8;
+  uint32_t qp[QBF ? G : 1][EK / 2];
+  float qf[QBF ? 1 : G][EK];
   float qs[G];
 };
 
-// two code values (exact in bf16: at most 8 significant bits) packed as a bf16 pair
-__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
-  return (__builtin_bit_cast(uint32_t, hi) & 0xffff0000u) | (__builtin_bit_cast(uint32_t, lo) >> 16);
-}
-
-// G logits of one row, reduced over the row's lane group (every lane of the group gets them)
+// G logits of one K row, reduced over the row's 8 lanes (every lane of the group gets them)
 template <int D, int G, Mode M, bool QBF>
-__device__ __forceinline__ void row_logits(const RowRegs<M>& rr, const QRegs<G, M, QBF>& q, float (&x)[G]) {
-  constexpr int LPR = Geo<D, M>::LPR;
-  if constexpr (M == F_BF16 || M == F_F32) {
-    const uint32_t kw[4] = {rr.d.x, rr.d.y, rr.d.z, rr.d.w};
+__device__ __forceinline__ void row_logits(const KRow<D, M>& kr, const QRegs<D, G, QBF>& q, float (&x)[G]) {
+  using GE = Geo<D, M>;
+  constexpr int EK = GE::EK;
+  if constexpr (M == F_BF16) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float acc = 0.f;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if constexpr (M == F_BF16)
-          acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kw[c]), __builtin_bit_cast(bf16x2, q.qp[h][c]), acc, false);
-        else
-          acc = fmaf(__builtin_bit_cast(float, kw[c]), __builtin_bit_cast(float, q.qp[h][c]), acc);
-      }
-      x[h] = group_sum<LPR>(acc);
+      for (int c = 0; c < EK / 2; ++c)
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kr.w[c]), __builtin_bit_cast(bf16x2, q.qp[h][c]), acc, false);
+      x[h] = group_sum<8>(acc);
+    }
+  } else if constexpr (M == F_F32) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float acc = 0.f;
+#pragma unroll
+      for (int c = 0; c < EK; ++c) acc = fmaf(__builtin_bit_cast(float, kr.w[c]), q.qf[h][c], acc);
+      x[h] = group_sum<8>(acc);
     }
   } else {
-    float kf[8];
-    unpack_codes<M>(rr, kf);
-    uint32_t kp[4];
+    float kf[EK];
+    unpack_codes<M, GE::KDW>(kr.w, kf);
+    uint32_t kp[EK / 2];
     if constexpr (QBF) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) kp[c] = pack_bf16_pair(kf[2 * c], kf[2 * c + 1]);
+      for (int c = 0; c < EK / 2; ++c) kp[c] = pack_bf16_pair(kf[2 * c], kf[2 * c + 1]);
     }
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      float acc = -Geo<D, M>::OFF * q.qs[h];
+      float acc = -GE::OFF * q.qs[h];
       if constexpr (QBF) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+        for (int c = 0; c < EK / 2; ++c)
           acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[c]), __builtin_bit_cast(bf16x2, q.qp[h][c]), acc, false);
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc = fmaf(q.qf[h][e], kf[e], acc);
+        for (int c = 0; c < EK; ++c) acc = fmaf(q.qf[h][c], kf[c], acc);
       }
-      if constexpr (M == Q_INT4) acc *= rr.sc;      // per-group scale: before the cross-lane sum
-      x[h] = group_sum<LPR>(acc);
-      if constexpr (M == Q_INT8) x[h] *= rr.sc;     // per-row scale
+      if constexpr (M == Q_INT4) acc *= kr.sc;      // per-group scale: before the cross-lane sum
+      x[h] = group_sum<8>(acc);
+      if constexpr (M == Q_INT8) x[h] *= kr.sc;     // per-row scale
     }
   }
 }
 
 template <int D, int G, Mode M>
-__device__ __forceinline__ void row_accumulate(const RowRegs<M>& rr, const float (&p)[GPad<G>::v],
-                                               float (&o)[G][Geo<D, M>::EPL], float (&osub)[G]) {
-  constexpr int EPL = Geo<D, M>::EPL;
+__device__ __forceinline__ void row_accumulate(const VRow<D, M>& vr, const float (&p)[GPad<G>::v],
+                                               float (&o)[G][Geo<D, M>::EV], float (&osub)[G]) {
+  constexpr int EV = Geo<D, M>::EV;
   if constexpr (M == F_BF16) {
-    const uint32_t vw[4] = {rr.d.x, rr.d.y, rr.d.z, rr.d.w};
     float vf[8];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) { vf[2 * c] = bf_lo(vw[c]); vf[2 * c + 1] = bf_hi(vw[c]); }
+    for (int c = 0; c < 4; ++c) { vf[2 * c] = bf_lo(vr.w[c]); vf[2 * c + 1] = bf_hi(vr.w[c]); }
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(p[h], vf[e], o[h][e]);
+      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(p[h], vf[e], o[h][e]);
   } else if constexpr (M == F_F32) {
-    const uint32_t vw[4] = {rr.d.x, rr.d.y, rr.d.z, rr.d.w};
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(p[h], __builtin_bit_cast(float, vw[e]), o[h][e]);
+      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(p[h], __builtin_bit_cast(float, vr.w[e]), o[h][e]);
   } else {
     float vf[8];
-    unpack_codes<M>(rr, vf);
+    unpack_codes<M, (M == Q_INT8) ? 2 : 1>(vr.w, vf);
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const float ps = p[h] * rr.sc;
+      const float ps = p[h] * vr.sc;
       osub[h] += ps;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(ps, vf[e], o[h][e]);
+      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(ps, vf[e], o[h][e]);
     }
   }
 }
@@ -236,18 +289,19 @@ template <int D, int G, Mode M, bool QBF>
 __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float* sm_ml, float* pbuf_all,
                                            int b, int kvh, int s, int ntok, const int* loc_list) {
   using GE = Geo<D, M>;
-  constexpr int EPL = GE::EPL, LPR = GE::LPR, NIT = GE::NIT;
+  constexpr int EV = GE::EV, LPRV = GE::LPRV, NITV = GE::NITV, EK = GE::EK;
   constexpr int GP = GPad<G>::v;
-  constexpr int U = 4;                     // rows per batch; two batches are kept in flight
-  constexpr int NB = NIT / U;              // batches per tile: 2, 4 or 8
-  static_assert(NIT % U == 0 && NB % 2 == 0, "tile loads come in an even number of batches of 4");
+  constexpr int UK = TKV_UK, NBK = 8 / UK;            // K: 8 wave-wide loads per tile, in batches of UK
+  constexpr int UV = (TKV_UV * 2 <= NITV) ? TKV_UV : NITV / 2, NBV = NITV / UV;   // V: NITV loads per tile
+  static_assert(NITV % UV == 0 && NBV % 2 == 0 && NBK % 2 == 0, "batches come in pairs");
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int grp = lane / LPR, r = lane % LPR;
+  const int g8 = lane >> 3, r8 = lane & 7;           // K side: row group and slice
+  const int gv = lane / LPRV, rv = lane % LPRV;      // V side
   float* pbuf = pbuf_all + wave * 64 * GP;
 
   RowSrc ks, vs;
   if constexpr (!GE::IS_Q) {
-    const uint32_t rb = D * (uint32_t)a.q_es;
+    const uint32_t rb = D * (QBF ? 2u : 4u);
     const size_t off = (size_t)(b * a.Hkv + kvh) * a.capF * rb;
     ks.data = make_rsrc(a.fpK + off, (uint32_t)a.capF * rb); vs.data = make_rsrc(a.fpV + off, (uint32_t)a.capF * rb);
     ks.scale = ks.data; vs.scale = vs.data;
@@ -259,44 +313,46 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
     ks.row_bytes = vs.row_bytes = a.cb; ks.scale_bytes = vs.scale_bytes = a.sb;
   }
 
-  // this lane's slice of the G query vectors
-  QRegs<G, M, QBF> q;
+  // this lane's 1/8 slice of the G query vectors
+  QRegs<D, G, QBF> q;
   {
     constexpr int qes = QBF ? 2 : 4;
-    const char* qb = (const char*)a.q + ((size_t)(b * a.Hq + kvh * G) * D + r * EPL) * qes;
+    const char* qb = (const char*)a.q + ((size_t)(b * a.Hq + kvh * G) * D + r8 * EK) * qes;
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       const char* qh = qb + (size_t)h * D * qes;
-      if constexpr (M == F_BF16 || M == F_F32) {
-        const u32x4 v = *(const u32x4*)qh;
-        q.qp[h][0] = v.x; q.qp[h][1] = v.y; q.qp[h][2] = v.z; q.qp[h][3] = v.w;
-      } else if constexpr (QBF) {
-        const u32x4 v = *(const u32x4*)qh;
-        q.qp[h][0] = v.x; q.qp[h][1] = v.y; q.qp[h][2] = v.z; q.qp[h][3] = v.w;
-        float sacc = 0.f;
+      float sacc = 0.f;
+      if constexpr (QBF) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) sacc += bf_lo(q.qp[h][c]) + bf_hi(q.qp[h][c]);
-        q.qs[h] = sacc;
+        for (int c = 0; c < EK / 8; ++c) {
+          const u32x4 v = *(const u32x4*)(qh + 16 * c);
+          q.qp[h][4 * c] = v.x; q.qp[h][4 * c + 1] = v.y; q.qp[h][4 * c + 2] = v.z; q.qp[h][4 * c + 3] = v.w;
+        }
+        if constexpr (GE::IS_Q) {
+#pragma unroll
+          for (int c = 0; c < EK / 2; ++c) sacc += bf_lo(q.qp[h][c]) + bf_hi(q.qp[h][c]);
+        }
       } else {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const float4 v = *(const float4*)(qh + c * 16);
+        for (int c = 0; c < EK / 4; ++c) {
+          const float4 v = *(const float4*)(qh + 16 * c);
           q.qf[h][4 * c] = v.x; q.qf[h][4 * c + 1] = v.y; q.qf[h][4 * c + 2] = v.z; q.qf[h][4 * c + 3] = v.w;
         }
-        float sacc = 0.f;
+        if constexpr (GE::IS_Q) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sacc += q.qf[h][e];
-        q.qs[h] = sacc;
+          for (int c = 0; c < EK; ++c) sacc += q.qf[h][c];
+        }
       }
+      q.qs[h] = sacc;
     }
   }
 
-  float o[G][EPL], osub[G], m_run[G], l_run[G];
+  float o[G][EV], osub[G], m_run[G], l_run[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
     osub[h] = 0.f; m_run[h] = -INFINITY; l_run[h] = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) o[h][e] = 0.f;
+    for (int e = 0; e < EV; ++e) o[h][e] = 0.f;
   }
 
 #pragma unroll
@@ -304,43 +360,46 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
     const int tbase = wave * TPW + tile * 64;          // first entry of the tile, relative to the workgroup
     if (tbase >= ntok) break;                          // wave-uniform
     const bool valid = tbase + lane < ntok;
-    // slot of tile entry `lane`; entry grp*LPR + it is loaded by lane group grp at iteration it
-    const int myloc = valid ? loc_list[tbase + lane] : -1;
+    const int myloc = valid ? loc_list[tbase + lane] : -1;   // slot of tile entry `lane`
 
-    // Batches 0..NB-1 are the tile's K rows, NB..2NB-1 its V rows; two batches are in flight at any time, so the
-    // first V batches are already on their way while the last K batches and the softmax are being computed.
-    RowRegs<M> buf0[U], buf1[U];
-    auto issue = [&](int k, RowRegs<M> (&dst)[U]) {
-      const bool is_k = k < NB;
-      const int batch = is_k ? k : k - NB;
-      RowSrc src;      // select the descriptor, not the loaded value
-      src.data = is_k ? ks.data : vs.data; src.scale = is_k ? ks.scale : vs.scale;
-      src.row_bytes = ks.row_bytes; src.scale_bytes = ks.scale_bytes;
+    // ---- K rows: entry g8*8 + it is loaded by lane group g8 at iteration it, two batches in flight
+    KRow<D, M> kb0[UK], kb1[UK];
+    auto issue_k = [&](int batch, KRow<D, M> (&dst)[UK]) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) dst[u] = load_row<D, M>(src, __shfl(myloc, grp * LPR + batch * U + u), r);
+      for (int u = 0; u < UK; ++u) dst[u] = load_krow<D, M>(ks, __shfl(myloc, g8 * 8 + batch * UK + u), r8);
     };
     float xt[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) xt[h] = 0.f;
-    auto logits = [&](int k, const RowRegs<M> (&src)[U]) {
+    auto logits = [&](int batch, const KRow<D, M> (&src)[UK]) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
+      for (int u = 0; u < UK; ++u) {
         float x[G];
         row_logits<D, G, M, QBF>(src[u], q, x);
-        const int it = k * U + u;
+        const int it = batch * UK + u;
 #pragma unroll
-        for (int h = 0; h < G; ++h) xt[h] = (r == it) ? x[h] : xt[h];   // lane grp*LPR+it keeps entry grp*LPR+it
+        for (int h = 0; h < G; ++h) xt[h] = (r8 == it) ? x[h] : xt[h];   // lane g8*8+it keeps entry g8*8+it
+        __builtin_amdgcn_sched_barrier(0);
       }
     };
-    issue(0, buf0);
-    issue(1, buf1);
+    issue_k(0, kb0);
+    issue_k(1, kb1);
 #pragma unroll 1
-    for (int k = 0; k < NB; k += 2) {
-      logits(k, buf0);
-      issue(k + 2, buf0);
-      logits(k + 1, buf1);
-      issue(k + 3, buf1);
+    for (int k = 0; k < NBK; k += 2) {
+      logits(k, kb0);
+      if (k + 2 < NBK) issue_k(k + 2, kb0);
+      logits(k + 1, kb1);
+      if (k + 3 < NBK) issue_k(k + 3, kb1);
     }
+    // ---- V rows: entry gv*LPRV + it is loaded by lane group gv at iteration it; the first two batches fly
+    //      while the softmax is computed
+    VRow<D, M> vb0[UV], vb1[UV];
+    auto issue_v = [&](int batch, VRow<D, M> (&dst)[UV]) {
+#pragma unroll
+      for (int u = 0; u < UV; ++u) dst[u] = load_vrow<D, M>(vs, __shfl(myloc, gv * LPRV + batch * UV + u), rv);
+    };
+    issue_v(0, vb0);
+    issue_v(1, vb1);
     // ---- online softmax, one entry per lane
     float corr[G];
     {
@@ -349,10 +408,13 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
       for (int h = 0; h < G; ++h) {
         const float x = valid ? xt[h] * a.softmax_scale : -INFINITY;
         if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x;
-        const float mn = uniform(fmaxf(m_run[h], wave_max(x)));
-        corr[h] = uniform(__builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E));
+        const float tm = wave_max(x);
+        float mn;
+        if (tile == 0) { mn = tm; corr[h] = 0.f; }
+        else { mn = fmaxf(m_run[h], tm); corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E); }
         const float p = valid ? __builtin_amdgcn_exp2f((x - mn) * LOG2E) : 0.f;
-        l_run[h] = uniform(fmaf(l_run[h], corr[h], wave_sum(p)));
+        const float ps = wave_sum(p);
+        l_run[h] = (tile == 0) ? ps : fmaf(l_run[h], corr[h], ps);
         m_run[h] = mn;
         pbuf[lane * GP + h] = p;
       }
@@ -363,29 +425,39 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
       for (int h = 0; h < G; ++h) {
         osub[h] *= corr[h];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[h][e] *= corr[h];
+        for (int e = 0; e < EV; ++e) o[h][e] *= corr[h];
       }
     }
-    // ---- V rows
-    auto accum = [&](int vb, const RowRegs<M> (&src)[U]) {
+    // probabilities of entry (gv, it): read one row ahead of their use, so only two rows' worth stay in registers
+    auto load_p = [&](int it, float (&p)[GP]) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int it = vb * U + u;
-        float p[GP];
+      for (int c = 0; c < GP; c += 4) {
+        const float4 pv = *(const float4*)(pbuf + (gv * LPRV + it) * GP + c);
+        p[c] = pv.x; p[c + 1] = pv.y; p[c + 2] = pv.z; p[c + 3] = pv.w;
+      }
+    };
+    auto accum = [&](int batch, const VRow<D, M> (&src)[UV]) {
+      float pc[GP];
+      load_p(batch * UV, pc);
 #pragma unroll
-        for (int c = 0; c < GP; c += 4) {
-          const float4 pv = *(const float4*)(pbuf + (grp * LPR + it) * GP + c);
-          p[c] = pv.x; p[c + 1] = pv.y; p[c + 2] = pv.z; p[c + 3] = pv.w;
+      for (int u = 0; u < UV; ++u) {
+        float pn[GP];
+        if (u + 1 < UV) load_p(batch * UV + u + 1, pn);
+        __builtin_amdgcn_sched_barrier(0);   // rows stay in order: bounds the live p / widened-V registers
+        row_accumulate<D, G, M>(src[u], pc, o, osub);
+        __builtin_amdgcn_sched_barrier(0);
+        if (u + 1 < UV) {
+#pragma unroll
+          for (int c = 0; c < GP; ++c) pc[c] = pn[c];
         }
-        row_accumulate<D, G, M>(src[u], p, o, osub);
       }
     };
 #pragma unroll 1
-    for (int vb = 0; vb < NB; vb += 2) {
-      accum(vb, buf0);
-      if (vb + 2 < NB) issue(NB + vb + 2, buf0);
-      accum(vb + 1, buf1);
-      if (vb + 3 < NB) issue(NB + vb + 3, buf1);
+    for (int k = 0; k < NBV; k += 2) {
+      accum(k, vb0);
+      if (k + 2 < NBV) issue_v(k + 2, vb0);
+      accum(k + 1, vb1);
+      if (k + 3 < NBV) issue_v(k + 3, vb1);
     }
     __builtin_amdgcn_wave_barrier();
   }
@@ -393,21 +465,21 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(-GE::OFF, osub[h], o[h][e]);
+      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(-GE::OFF, osub[h], o[h][e]);
   }
   // ---- wave partial: sum the row groups, then merge the four waves through LDS
 #pragma unroll
-  for (int st = LPR; st < 64; st <<= 1) {
+  for (int st = LPRV; st < 64; st <<= 1) {
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[h][e] += __shfl_xor(o[h][e], st);
+      for (int e = 0; e < EV; ++e) o[h][e] += __shfl_xor(o[h][e], st);
   }
-  if (lane < LPR) {
+  if (lane < LPRV) {
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) sm_o[(wave * G + h) * D + lane * EPL + e] = o[h][e];
+      for (int e = 0; e < EV; ++e) sm_o[(wave * G + h) * D + lane * EV + e] = o[h][e];
   }
   if (lane == 0) {
 #pragma unroll
@@ -423,7 +495,7 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
     float acc = 0.f;
 #pragma unroll
     for (int w = 0; w < NWAVE; ++w) acc = fmaf(__builtin_amdgcn_exp2f((sm_ml[w * 16 + h] - mb) * LOG2E), sm_o[w * G * D + i], acc);
-    st_dev(po + i, acc);
+    po[i] = acc;
   }
   if (t < G) {
     float mb = sm_ml[t];
@@ -433,22 +505,21 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
 #pragma unroll
     for (int w = 0; w < NWAVE; ++w) ll = fmaf(__builtin_amdgcn_exp2f((sm_ml[w * 16 + t] - mb) * LOG2E), sm_ml[w * 16 + 8 + t], ll);
     float* pm = a.part_ml + ((size_t)((b * a.Hkv + kvh) * a.S + s) * 2) * G;
-    st_dev(pm + t, mb);
-    st_dev(pm + G + t, ll);
+    pm[t] = mb;
+    pm[G + t] = ll;
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores have completed
 }
 
 template <int D, int G, bool BF16>
-__global__ __launch_bounds__(ATTN_THREADS) void k_attn_tiered(const AttnArgs a) {
+__global__ __launch_bounds__(ATTN_THREADS) TKV_WPE void k_attn_tiered(const AttnArgs a) {
   constexpr int GP = GPad<G>::v;
   __shared__ __attribute__((aligned(16))) float pbuf[NWAVE * 64 * GP];
   __shared__ float sm_o[NWAVE * G * D];
   __shared__ float sm_ml[NWAVE * 16];
-  __shared__ float sm_fin[16];
-  __shared__ int sm_ticket;
-  const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, t = threadIdx.x;
-  const int nF = a.cnt[b * CNT_N + C_NF], nQ = a.cnt[b * CNT_N + C_NQ];
+  const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  int nF, nQ;
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
   const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = cf + cq;
   if (s >= ns) return;
   if (s < cf) {
@@ -459,63 +530,75 @@ __global__ __launch_bounds__(ATTN_THREADS) void k_attn_tiered(const AttnArgs a) 
     if (a.t2fmt == 0) attn_block<D, G, Q_INT8, BF16>(a, sm_o, sm_ml, pbuf, b, kvh, s, min(TB, nQ - j0), a.q_loc + (size_t)b * a.Nmax + j0);
     else attn_block<D, G, Q_INT4, BF16>(a, sm_o, sm_ml, pbuf, b, kvh, s, min(TB, nQ - j0), a.q_loc + (size_t)b * a.Nmax + j0);
   }
-  // ---- the last workgroup of this (b, kvh) merges the split partials
-  __syncthreads();
-  if (t == 0) sm_ticket = __hip_atomic_fetch_add(&a.counter[b * a.Hkv + kvh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (sm_ticket != ns - 1) return;
-  const float* pm = a.part_ml + ((size_t)(b * a.Hkv + kvh) * a.S * 2) * G;
-  const float* pob = a.part_o + ((size_t)(b * a.Hkv + kvh) * a.S * G) * D;
-  if (t < G) {
-    float mg = -INFINITY;
-    for (int k = 0; k < ns; ++k) mg = fmaxf(mg, ld_dev(pm + (size_t)k * 2 * G + t));
-    float lg = 0.f;
-    for (int k = 0; k < ns; ++k)
-      lg = fmaf(ld_dev(pm + (size_t)k * 2 * G + G + t), __builtin_amdgcn_exp2f((ld_dev(pm + (size_t)k * 2 * G + t) - mg) * LOG2E), lg);
-    const float il = 1.0f / lg;
-    sm_fin[t] = mg; sm_fin[8 + t] = il;
-    float* mf = a.ml_final + ((size_t)b * a.Hq + kvh * G + t) * 2;
-    mf[0] = mg; mf[1] = il;
-  }
-  if (t == 0) a.counter[b * a.Hkv + kvh] = 0;
-  __syncthreads();
-  for (int i = t; i < G * D; i += ATTN_THREADS) {
-    const int h = i / D;
-    const float mg = sm_fin[h];
-    float acc = 0.f;
-    for (int k = 0; k < ns; ++k)
-      acc = fmaf(__builtin_amdgcn_exp2f((ld_dev(pm + (size_t)k * 2 * G + h) - mg) * LOG2E), ld_dev(pob + (size_t)k * G * D + i), acc);
-    acc *= sm_fin[8 + h];
-    const size_t oi = ((size_t)b * a.Hq + kvh * G + h) * D + (i % D);
-    if (a.out_bf16) ((uint16_t*)a.out)[oi] = f32_to_bf16(acc);
-    else ((float*)a.out)[oi] = acc;
-  }
 }
 
-// ---- scores: one list entry per thread -------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_attn_scores(const AttnArgs a) {
+// ---- finish: global softmax statistics, scores, output ------------------------------------------------------
+constexpr int FIN_LDS_FLOATS = 8192;   // room for the (m, l) of all splits of one sequence: Hkv * S * 2 * G floats
+
+template <int D, int G>
+__global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_tiles) {
+  __shared__ float sm_pm[FIN_LDS_FLOATS];
   __shared__ float M[128], IL[128];
   const int t = threadIdx.x, b = blockIdx.y;
-  const int nF = a.cnt[b * CNT_N + C_NF], nQ = a.cnt[b * CNT_N + C_NQ];
-  const int cf = (nF + TB - 1) / TB;
-  const int j = blockIdx.x * 256 + t;
-  if ((int)blockIdx.x * 256 >= cf * TB + nQ) return;
+  int nF, nQ;
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = cf + cq;
+  const bool is_tile = (int)blockIdx.x < n_tiles;
+  if (is_tile && (int)blockIdx.x * 256 >= cf * TB + nQ) return;
+  // (m, l) of every split of this sequence: part_ml[b][kvh][s][2][G], s < ns
+  const float* pmb = a.part_ml + (size_t)b * a.Hkv * a.S * 2 * G;
+  const int per_kvh = ns * 2 * G;
+  const bool in_lds = a.Hkv * per_kvh <= FIN_LDS_FLOATS;
+  if (in_lds) {
+    for (int i = t; i < a.Hkv * per_kvh; i += 256) {
+      const int kvh = i / per_kvh, rem = i % per_kvh;
+      sm_pm[i] = pmb[(size_t)kvh * a.S * 2 * G + rem];
+    }
+    __syncthreads();
+  }
   if (t < a.Hq) {
-    M[t] = a.ml_final[((size_t)b * a.Hq + t) * 2];
-    IL[t] = a.ml_final[((size_t)b * a.Hq + t) * 2 + 1];
+    const int kvh = t / G, g = t % G;
+    const float* src = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S * 2 * G);
+    float mm = -INFINITY;
+    for (int k = 0; k < ns; ++k) mm = fmaxf(mm, src[k * 2 * G + g]);
+    float ll = 0.f;
+    for (int k = 0; k < ns; ++k) ll = fmaf(src[k * 2 * G + G + g], __builtin_amdgcn_exp2f((src[k * 2 * G + g] - mm) * LOG2E), ll);
+    M[t] = mm;
+    IL[t] = 1.0f / ll;
   }
   __syncthreads();
-  int pos = -1;
-  if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
-  else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
-  if (pos < 0) return;
-  // alpha summed over the query heads in the fixed order kv head, then group member
-  float acc = 0.f;
-  for (int hq = 0; hq < a.Hq; ++hq) {
-    const float x = a.xs[((size_t)b * a.Hq + hq) * a.xs_stride + j];
-    acc += __builtin_amdgcn_exp2f((x - M[hq]) * LOG2E) * IL[hq];
+  if (is_tile) {
+    // one list entry per thread: alpha summed over the query heads in the fixed order kv head, then group member
+    const int j = blockIdx.x * 256 + t;
+    int pos = -1;
+    if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
+    else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
+    if (pos < 0) return;
+    float acc = 0.f;
+#pragma unroll 8
+    for (int hq = 0; hq < a.Hq; ++hq) {
+      const float x = a.xs[((size_t)b * a.Hq + hq) * a.xs_stride + j];
+      acc += __builtin_amdgcn_exp2f((x - M[hq]) * LOG2E) * IL[hq];
+    }
+    a.score[(size_t)b * a.Nmax + pos] += a.score_scale * acc;
+  } else {
+    const int kvh = blockIdx.x - n_tiles;
+    const float* pm = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S * 2 * G);
+    const float* pob = a.part_o + ((size_t)(b * a.Hkv + kvh) * a.S * G) * D;
+    for (int i = t; i < G * D; i += 256) {
+      const int h = i / D, hq = kvh * G + h;
+      const float mg = M[hq];
+      float acc = 0.f;
+#pragma unroll 4
+      for (int k = 0; k < ns; ++k)
+        acc = fmaf(__builtin_amdgcn_exp2f((pm[k * 2 * G + h] - mg) * LOG2E), pob[(size_t)k * G * D + i], acc);
+      acc *= IL[hq];
+      const size_t oi = ((size_t)b * a.Hq + hq) * D + (i % D);
+      if (a.out_bf16) ((uint16_t*)a.out)[oi] = f32_to_bf16(acc);
+      else ((float*)a.out)[oi] = acc;
+    }
   }
-  a.score[(size_t)b * a.Nmax + pos] += a.score_scale * acc;
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------------
@@ -523,6 +606,12 @@ template <int D, int G, bool BF16>
 static hipError_t run_tiered(const AttnArgs& a, hipStream_t st) {
   dim3 grid(a.S, a.Hkv, a.B);
   hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(ATTN_THREADS), 0, st, a);
+  return hipGetLastError();
+}
+template <int D, int G, bool BF16>
+static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
+  const int tiles = (a.S * TB + 255) / 256;
+  hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hkv, a.B), dim3(256), 0, st, a, tiles);
   return hipGetLastError();
 }
 
@@ -546,10 +635,10 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStr
   if (D == 64 && !bf16) { TKV_DISPATCH_G(run_tiered, 64, false, a, st) }
   return hipErrorInvalidValue;
 }
-hipError_t launch_attn_scores(const AttnArgs& a, hipStream_t st) {
-  const int tiles = (a.S * TB + 255) / 256;
-  hipLaunchKernelGGL(k_attn_scores, dim3(tiles, a.B), dim3(256), 0, st, a);
-  return hipGetLastError();
+hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {
+  if (D == 128) { TKV_DISPATCH_G(run_finish, 128, true, a, st) }
+  if (D == 64) { TKV_DISPATCH_G(run_finish, 64, true, a, st) }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace tkv

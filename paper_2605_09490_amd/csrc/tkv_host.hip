@@ -41,8 +41,7 @@ struct tkv_cache {
   std::vector<int64_t> ntier;      // [4] summed over sequences
   bool plan_pending = false;
   // attention scratch
-  float* xs = nullptr; float* part_ml = nullptr; float* part_o = nullptr; float* ml_final = nullptr;
-  int* counter = nullptr;
+  float* xs = nullptr; float* part_ml = nullptr; float* part_o = nullptr;
   int S_alloc = 0, xs_stride = 0;
   // T1 store and transport
   char* hstore = nullptr;
@@ -256,7 +255,6 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
   ok = ok && dalloc(c, c->part_ml, (size_t)B * Hkv * c->S_alloc * 2 * G);
   ok = ok && dalloc(c, c->part_o, (size_t)B * Hkv * c->S_alloc * G * D);
-  ok = ok && dalloc(c, c->ml_final, (size_t)B * v.Hq * 2) && dalloc(c, c->counter, (size_t)B * Hkv);
   c->tok_bytes = (size_t)Hkv * 2 * D * c->es;
   c->bounce_bytes = cfg->bounce_bytes ? (size_t)cfg->bounce_bytes : ((size_t)64 << 20);
   if (c->bounce_bytes < RING * c->tok_bytes) c->bounce_bytes = RING * c->tok_bytes;
@@ -284,8 +282,6 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   for (int i = 0; i < RING && evok; ++i) evok = hipEventCreateWithFlags(&c->ev_piece[i], hipEventDisableTiming) == hipSuccess;
   for (int l = 0; l < L && evok; ++l) evok = hipEventCreateWithFlags(&c->ev_ready[l], hipEventDisableTiming) == hipSuccess;
   if (!evok) return die(TKV_EDEVICE, "tkv_create: hipEventCreate failed");
-  if (hipMemsetAsync(c->counter, 0, (size_t)B * Hkv * sizeof(int), nullptr) != hipSuccess)
-    return die(TKV_EDEVICE, "tkv_create: hipMemset failed");
   if (launch_init_state(v, nullptr) != hipSuccess || hipStreamSynchronize(nullptr) != hipSuccess)
     return die(TKV_EDEVICE, "tkv_create: state initialisation failed");
   *out = c;
@@ -368,7 +364,8 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   a.q = q; a.out = out;
   a.f_loc = use_old ? v.f_loc_old : v.f_loc; a.f_pos = v.f_pos; a.q_loc = v.q_loc; a.q_pos = v.q_pos;
   a.cnt = v.cnt; a.score = v.score; a.xs = c->xs; a.part_ml = c->part_ml; a.part_o = c->part_o;
-  a.ml_final = c->ml_final; a.counter = c->counter; a.q_es = c->es;
+  a.q_es = c->es;
+  if (v.B <= ATTN_ARG_SEQS) for (int b = 0; b < v.B; ++b) { a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b]; }
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capF; a.cap2 = v.cap2;
   a.S = S; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
@@ -380,7 +377,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   }
   HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st));
   if (pe) HIPCHK(c, hipEventRecord(pe->b, st));
-  HIPCHK(c, launch_attn_scores(a, st));
+  HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
   return TKV_OK;
 }
 

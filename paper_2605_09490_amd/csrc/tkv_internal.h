@@ -21,10 +21,17 @@ enum Cnt : int {
   CNT_N = 28
 };
 
-constexpr int TOK_PER_BLOCK = 256;  // list entries one attention block owns (split granularity)
-constexpr int ATTN_THREADS = 256;
+#ifndef TKV_TOK_PER_BLOCK
+#define TKV_TOK_PER_BLOCK 256
+#endif
+constexpr int TOK_PER_BLOCK = TKV_TOK_PER_BLOCK;  // list entries one attention workgroup owns (split granularity)
+#ifndef TKV_ATTN_THREADS
+#define TKV_ATTN_THREADS 256
+#endif
+constexpr int ATTN_THREADS = TKV_ATTN_THREADS;
 constexpr int PLAN_THREADS = 1024;
 constexpr int MAX_G = 8;
+constexpr int ATTN_ARG_SEQS = 64;    // list lengths travel as kernel arguments up to this batch size
 
 // Device view of one cache, passed by value to the tier-management kernels.
 struct DevView {
@@ -72,15 +79,14 @@ struct AttnArgs {
   float* xs;        // [B][Hkv][G][xs_stride] scaled logits by list index (F entries, then Q entries from f_pad)
   float* part_ml;   // [B][Hkv][S][2][G]  (m, l) of each split
   float* part_o;    // [B][Hkv][S][G][D]
-  float* ml_final;  // [B][Hq][2] global (m, 1/l) of every head, written by the last workgroup of each (b, kv head)
-  int* counter;     // [B][Hkv] arrival counters of the split workgroups; zero between launches
   int B, Hq, Hkv, Nmax, capF, cap2, S, xs_stride, cb, sb, t2fmt, out_bf16, q_es;
   float softmax_scale, score_scale;
+  int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
 };
 
 // launchers (defined in the .hip files)
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st);
-hipError_t launch_attn_scores(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
 hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStream_t st);
