@@ -224,17 +224,23 @@ def main():
     other_mode = "wait" if args.mode == "lazy" else "lazy"
     extra = {}
     if not args.no_twin:
-        twin = run_job(cfg, twin_pol, args.mode, args.steps, warmup, 0, "all-T0 twin")
-        twin.pop("gpu").close(); twin.pop("wl")
-        log(f"[bench] twin: {twin['ms_per_step']:.3f} ms/step")
-        alt = run_job(cfg, pol, other_mode, args.steps, warmup, 0, f"tiered-{other_mode}")
-        alt.pop("gpu").close(); alt.pop("wl")
-        log(f"[bench] {other_mode}: {alt['ms_per_step']:.3f} ms/step")
+        # The overhead is a difference of two wall times, and the clock of a busy GPU drifts between jobs: the three
+        # job kinds are therefore run in turn, twice, and compared on the fastest run of each kind.
+        runs = {args.mode: [main_res["wall_s"]], "twin": [], other_mode: []}
+        for rnd in range(2):
+            for kind in ("twin", other_mode, args.mode):
+                if kind == args.mode and rnd == 1:
+                    continue
+                r = run_job(cfg, twin_pol if kind == "twin" else pol, args.mode if kind == "twin" else kind,
+                            args.steps, warmup, 0, kind)
+                r.pop("gpu").close(); r.pop("wl")
+                runs[kind].append(r["wall_s"])
+                log(f"[bench] {kind}: {r['ms_per_step']:.3f} ms/step")
+        best = {k: min(v) for k, v in runs.items()}
         extra = {
-            "prefetch_overhead_pct": round(100.0 * (main_res["wall_s"] - twin["wall_s"]) / twin["wall_s"], 2),
-            f"prefetch_overhead_pct_{other_mode}": round(100.0 * (alt["wall_s"] - twin["wall_s"]) / twin["wall_s"], 2),
-            "twin_ms_per_step": round(twin["ms_per_step"], 4),
-            f"{other_mode}_ms_per_step": round(alt["ms_per_step"], 4),
+            "prefetch_overhead_pct": round(100.0 * (best[args.mode] - best["twin"]) / best["twin"], 2),
+            f"prefetch_overhead_pct_{other_mode}": round(100.0 * (best[other_mode] - best["twin"]) / best["twin"], 2),
+            "ms_per_step_runs": {k: [round(w * 1e3 / args.steps, 4) for w in v] for k, v in runs.items()},
         }
     value = main_res["bytes"] / main_res["wall_s"] / 1e9
     kernel_GBps = main_res["kernel_bytes_per_launch"] / (main_res["kernel_avg_us"] * 1e-6) / 1e9 if main_res.get("kernel_avg_us") else None
@@ -252,7 +258,7 @@ def main():
         "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
         "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(kernel_GBps / HBM_PEAK_GBPS, 4) if kernel_GBps else None,
-                     "traffic": None, "kernel": "k_attn_split", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
+                     "traffic": None, "kernel": "k_attn_tiered", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
                      "algorithmic_bytes_per_launch": int(main_res.get("kernel_bytes_per_launch", 0)),
                      "launches_timed": main_res.get("kernel_launches")},
         "cpu_baseline": cpu,

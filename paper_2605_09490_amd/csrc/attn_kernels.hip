@@ -12,10 +12,10 @@
 //                             LDS, per-lane fp32 output slices.
 //                 The four waves are merged through LDS into one split partial (m, l, o[G][D]); the scaled
 //                 logits go to a scratch array.
-//   attn_finish : grid (tiles + Hkv, B).  Every workgroup first merges the (m, l) of all splits of its sequence
+//   attn_finish : grid (64-entry tiles + Hq, B).  Every workgroup first merges the (m, l) of all splits of its sequence
 //                 into the global (m, 1/l) of every query head.  Tile workgroups then turn the stored logits
 //                 into softmax weights, summed over all query heads in a fixed order, into score[b, pos]; the
-//                 Hkv remaining workgroups merge the split outputs into out[b, kvh*G .. kvh*G+G).
+//                 Hq remaining workgroups merge the split outputs of one query head each into out[b, hq].
 // The split boundaries and the fp32 summation order depend only on the lists' logical order, never on whether a
 // row lives in the HBM pool or the staging buffer (both are one slot space), which is what makes T1 placement
 // bit-invisible (Prop. 1).  No MFMA: the path is bound by HBM, and the per-row work is G dot products.
@@ -545,7 +545,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
   const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = cf + cq;
   const bool is_tile = (int)blockIdx.x < n_tiles;
-  if (is_tile && (int)blockIdx.x * 256 >= cf * TB + nQ) return;
+  if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
   // (m, l) of every split of this sequence: part_ml[b][kvh][s][2][G], s < ns
   const float* pmb = a.part_ml + (size_t)b * a.Hkv * a.S * 2 * G;
   const int per_kvh = ns * 2 * G;
@@ -569,34 +569,54 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   }
   __syncthreads();
   if (is_tile) {
-    // one list entry per thread: alpha summed over the query heads in the fixed order kv head, then group member
-    const int j = blockIdx.x * 256 + t;
+    // 64 list entries per workgroup; thread (e, hg) sums the softmax weights of kv heads hg, hg+4, ... (all G members
+    // of each), then the four partial sums of an entry are added in the fixed order hg = 0, 1, 2, 3
+    const int e = t & 63, hg = t >> 6;
+    const int j = blockIdx.x * 64 + e;
     int pos = -1;
     if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
     else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
-    if (pos < 0) return;
+    float acc = 0.f;
+    if (pos >= 0) {
+      for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
+        float x[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)b * a.Hq + kvh * G + g) * a.xs_stride + j];
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[kvh * G + g]) * LOG2E) * IL[kvh * G + g];
+      }
+    }
+    __syncthreads();          // sm_pm is free now: reuse it for the partial sums
+    sm_pm[hg * 64 + e] = acc;
+    __syncthreads();
+    if (hg == 0 && pos >= 0) {
+      const float tot = ((sm_pm[e] + sm_pm[64 + e]) + sm_pm[128 + e]) + sm_pm[192 + e];
+      a.score[(size_t)b * a.Nmax + pos] += a.score_scale * tot;
+    }
+  } else {
+    // one workgroup per query head: thread (d, sg) sums the splits sg, sg+NSG, ... of output element d, then the NSG
+    // partial sums are added in the fixed order sg = 0, 1, ...
+    constexpr int NSG = 256 / D;
+    const int hq = blockIdx.x - n_tiles, kvh = hq / G, h = hq % G;
+    const int d = t % D, sg = t / D;
+    const float* pm = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S * 2 * G);
+    const float* pob = a.part_o + ((size_t)(b * a.Hkv + kvh) * a.S * G) * D + h * D + d;
+    const float mg = M[hq];
     float acc = 0.f;
 #pragma unroll 8
-    for (int hq = 0; hq < a.Hq; ++hq) {
-      const float x = a.xs[((size_t)b * a.Hq + hq) * a.xs_stride + j];
-      acc += __builtin_amdgcn_exp2f((x - M[hq]) * LOG2E) * IL[hq];
-    }
-    a.score[(size_t)b * a.Nmax + pos] += a.score_scale * acc;
-  } else {
-    const int kvh = blockIdx.x - n_tiles;
-    const float* pm = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S * 2 * G);
-    const float* pob = a.part_o + ((size_t)(b * a.Hkv + kvh) * a.S * G) * D;
-    for (int i = t; i < G * D; i += 256) {
-      const int h = i / D, hq = kvh * G + h;
-      const float mg = M[hq];
-      float acc = 0.f;
-#pragma unroll 4
-      for (int k = 0; k < ns; ++k)
-        acc = fmaf(__builtin_amdgcn_exp2f((pm[k * 2 * G + h] - mg) * LOG2E), pob[(size_t)k * G * D + i], acc);
-      acc *= IL[hq];
-      const size_t oi = ((size_t)b * a.Hq + hq) * D + (i % D);
-      if (a.out_bf16) ((uint16_t*)a.out)[oi] = f32_to_bf16(acc);
-      else ((float*)a.out)[oi] = acc;
+    for (int k = sg; k < ns; k += NSG)
+      acc = fmaf(__builtin_amdgcn_exp2f((pm[k * 2 * G + h] - mg) * LOG2E), pob[(size_t)k * G * D], acc);
+    __syncthreads();          // every thread has read what it needs from sm_pm
+    sm_pm[sg * D + d] = acc;
+    __syncthreads();
+    if (sg == 0) {
+      float tot = sm_pm[d];
+#pragma unroll
+      for (int g2 = 1; g2 < NSG; ++g2) tot += sm_pm[g2 * D + d];
+      tot *= IL[hq];
+      const size_t oi = ((size_t)b * a.Hq + hq) * D + d;
+      if (a.out_bf16) ((uint16_t*)a.out)[oi] = f32_to_bf16(tot);
+      else ((float*)a.out)[oi] = tot;
     }
   }
 }
@@ -610,8 +630,8 @@ static hipError_t run_tiered(const AttnArgs& a, hipStream_t st) {
 }
 template <int D, int G, bool BF16>
 static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
-  const int tiles = (a.S * TB + 255) / 256;
-  hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hkv, a.B), dim3(256), 0, st, a, tiles);
+  const int tiles = (a.S * TB + 63) / 64;
+  hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, a, tiles);
   return hipGetLastError();
 }
 

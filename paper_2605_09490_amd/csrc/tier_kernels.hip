@@ -74,6 +74,30 @@ __global__ void k_append_rows(DevView v, int layer, const char* __restrict__ k, 
   *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + src);
 }
 
+// one new token for every layer at once: k, v [L][B][1][Hkv][D]
+__global__ void k_append_step(DevView v, const char* __restrict__ k, const char* __restrict__ vv, int pos) {
+  const int row_bytes = v.D * v.es, cpr = row_bytes / 16;
+  const long long total = (long long)v.L * v.B * v.Hkv * cpr;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cpr);
+  long long r = i / cpr;
+  const int kvh = (int)(r % v.Hkv); r /= v.Hkv;
+  const int b = (int)(r % v.B);
+  const int layer = (int)(r / v.B);
+  const int slot = v.loc[(size_t)b * v.Nmax + pos];
+  if (slot < 0 || slot >= v.capF) return;
+  const size_t dst = ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capF + slot) * row_bytes + (size_t)c * 16;
+  *(u32x4*)(v.fpK + dst) = *(const u32x4*)(k + (size_t)i * 16);
+  *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + (size_t)i * 16);
+}
+hipError_t launch_append_step(const DevView& v, const void* k, const void* v_, int pos, hipStream_t st) {
+  hipLaunchKernelGGL(k_append_assign, dim3(v.B), dim3(256), 0, st, v, pos, 1);
+  const long long total = (long long)v.L * v.B * v.Hkv * (v.D * v.es / 16);
+  hipLaunchKernelGGL(k_append_step, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, (const char*)k, (const char*)v_, pos);
+  return hipGetLastError();
+}
+
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new, bool assign,
                          hipStream_t st) {
   if (assign) hipLaunchKernelGGL(k_append_assign, dim3(v.B), dim3(256), 0, st, v, pos0, n_new);

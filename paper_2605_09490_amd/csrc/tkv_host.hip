@@ -389,6 +389,23 @@ tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, c
   const size_t kv_stride = (size_t)v.B * v.Hkv * v.D * v.es;
   const size_t q_stride = (size_t)v.B * v.Hq * v.D * v.es;
   const size_t o_stride = (size_t)v.B * v.Hq * v.D * (c->cfg.out_dtype == TKV_BF16 ? 2 : 4);
+  // all layers are at the same length here, so the new token's rows of every layer go in with one launch
+  const int n = common_length(c);
+  if (n >= 0 && n == c->n_assigned && !c->plan_pending) {
+    if (n + 1 > c->cfg.max_tokens) return fail(c, TKV_ECAPACITY, "tkv_decode_step: %d + 1 exceeds max_tokens %d", n, c->cfg.max_tokens);
+    for (int b = 0; b < v.B; ++b)
+      if (c->free0[b] < 1) return fail(c, TKV_ECAPACITY, "tkv_decode_step: HBM pool of sequence %d is full", b);
+    HIPCHK(c, launch_append_step(v, k_all, v_all, n, (hipStream_t)hip_stream));
+    for (int b = 0; b < v.B; ++b) { c->free0[b] -= 1; c->nF[b] += 1; }
+    c->ntier[0] += v.B;
+    c->n_assigned += 1;
+    for (int l = 0; l < v.L; ++l) c->len[l] = n + 1;
+    for (int l = 0; l < v.L; ++l) {
+      tkv_status s = tkv_attend_and_score(c, l, (const char*)q_all + l * q_stride, (char*)out_all + l * o_stride, hip_stream);
+      if (s != TKV_OK) return s;
+    }
+    return TKV_OK;
+  }
   for (int l = 0; l < v.L; ++l) {
     tkv_status s = tkv_append(c, l, (const char*)k_all + l * kv_stride, (const char*)v_all + l * kv_stride, 1, hip_stream);
     if (s != TKV_OK) return s;

@@ -89,6 +89,7 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStr
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
+hipError_t launch_append_step(const DevView& v, const void* k, const void* v_, int pos, hipStream_t st);
 hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStream_t st);
 hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st);
 hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st);

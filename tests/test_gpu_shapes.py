@@ -1,0 +1,90 @@
+"""GPU parity at the benchmark's shapes: the per-layer launch configuration depends on (batch, heads, head_dim,
+context, tier mix), not on the layer count, so these cases keep the full per-layer shape of the BASELINE configs and
+cut the number of layers (and, for the production-batch config, the number of sequences) to what the CPU oracle
+finishes in seconds.  Every output element and every score is compared, not a sample."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from tkv_synth import CONFIGS, small_config
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_shape(cfg, mode, steps_before=1, steps_after=2):
+    from gpu_common import Pair, assert_out_close, assert_scores_close, to_f64
+    print(f"[case] {cfg.name}-shaped L={cfg.n_layers} B={cfg.batch} Hq={cfg.n_q_heads} Hkv={cfg.n_kv_heads} D={cfg.head_dim} "
+          f"ctx={cfg.context} t2={cfg.t2_format} mode={mode}", flush=True)
+    p = Pair(cfg, prefetch_mode=mode)
+    L = cfg.n_layers
+    k_all, v_all, q_all = p.wl.decode_inputs(0, steps_before + steps_after)
+    calls, worst = 0, 0.0
+
+    def step(s):
+        nonlocal calls, worst
+        out = p.gpu.decode_step(k_all[s], v_all[s], q_all[s])
+        for l in range(L):
+            p.orc.append(l, to_f64(k_all[s, l]), to_f64(v_all[s, l]))
+            ref = p.orc.attend_and_score(l, to_f64(q_all[s, l]))
+            worst = max(worst, assert_out_close(to_f64(out[l]), ref, cfg.kv_dtype, f"step {s} layer {l}"))
+            calls += 1
+
+    for s in range(steps_before):
+        step(s)
+    n = p.gpu.layer_length(0)
+    p.gpu.classify(cfg.policy_ppm)
+    plan = p.gpu.get_pending_tiers()[:, :n]
+    want = p.orc.classify(cfg.policy_ppm, score_f32=p.gpu.get_scores())[:, :n]
+    assert np.array_equal(plan, want)
+    p.gpu.migrate()
+    p.orc.migrate()
+    for s in range(steps_before, steps_before + steps_after):
+        step(s)
+    ss = 1.0 / (cfg.n_layers * cfg.n_q_heads)
+    n = p.gpu.layer_length(0)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, calls * cfg.n_q_heads * ss)
+    st = p.gpu.get_stats()
+    print(f"[case] worst output error {worst:.2e} of the head max-norm; tiers {st['tier_count']}", flush=True)
+    assert st["tier_count"][1] > 0 and st["tier_count"][2] > 0
+    p.close()
+
+
+def test_14b_shape():
+    _run_shape(dataclasses.replace(CONFIGS["14b"], n_layers=2, decode_steps=3), "lazy")
+
+
+def test_7b_shape():
+    _run_shape(dataclasses.replace(CONFIGS["7b"], n_layers=2, decode_steps=3), "wait")
+
+
+def test_32b_shape():
+    _run_shape(dataclasses.replace(CONFIGS["32b"], n_layers=1, decode_steps=3), "lazy")
+
+
+def test_prod_shape_subset_of_sequences():
+    # 16384-token context, int4-g32 T2; 4 of the 64 sequences (sequences are independent units of work)
+    _run_shape(dataclasses.replace(CONFIGS["prod"], n_layers=1, batch=4, decode_steps=2), "lazy", steps_after=1)
+
+
+def test_decode_step_equals_per_layer_calls():
+    """tkv_decode_step is tkv_append + tkv_attend_and_score per layer: same bits."""
+    from gpu_common import Pair
+    cfg = small_config(n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=500,
+                       decode_steps=4)
+    a, b = Pair(cfg), Pair(cfg)
+    k_all, v_all, q_all = a.wl.decode_inputs(0, 4)
+    for s in range(4):
+        oa = a.gpu.decode_step(k_all[s], v_all[s], q_all[s])
+        for l in range(cfg.n_layers):
+            b.gpu.append(l, k_all[s, l], v_all[s, l])
+            ob = b.gpu.attend_and_score(l, q_all[s, l])
+            assert torch.equal(oa[l], ob)
+        if s == 1:
+            for p in (a, b):
+                p.gpu.classify(cfg.policy_ppm)
+                p.gpu.migrate()
+    assert np.array_equal(a.gpu.get_scores().view(np.uint32), b.gpu.get_scores().view(np.uint32))
+    assert np.array_equal(a.gpu.get_tiers(), b.gpu.get_tiers())
+    a.close(); b.close()
