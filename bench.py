@@ -19,6 +19,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the attention kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each
+# scaled by the same counter's reading for the library's plain row-copy kernel of known size (the context preload:
+# 134 217 728 bytes read and written per launch; FETCH_SIZE reads 1 per 2031 bytes, WRITE_SIZE 1 per KiB).
+# See profiles/attn_tiered_14b_hbm_traffic.txt.
+MEASURED_TRAFFIC = {"14b": {"fetch_bytes": 123_760_000, "write_bytes": 7_980_000}}
 LINK_PEAK_GBPS = 64.0       # PCIe Gen5 x16, one direction
 
 
@@ -258,7 +263,8 @@ def main():
         "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
         "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(kernel_GBps / HBM_PEAK_GBPS, 4) if kernel_GBps else None,
-                     "traffic": None, "kernel": "k_attn_tiered", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
+                     "traffic": (sum(MEASURED_TRAFFIC[cfg.name].values()) if cfg.name in MEASURED_TRAFFIC else None),
+                     "kernel": "k_attn_tiered", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
                      "algorithmic_bytes_per_launch": int(main_res.get("kernel_bytes_per_launch", 0)),
                      "launches_timed": main_res.get("kernel_launches")},
         "cpu_baseline": cpu,

@@ -19,6 +19,8 @@
 // The split boundaries and the fp32 summation order depend only on the lists' logical order, never on whether a
 // row lives in the HBM pool or the staging buffer (both are one slot space), which is what makes T1 placement
 // bit-invisible (Prop. 1).  No MFMA: the path is bound by HBM, and the per-row work is G dot products.
+#include <hip/hip_ext.h>
+
 #include "tkv_internal.h"
 
 namespace tkv {
@@ -39,6 +41,9 @@ static_assert(TPW % 64 == 0 && NTILE >= 1, "a wave works in tiles of 64 entries"
 #endif
 #ifndef TKV_UV
 #define TKV_UV 4      // V rows per batch and lane group (two batches are in flight)
+#endif
+#ifndef TKV_DEEP
+#define TKV_DEEP 0
 #endif
 #ifdef TKV_ATTN_WAVES_PER_EU
 #define TKV_WPE __attribute__((amdgpu_waves_per_eu(TKV_ATTN_WAVES_PER_EU, TKV_ATTN_WAVES_PER_EU)))
@@ -355,6 +360,88 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
     for (int e = 0; e < EV; ++e) o[h][e] = 0.f;
   }
 
+  // Two schedules for the tile loop.  DEEP keeps a whole tile's K rows and V rows in flight (128 registers of
+  // buffers, two waves per SIMD) and fetches the next tile's rows while the current one is being computed; the
+  // batched schedule keeps two small batches in flight and fits three or four waves per SIMD.
+  constexpr bool DEEP = (TKV_DEEP != 0) && (G <= 6) && (M != F_F32);
+  if constexpr (DEEP) {
+    KRow<D, M> kb[8];
+    VRow<D, M> vb[NITV];
+    int locs[NTILE];
+#pragma unroll
+    for (int tl = 0; tl < NTILE; ++tl) {
+      const int tb2 = wave * TPW + tl * 64;
+      locs[tl] = (tb2 + lane < ntok) ? loc_list[tb2 + lane] : -1;
+    }
+    auto issue_k_all = [&](int myloc) {
+#pragma unroll
+      for (int it = 0; it < 8; ++it) kb[it] = load_krow<D, M>(ks, __shfl(myloc, g8 * 8 + it), r8);
+    };
+    auto issue_v_all = [&](int myloc) {
+#pragma unroll
+      for (int it = 0; it < NITV; ++it) vb[it] = load_vrow<D, M>(vs, __shfl(myloc, gv * LPRV + it), rv);
+    };
+    issue_k_all(locs[0]);
+    issue_v_all(locs[0]);
+#pragma unroll
+    for (int tile = 0; tile < NTILE; ++tile) {
+      const int tbase = wave * TPW + tile * 64;
+      if (tbase >= ntok) break;                          // wave-uniform
+      const bool valid = tbase + lane < ntok;
+      float xt[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) xt[h] = 0.f;
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        float x[G];
+        row_logits<D, G, M, QBF>(kb[it], q, x);
+#pragma unroll
+        for (int h = 0; h < G; ++h) xt[h] = (r8 == it) ? x[h] : xt[h];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (tile + 1 < NTILE) issue_k_all(locs[tile + 1 < NTILE ? tile + 1 : tile]);   // out-of-range slots cost nothing
+      float corr[G];
+      {
+        const size_t xbase = ((size_t)(b * a.Hq + kvh * G)) * a.xs_stride + (size_t)s * TB + tbase + lane;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          const float x = valid ? xt[h] * a.softmax_scale : -INFINITY;
+          if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x;
+          const float tm = wave_max(x);
+          float mn;
+          if (tile == 0) { mn = tm; corr[h] = 0.f; }
+          else { mn = fmaxf(m_run[h], tm); corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E); }
+          const float p = valid ? __builtin_amdgcn_exp2f((x - mn) * LOG2E) : 0.f;
+          const float ps = wave_sum(p);
+          l_run[h] = (tile == 0) ? ps : fmaf(l_run[h], corr[h], ps);
+          m_run[h] = mn;
+          pbuf[lane * GP + h] = p;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (tile > 0) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          osub[h] *= corr[h];
+#pragma unroll
+          for (int e = 0; e < EV; ++e) o[h][e] *= corr[h];
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NITV; ++it) {
+        float p[GP];
+#pragma unroll
+        for (int c = 0; c < GP; c += 4) {
+          const float4 pv = *(const float4*)(pbuf + (gv * LPRV + it) * GP + c);
+          p[c] = pv.x; p[c + 1] = pv.y; p[c + 2] = pv.z; p[c + 3] = pv.w;
+        }
+        row_accumulate<D, G, M>(vb[it], p, o, osub);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (tile + 1 < NTILE) issue_v_all(locs[tile + 1 < NTILE ? tile + 1 : tile]);
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else {
 #pragma unroll
   for (int tile = 0; tile < NTILE; ++tile) {
     const int tbase = wave * TPW + tile * 64;          // first entry of the tile, relative to the workgroup
@@ -460,6 +547,7 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
       if (k + 3 < NBV) issue_v(k + 3, vb1);
     }
     __builtin_amdgcn_wave_barrier();
+  }
   }
   if constexpr (GE::IS_Q) {
 #pragma unroll
@@ -622,10 +710,12 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------------
+// With a pair of events the launch is timed by the dispatch's own begin / end timestamps (no bracket overhead).
 template <int D, int G, bool BF16>
-static hipError_t run_tiered(const AttnArgs& a, hipStream_t st) {
+static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   dim3 grid(a.S, a.Hkv, a.B);
-  hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(ATTN_THREADS), 0, st, a);
+  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(ATTN_THREADS), 0, st, ev0, ev1, 0, a);
+  else hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(ATTN_THREADS), 0, st, a);
   return hipGetLastError();
 }
 template <int D, int G, bool BF16>
@@ -648,11 +738,11 @@ static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
     default: return hipErrorInvalidValue;                   \
   }
 
-hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st) {
-  if (D == 128 && bf16) { TKV_DISPATCH_G(run_tiered, 128, true, a, st) }
-  if (D == 128 && !bf16) { TKV_DISPATCH_G(run_tiered, 128, false, a, st) }
-  if (D == 64 && bf16) { TKV_DISPATCH_G(run_tiered, 64, true, a, st) }
-  if (D == 64 && !bf16) { TKV_DISPATCH_G(run_tiered, 64, false, a, st) }
+hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (D == 128 && bf16) { TKV_DISPATCH_G(run_tiered, 128, true, a, st, ev0, ev1) }
+  if (D == 128 && !bf16) { TKV_DISPATCH_G(run_tiered, 128, false, a, st, ev0, ev1) }
+  if (D == 64 && bf16) { TKV_DISPATCH_G(run_tiered, 64, true, a, st, ev0, ev1) }
+  if (D == 64 && !bf16) { TKV_DISPATCH_G(run_tiered, 64, false, a, st, ev0, ev1) }
   return hipErrorInvalidValue;
 }
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {

@@ -373,10 +373,8 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   if (c->cfg.profile) {
     pe = next_pair(c->prof_events, c->prof_used);
     if (!pe) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
-    HIPCHK(c, hipEventRecord(pe->a, st));
   }
-  HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st));
-  if (pe) HIPCHK(c, hipEventRecord(pe->b, st));
+  HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
   return TKV_OK;
 }

@@ -85,7 +85,7 @@ struct AttnArgs {
 };
 
 // launchers (defined in the .hip files)
-hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st);
+hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
