@@ -169,15 +169,24 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_classify(DevView v, int n, Ppm
         if (shift == 48 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(key >> shift) & 255], 1);
       }
       __syncthreads();
-      if (t == 0) {
-        int kk = sh_k, d = 0;
-        for (; d < 255; ++d) {
-          const int c = hist[d];
-          if (kk < c) break;
-          kk -= c;
+      if (t < 64) {
+        // the digit whose bin holds rank sh_k: wave 0 scans the 256 bins, 4 per lane
+        const int kk = sh_k;
+        const int c0 = hist[4 * t], c1 = hist[4 * t + 1], c2 = hist[4 * t + 2], c3 = hist[4 * t + 3];
+        const int sum = c0 + c1 + c2 + c3;
+        int inc = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int u = __shfl_up(inc, o);
+          if (t >= o) inc += u;
         }
-        sh_k = kk;
-        sh_prefix = prefix | ((unsigned long long)d << shift);
+        const int exc = inc - sum;
+        if (kk >= exc && kk < inc) {     // exactly one lane (the bins hold at least sh_k + 1 keys in total)
+          int r = kk - exc, d = 4 * t;
+          if (r >= c0) { r -= c0; ++d; if (r >= c1) { r -= c1; ++d; if (r >= c2) { r -= c2; ++d; } } }
+          sh_k = r;
+          sh_prefix = prefix | ((unsigned long long)d << shift);
+        }
       }
       __syncthreads();
     }
@@ -404,63 +413,86 @@ __global__ void k_move_copy(DevView v) {
   *(u32x4*)(base + fp_row(v, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(base + fp_row(v, layer, b, kvh, src) + c * 16);
 }
 
-__device__ __forceinline__ float load_elem(const char* row, int d, int es) {
-  if (es == 4) return ((const float*)row)[d];
-  return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)row)[d] << 16);
+// 8 consecutive elements of a stored row as binary32
+__device__ __forceinline__ void load8(const char* row, int e0, int es, float (&x)[8]) {
+  if (es == 4) {
+    const float4 a = *(const float4*)(row + (size_t)e0 * 4), b = *(const float4*)(row + (size_t)e0 * 4 + 16);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  } else {
+    const u32x4 w = *(const u32x4*)(row + (size_t)e0 * 2);
+    const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      x[2 * c] = __builtin_bit_cast(float, u[c] << 16);
+      x[2 * c + 1] = __builtin_bit_cast(float, u[c] & 0xffff0000u);
+    }
+  }
 }
-__device__ __forceinline__ void store_elem(char* row, int d, int es, float x) {
-  if (es == 4) { ((float*)row)[d] = x; return; }
-  uint32_t u = __builtin_bit_cast(uint32_t, x);
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
   u += 0x7fffu + ((u >> 16) & 1u);
-  ((uint16_t*)row)[d] = (uint16_t)(u >> 16);
+  return u >> 16;
+}
+__device__ __forceinline__ void store8(char* row, int e0, int es, const float (&x)[8]) {
+  if (es == 4) {
+    *(float4*)(row + (size_t)e0 * 4) = make_float4(x[0], x[1], x[2], x[3]);
+    *(float4*)(row + (size_t)e0 * 4 + 16) = make_float4(x[4], x[5], x[6], x[7]);
+  } else {
+    u32x4 w;
+    w.x = bf16_rne_bits(x[0]) | (bf16_rne_bits(x[1]) << 16); w.y = bf16_rne_bits(x[2]) | (bf16_rne_bits(x[3]) << 16);
+    w.z = bf16_rne_bits(x[4]) | (bf16_rne_bits(x[5]) << 16); w.w = bf16_rne_bits(x[6]) | (bf16_rne_bits(x[7]) << 16);
+    *(u32x4*)(row + (size_t)e0 * 2) = w;
+  }
 }
 
-// -> T2: encode the current stored row.  One wave per (row, K|V); block = 256 threads = 4 rows.
-// grid (ceil(maxq/4), Hkv*2, L*B).  All arithmetic in binary32, round-to-nearest-even, true division.
+// -> T2: encode the current stored row.  D/8 lanes per row (8 elements each), 64/(D/8) rows per wave.
+// grid (pieces, Hkv*2, L*B).  All arithmetic in binary32, round-to-nearest-even, true division.
 __global__ __launch_bounds__(256) void k_move_quant(DevView v) {
   const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
-  const int lane = threadIdx.x & 63;
-  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, lpr = v.D / 8, rpw = 64 / lpr;
+  const int g = lane / lpr, r = lane % lpr;
+  const int j = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw + g;
   const int n = v.cnt[b * CNT_N + C_M02] + v.cnt[b * CNT_N + C_M12];
-  if (j >= n) return;
-  const int src = v.mvq_src[(size_t)b * v.Nmax + j], dst = v.mvq_dst[(size_t)b * v.Nmax + j];
-  if (src < 0 || src >= v.capF || dst < 0 || dst >= v.cap2) return;
-  const char* row = (which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, src);
+  const bool act = j < n;
+  int src = -1, dst = -1;
+  if (act) { src = v.mvq_src[(size_t)b * v.Nmax + j]; dst = v.mvq_dst[(size_t)b * v.Nmax + j]; }
+  const bool ok = act && src >= 0 && src < v.capF && dst >= 0 && dst < v.cap2;
+  float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (ok) load8((which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, src), r * 8, v.es, x);
+  float a = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(x[e]));
+  // absmax over the row (int8: all lanes of the row) or over the 32-element group (int4: 4 lanes)
+  const int span = v.t2fmt == 0 ? lpr : 4;
+  for (int o = 1; o < span; o <<= 1) a = fmaxf(a, __shfl_xor(a, o));
+  if (!ok) return;
   const size_t r2 = t2_row(v, layer, b, kvh, dst);
   char* codes = (which ? v.c2V : v.c2K) + r2 * v.cb;
   char* scales = (which ? v.s2V : v.s2K) + r2 * v.sb;
-  const int ept = v.D / 64;   // 1 or 2 elements per lane
-  float x[2] = {0.f, 0.f};
-  for (int e = 0; e < ept; ++e) x[e] = load_elem(row, lane * ept + e, v.es);
-  float a = fmaxf(fabsf(x[0]), fabsf(x[1]));
   if (v.t2fmt == 0) {
-    for (int o = 32; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
     const float scale = a / 127.0f;
-    for (int e = 0; e < ept; ++e) {
-      float r = 0.f;
-      if (scale > 0.f) r = fminf(fmaxf(rintf(x[e] / scale), -127.f), 127.f);
-      ((int8_t*)codes)[lane * ept + e] = (int8_t)(int)r;
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float q = 0.f;
+      if (scale > 0.f) q = fminf(fmaxf(rintf(x[e] / scale), -127.f), 127.f);
+      w[e >> 2] |= ((uint32_t)((int)q & 0xFF)) << (8 * (e & 3));
     }
-    if (lane == 0) *(float*)scales = scale;
+    *(uint2*)(codes + r * 8) = make_uint2(w[0], w[1]);
+    if (r == 0) *(float*)scales = scale;
   } else {
-    const int gl = 32 / ept;   // lanes per 32-element group
-    for (int o = gl >> 1; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
     const _Float16 sh = (_Float16)(a / 7.0f);
     const float scale = (float)sh;
-    int q[2] = {0, 0};
-    for (int e = 0; e < ept; ++e) {
-      float r = 0.f;
-      if (scale > 0.f) r = fminf(fmaxf(rintf(x[e] / scale), -7.f), 7.f);
-      q[e] = ((int)r) & 0xF;
+    uint32_t w = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float q = 0.f;
+      if (scale > 0.f) q = fminf(fmaxf(rintf(x[e] / scale), -7.f), 7.f);
+      w |= ((uint32_t)((int)q & 0xF)) << (4 * e);
     }
-    if (ept == 2) {
-      ((uint8_t*)codes)[lane] = (uint8_t)(q[0] | (q[1] << 4));
-    } else {
-      const int hi = __shfl_down(q[0], 1);
-      if ((lane & 1) == 0) ((uint8_t*)codes)[lane >> 1] = (uint8_t)(q[0] | (hi << 4));
-    }
-    if ((lane % gl) == 0) ((uint16_t*)scales)[lane / gl] = __builtin_bit_cast(uint16_t, sh);
+    *(uint32_t*)(codes + r * 4) = w;
+    if ((r & 3) == 0) ((uint16_t*)scales)[r >> 2] = __builtin_bit_cast(uint16_t, sh);
   }
 }
 
@@ -468,41 +500,44 @@ __global__ __launch_bounds__(256) void k_move_quant(DevView v) {
 __global__ __launch_bounds__(256) void k_move_dequant(DevView v) {
   const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
-  const int lane = threadIdx.x & 63;
-  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, lpr = v.D / 8, rpw = 64 / lpr;
+  const int g = lane / lpr, r = lane % lpr;
+  const int j = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw + g;
   const int n = v.cnt[b * CNT_N + C_M20] + v.cnt[b * CNT_N + C_M21];
   if (j >= n) return;
   const int src = v.mvd_src[(size_t)b * v.Nmax + j], dst = v.mvd_dst[(size_t)b * v.Nmax + j];
   if (src < 0 || src >= v.cap2 || dst < 0 || dst >= v.capF) return;
-  char* row = (which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, dst);
   const size_t r2 = t2_row(v, layer, b, kvh, src);
   const char* codes = (which ? v.c2V : v.c2K) + r2 * v.cb;
   const char* scales = (which ? v.s2V : v.s2K) + r2 * v.sb;
-  const int ept = v.D / 64;
-  for (int e = 0; e < ept; ++e) {
-    const int d = lane * ept + e;
-    float val;
-    if (v.t2fmt == 0) {
-      val = (float)((const int8_t*)codes)[d] * *(const float*)scales;
-    } else {
-      const uint8_t byte = ((const uint8_t*)codes)[d >> 1];
-      int c = (d & 1) ? (byte >> 4) : (byte & 0xF);
-      c = (c ^ 8) - 8;
-      const _Float16 sh = __builtin_bit_cast(_Float16, ((const uint16_t*)scales)[d >> 5]);
-      val = (float)c * (float)sh;
+  float x[8];
+  if (v.t2fmt == 0) {
+    const uint2 w = *(const uint2*)(codes + r * 8);
+    const float sc = *(const float*)scales;
+    const uint32_t u[2] = {w.x, w.y};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (float)(int)(int8_t)((u[e >> 2] >> (8 * (e & 3))) & 0xFF) * sc;
+  } else {
+    const uint32_t w = *(const uint32_t*)(codes + r * 4);
+    const float sc = (float)__builtin_bit_cast(_Float16, ((const uint16_t*)scales)[r >> 2]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = (int)(((w >> (4 * e)) & 0xF) ^ 8) - 8;
+      x[e] = (float)c * sc;
     }
-    store_elem(row, d, v.es, val);
   }
+  store8((which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, dst), r * 8, v.es, x);
 }
 
 hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st) {
   const int cpr = v.D * v.es / 16;
+  const int rpb = 4 * (64 / (v.D / 8));   // rows per workgroup of the encode / decode movers
   if (maxd > 0)
-    hipLaunchKernelGGL(k_move_dequant, dim3((maxd + 3) / 4, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+    hipLaunchKernelGGL(k_move_dequant, dim3((maxd + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
   if (max10 > 0)
     hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
   if (maxq > 0)
-    hipLaunchKernelGGL(k_move_quant, dim3((maxq + 3) / 4, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+    hipLaunchKernelGGL(k_move_quant, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
   return hipGetLastError();
 }
 

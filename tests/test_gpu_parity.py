@@ -286,3 +286,87 @@ def test_error_paths_leave_the_gpu_alone():
         p.gpu.migrate()
     assert e.value.status == tkv.TKV_ESTATE
     p.close()
+
+
+def test_allocator_failure_gives_enomem():
+    """An allocator callback that returns NULL part-way through tkv_create: TKV_ENOMEM, everything handed out so far
+    is given back, no handle."""
+    import ctypes as C
+    import paper_2605_09490_amd as tkv
+    from paper_2605_09490_amd import binding
+    lib = tkv.load_library()
+    held, calls = {}, {"n": 0, "freed": 0}
+
+    def dev_alloc(nbytes, _ctx):
+        calls["n"] += 1
+        if calls["n"] > 5:
+            return None
+        t = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda")
+        held[t.data_ptr()] = t
+        return t.data_ptr()
+
+    def dev_free(ptr, _ctx):
+        calls["freed"] += 1
+        held.pop(ptr, None)
+
+    def pin_alloc(nbytes, _ctx):
+        t = torch.empty(int(nbytes), dtype=torch.uint8, pin_memory=True)
+        held[t.data_ptr()] = t
+        return t.data_ptr()
+
+    cbs = (binding.ALLOC_FN(dev_alloc), binding.FREE_FN(dev_free), binding.ALLOC_FN(pin_alloc), binding.FREE_FN(dev_free))
+    cfg = binding.tkv_config()
+    cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens = 1, 1, 4, 2, 64, 128
+    cfg.kv_dtype, cfg.out_dtype, cfg.t2_format = binding.TKV_BF16, binding.TKV_F32, binding.TKV_T2_INT8_ROW
+    cfg.dev_alloc, cfg.dev_free, cfg.pin_alloc, cfg.pin_free = cbs
+    h = C.c_void_p()
+    assert lib.tkv_create(C.byref(cfg), C.byref(h)) == tkv.TKV_ENOMEM
+    assert not h.value and calls["freed"] == 5 and not held
+
+
+def test_pool_capacities_are_checked_before_anything_moves():
+    import paper_2605_09490_amd as tkv
+    from gpu_common import Pair, assert_out_close
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=64, kv_dtype="bf16", context=200,
+                       decode_steps=4)
+    # staging buffer too small for the plan: ECAPACITY, the plan stays pending, tiers unchanged, attention still right
+    p = Pair(cfg, staging_rows=10, t2_rows=50)
+    t = np.zeros((cfg.batch, 200), np.uint8)
+    t[:, 50:90] = 1
+    p.gpu.set_tiers(t)
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.migrate()
+    assert e.value.status == tkv.TKV_ECAPACITY
+    assert np.all(p.gpu.get_tiers() == 0)
+    t[:, 60:90] = 2                                   # 10 rows to T1, 30 to T2: fits
+    p.gpu.set_tiers(t); p.gpu.migrate()
+    p.orc.set_tiers(t); p.orc.migrate()
+    k, v = p.wl.step_kv(0, 0)
+    for l in range(2):
+        p.append(l, *p.wl.step_kv(0, l))
+        got, ref = p.attend(l, p.wl.step_q(0, l))
+        assert_out_close(got, ref, "bf16")
+    t2 = np.zeros((cfg.batch, 201), np.uint8)
+    t2[:, :201] = np.pad(t, ((0, 0), (0, 1)))
+    t2[:, 100:160] = 2                                # 90 rows in T2 > 50 slots
+    p.gpu.set_tiers(t2)
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.migrate()
+    assert e.value.status == tkv.TKV_ECAPACITY
+    p.close()
+    # pinned host store too small
+    p = Pair(cfg, host_rows=16)
+    t = np.zeros((cfg.batch, 200), np.uint8)
+    t[:, 50:70] = 1                                   # 2 x 20 rows > 16
+    p.gpu.set_tiers(t)
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.migrate()
+    assert e.value.status == tkv.TKV_ECAPACITY
+    p.close()
+    # HBM pool too small for the appended tokens
+    p = Pair(cfg, t0_rows=201, preload=True)
+    p.gpu.append(0, *p.wl.step_kv(0, 0))
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.append(0, *p.wl.step_kv(1, 0))
+    assert e.value.status == tkv.TKV_ECAPACITY
+    p.close()
