@@ -9,7 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtkv.so")
-SOURCES = ["tkv_host.hip", "attn_kernels.hip", "tier_kernels.hip"]
+# (source, extra flags, object name); the attention kernels are one source compiled in five parts that build in parallel
+UNITS = [("attn_kernels.hip", [f"-DTKV_ATTN_PART={p}"], f"attn_kernels_{p}.o") for p in range(5)]
+UNITS += [("tkv_host.hip", [], "tkv_host.o"), ("tier_kernels.hip", [], "tier_kernels.o")]
 # packed-fp32 VALU forms are switched off on purpose (the compiler would otherwise emit them from plain float code)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -27,9 +29,10 @@ def build(verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
 
-    def compile_one(src):
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    def compile_one(unit):
+        src, extra, name = unit
+        obj = os.path.join(objdir, name)
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(ln for ln in r.stderr.splitlines() if "packed-fp32-ops" not in ln)
         if r.returncode != 0:
@@ -38,8 +41,8 @@ def build(verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=3) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
+    with ThreadPoolExecutor(max_workers=min(len(UNITS), os.cpu_count() or 4)) as ex:
+        objs = list(ex.map(compile_one, UNITS))
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB],
                        capture_output=True, text=True)
     if r.returncode != 0:

@@ -1,60 +1,102 @@
 // Decode attention over the tiered KV cache, with cumulative-score emission (Eq. 1, Eq. 2-3 of the paper).
 //
-//   attn_tiered : grid (S, Hkv, B), 4 waves per workgroup.  Workgroup (s, kvh, b) owns TOK_PER_BLOCK consecutive
-//                 entries of one of the two per-sequence lists -- F (T0 u T1 rows at full precision, ascending
-//                 position) or Q (T2 rows, int8 / int4 codes dequantised in registers); T3 positions are in
-//                 neither list.  Every wave is autonomous and works on 64-entry tiles:
-//                   K rows  - 8 lanes per row (each lane 1/8 of the row), 8 rows per wave-wide load; the G logits
-//                             of a row are reduced over its 8 lanes by DPP and kept by the lane whose index
-//                             equals the entry's index in the tile, so after 8 loads lane i holds entry i;
+//   attn_tiered : grid (S, Hkv, B), one workgroup per compute unit.  The per-sequence lists F (T0 u T1 rows at full
+//                 precision, ascending position) and Q (T2 rows, int8 / int4 codes) are cut into tiles of 64 entries;
+//                 T3 positions are in neither list.  The S * NW waves of a (sequence, kv head) pair are divided
+//                 between the two lists in proportion to their cost, and every wave walks its tiles with a stride,
+//                 on its own, with no workgroup barrier until the end.
+//                 Rows never pass through registers on their way in: every lane fetches 16-byte (4-byte for short
+//                 code rows) pieces straight into the wave's LDS buffers (buffer_load ... lds), one K buffer and one
+//                 V buffer of a whole tile each.  As soon as a piece has been read for tile t the same lane refills
+//                 it with the piece of tile t+1, so a wave keeps close to two tiles' worth of rows in flight while
+//                 it computes; waits are vmcnt counts derived from the fixed issue order of one tile period.
+//                   K rows  - 8 lanes per row; the G logits of a row are reduced over its 8 lanes by DPP and kept
+//                             by the lane whose index equals the entry's index in the tile;
 //                   softmax - online, one entry per lane (exact tile maximum, exp2, running m and l);
-//                   V rows  - 16 bytes per lane, 64/LPR rows per wave-wide load, probabilities broadcast from
-//                             LDS, per-lane fp32 output slices.
-//                 The four waves are merged through LDS into one split partial (m, l, o[G][D]); the scaled
+//                   V rows  - D/EV lanes per row, probabilities broadcast from LDS, per-lane fp32 output slices.
+//                 The waves of a workgroup are merged through LDS into one split partial (m, l, o[G][D]); the scaled
 //                 logits go to a scratch array.
 //   attn_finish : grid (64-entry tiles + Hq, B).  Every workgroup first merges the (m, l) of all splits of its sequence
 //                 into the global (m, 1/l) of every query head.  Tile workgroups then turn the stored logits
 //                 into softmax weights, summed over all query heads in a fixed order, into score[b, pos]; the
 //                 Hq remaining workgroups merge the split outputs of one query head each into out[b, hq].
-// The split boundaries and the fp32 summation order depend only on the lists' logical order, never on whether a
-// row lives in the HBM pool or the staging buffer (both are one slot space), which is what makes T1 placement
-// bit-invisible (Prop. 1).  No MFMA: the path is bound by HBM, and the per-row work is G dot products.
+// The tile boundaries, the wave assignment and the fp32 summation order depend only on the lists' logical order and
+// lengths, never on whether a row lives in the HBM pool or the staging buffer (both are one slot space), which is
+// what makes T1 placement bit-invisible (Prop. 1).  No MFMA: the path is bound by HBM, and the per-row work is G
+// dot products.
 #include <hip/hip_ext.h>
+
+#include <utility>
 
 #include "tkv_internal.h"
 
 namespace tkv {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int TB = TOK_PER_BLOCK;
-constexpr int NWAVE = ATTN_THREADS / 64;
-constexpr int TPW = TB / NWAVE;   // list entries per wave
-constexpr int NTILE = TPW / 64;   // 64-entry tiles per wave
-static_assert(TPW % 64 == 0 && NTILE >= 1, "a wave works in tiles of 64 entries");
-
-#ifndef TKV_UK
-#define TKV_UK 2      // K rows per batch and lane group (two batches are in flight)
-#endif
-#ifndef TKV_UV
-#define TKV_UV 4      // V rows per batch and lane group (two batches are in flight)
-#endif
-#ifndef TKV_DEEP
-#define TKV_DEEP 0
-#endif
-#ifdef TKV_ATTN_WAVES_PER_EU
-#define TKV_WPE __attribute__((amdgpu_waves_per_eu(TKV_ATTN_WAVES_PER_EU, TKV_ATTN_WAVES_PER_EU)))
-#else
-#define TKV_WPE
-#endif
+static_assert(TB == 64, "a tile is one list entry per lane");
 
 enum Mode : int { F_BF16 = 0, F_F32 = 1, Q_INT8 = 2, Q_INT4 = 3 };
 
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): loop indices usable as immediates
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// at most N vector-memory operations of this wave still outstanding (they complete in issue order)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  constexpr int n = N > 63 ? 63 : (N < 0 ? 0 : N);
+  __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0F70);
+}
+
+// ---- LDS accesses the compiler's wait insertion does not see ------------------------------------------------
+// A compiler-visible LDS load issued while direct-to-LDS loads are outstanding is preceded by a wait for all of
+// them, which would serialise the pipeline; the waits for these are placed by hand (lds_fence).
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_rd128(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ uint32_t lds_rd32(uint32_t addr) {
+  uint32_t v;
+  asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ void lds_wr128(uint32_t addr, u32x4 v) {
+  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ void lds_wr32(uint32_t addr, uint32_t v) {
+  asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory"); }
+// values read by lds_rd* may be used only after lds_wait() and tie() of the variable
+__device__ __forceinline__ void tie(u32x4& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void tie(uint32_t& v) { asm volatile("" : "+v"(v)); }
+template <class T, int N>
+__device__ __forceinline__ void tie(T (&v)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) tie(v[i]);
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(size_t)(const lds_char*)p;
 }
 
 template <int CTRL>
@@ -74,7 +116,6 @@ __device__ __forceinline__ float group_sum(float x) {
   if constexpr (LPR >= 4) x += dpp_f<0x4E>(x);    // quad_perm [2,3,0,1]
   if constexpr (LPR >= 8) x += dpp_f<0x141>(x);   // row_half_mirror
   if constexpr (LPR >= 16) x += dpp_f<0x140>(x);  // row_mirror
-  if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
   return x;
 }
 __device__ __forceinline__ float rdlane(float x, int l) {
@@ -83,8 +124,12 @@ __device__ __forceinline__ float rdlane(float x, int l) {
 
 // whole-wave reductions: 16-lane rows by DPP, rows 0/1 and 2/3 by row_bcast15, halves by row_bcast31; lane 63 has
 // the result, which is returned in a scalar register
+template <int CTRL>
+__device__ __forceinline__ float dpp_ninf(float x) {     // lanes without a source read -inf, the identity of max
+  return __builtin_amdgcn_update_dpp(-INFINITY, x, CTRL, 0xf, 0xf, false);
+}
 __device__ __forceinline__ float wave_max(float x) {
-  x = fmaxf(x, dpp_f<0xB1>(x)); x = fmaxf(x, dpp_f<0x4E>(x)); x = fmaxf(x, dpp_f<0x141>(x)); x = fmaxf(x, dpp_f<0x140>(x));
+  x = fmaxf(x, dpp_ninf<0xB1>(x)); x = fmaxf(x, dpp_ninf<0x4E>(x)); x = fmaxf(x, dpp_ninf<0x141>(x)); x = fmaxf(x, dpp_ninf<0x140>(x));
   x = fmaxf(x, dpp_rows<0x142, 0xA>(x));
   x = fmaxf(x, dpp_rows<0x143, 0xC>(x));
   return rdlane(x, 63);
@@ -106,320 +151,432 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
   return (__builtin_bit_cast(uint32_t, hi) & 0xffff0000u) | (__builtin_bit_cast(uint32_t, lo) >> 16);
 }
+__device__ __forceinline__ float half_of(uint32_t w, int hi) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)(hi ? (w >> 16) : (w & 0xffffu)));
+}
 
 template <int G>
 struct GPad { static constexpr int v = (G <= 4) ? 4 : 8; };
 
 // ---- geometry ------------------------------------------------------------------------------------------------
+// A row is fetched in "units" of 16 bytes (4 bytes where a lane's share of a row is shorter than 16), one unit per
+// lane and direct-to-LDS instruction; the lane that fetched a unit is the lane that reads it back.
+//   K side: 8 lanes per row; lane r8 owns units j*8 + r8, j < KU          (K batch i = rows 8*g8 + i, g8 = lane/8)
+//   V side: LPRV lanes per row; lane rv owns units rv*VU + u, u < VU      (V step it = rows LPRV*gv + it, gv = lane/LPRV)
 template <int D, Mode M>
 struct Geo {
   static constexpr bool IS_Q = (M == Q_INT8 || M == Q_INT4);
-  // K side: 8 lanes per row
-  static constexpr int EK = D / 8;                                            // elements of a K row per lane
-  static constexpr int KDW = (M == F_BF16) ? EK / 2 : (M == F_F32) ? EK : (M == Q_INT8) ? EK / 4 : EK / 8;  // dwords per lane
-  // V side: one 16-byte piece (F modes) / 8 codes (Q modes) per lane
-  static constexpr int EV = (M == F_F32) ? 4 : 8;
-  static constexpr int LPRV = D / EV;                                         // lanes per V row
-  static constexpr int NITV = LPRV;                                           // wave-wide V loads per tile
-  static constexpr float OFF = (M == Q_INT4) ? 8.f : 128.f;                   // codes are read as code + OFF
+  static constexpr int RB = (M == F_BF16) ? 2 * D : (M == F_F32) ? 4 * D : (M == Q_INT8) ? D : D / 2;   // bytes per row
+  static constexpr int KLB = RB / 8;                        // bytes of a K row per lane
+  static constexpr int KS = (KLB % 16 == 0) ? 16 : 4;       // bytes per unit
+  static constexpr int KU = KLB / KS;                       // units per lane and row
+  static constexpr int EUK = KS * D / RB;                   // elements per unit
+  static constexpr int EV = (M == F_F32) ? 4 : 8;           // elements of a V row per lane
+  static constexpr int LPRV = D / EV;                       // lanes per V row
+  static constexpr int NITV = LPRV;                         // V steps per tile
+  static constexpr int VLB = RB / LPRV;                     // bytes of a V row per lane
+  static constexpr int VS = (VLB % 16 == 0) ? 16 : 4;
+  static constexpr int VU = VLB / VS;
+  static constexpr int EUV = EV / VU;                       // elements per V unit
+  static constexpr int SCD = (M == Q_INT8) ? 1 : (M == Q_INT4) ? D / 64 : 0;   // dwords of scales per row
+  static constexpr float OFF = (M == Q_INT4) ? 8.f : 128.f; // codes are read as code + OFF
+  // direct-to-LDS operations of one tile period, in issue order: slot list, K scales, K batches, V scales, V steps
+  static constexpr int N_K = 8 * KU, N_V = NITV * VU;
+  static constexpr int T = 1 + SCD + N_K + SCD + N_V;
+  static_assert(KLB % KS == 0 && VLB % VS == 0 && LPRV % 4 == 0 && (!IS_Q || D % 64 == 0), "unsupported head_dim");
 };
 
-struct RowSrc {
-  __amdgpu_buffer_rsrc_t data, scale;
-  uint32_t row_bytes, scale_bytes;
-};
+template <int S>
+struct UnitT { using type = uint32_t; };
+template <>
+struct UnitT<16> { using type = u32x4; };
 
-template <int NDW>
-__device__ __forceinline__ void load_dwords(const __amdgpu_buffer_rsrc_t& rs, uint32_t off, uint32_t (&w)[NDW]) {
-  if constexpr (NDW >= 4) {
-#pragma unroll
-    for (int i = 0; i < NDW / 4; ++i) {
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 16 * i, 0, 2);
-      w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
-    }
-  } else if constexpr (NDW == 2) {
-    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, 2);
-    w[0] = v.x; w[1] = v.y;
-  } else {
-    w[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 2);
-  }
+// element c of a vector, by value (a bit cast applied directly to a vector element reads element 0)
+__device__ __forceinline__ uint32_t elem(const u32x4& v, int c) { return v[c]; }
+__device__ __forceinline__ float elem_f(const u32x4& v, int c) { const uint32_t w = v[c]; return __builtin_bit_cast(float, w); }
+
+template <int S>
+__device__ __forceinline__ uint32_t unit_word(const typename UnitT<S>::type& u, int c) {
+  if constexpr (S == 16) return u[c]; else return u;
 }
 
-// scale of a T2 row (INT8) or of the 32-code group that starts at element e0 (INT4).  loc == -1 is out of range: 0
-template <Mode M>
-__device__ __forceinline__ float load_scale(const RowSrc& s, int loc, int e0) {
-  if constexpr (M == Q_INT8) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(s.scale, (uint32_t)loc * s.scale_bytes, 0, 0));
-  } else if constexpr (M == Q_INT4) {
-    const uint16_t hb = __builtin_amdgcn_raw_buffer_load_b16(s.scale, (uint32_t)loc * s.scale_bytes + (uint32_t)(e0 >> 5) * 2, 0, 0);
-    return (float)__builtin_bit_cast(_Float16, hb);
-  } else {
-    return 0.f;
-  }
-}
-
-template <int D, Mode M>
-struct KRow { uint32_t w[Geo<D, M>::KDW]; float sc; };
-template <int D, Mode M>
-struct VRow { uint32_t w[(M == Q_INT8) ? 2 : (M == Q_INT4) ? 1 : 4]; float sc; };
-
-// loc == -1 gives offsets beyond the buffer: such loads return zeros
-template <int D, Mode M>
-__device__ __forceinline__ KRow<D, M> load_krow(const RowSrc& s, int loc, int r8) {
-  KRow<D, M> out;
-  load_dwords<Geo<D, M>::KDW>(s.data, (uint32_t)loc * s.row_bytes + (uint32_t)r8 * (Geo<D, M>::KDW * 4), out.w);
-  out.sc = load_scale<M>(s, loc, r8 * Geo<D, M>::EK);
-  return out;
-}
-template <int D, Mode M>
-__device__ __forceinline__ VRow<D, M> load_vrow(const RowSrc& s, int loc, int r) {
-  VRow<D, M> out;
-  constexpr int NDW = (M == Q_INT8) ? 2 : (M == Q_INT4) ? 1 : 4;
-  load_dwords<NDW>(s.data, (uint32_t)loc * s.row_bytes + (uint32_t)r * (NDW * 4), out.w);
-  out.sc = load_scale<M>(s, loc, r * 8);
-  return out;
-}
-
-// codes as unsigned values code + OFF; the offset is removed once per row: sum q*(u-OFF) = sum q*u - OFF*sum q
-template <Mode M, int NDW>
-__device__ __forceinline__ void unpack_codes(const uint32_t (&w)[NDW], float (&f)[(M == Q_INT8) ? NDW * 4 : NDW * 8]) {
+// codes of one unit as unsigned values code + OFF; the offset is removed once per row (sum q*(u-OFF) = sum q*u - OFF*sum q)
+template <Mode M, int S, int E>
+__device__ __forceinline__ void unpack_unit(const typename UnitT<S>::type& u, float (&f)[E]) {
   if constexpr (M == Q_INT8) {
 #pragma unroll
-    for (int i = 0; i < NDW; ++i) {
-      const uint32_t u = w[i] ^ 0x80808080u;
+    for (int i = 0; i < S / 4; ++i) {
+      const uint32_t w = unit_word<S>(u, i) ^ 0x80808080u;
 #pragma unroll
-      for (int n = 0; n < 4; ++n) f[i * 4 + n] = (float)((u >> (8 * n)) & 0xFFu);
+      for (int n = 0; n < 4; ++n) f[i * 4 + n] = (float)((w >> (8 * n)) & 0xFFu);
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < NDW; ++i) {
-      const uint32_t u = w[i] ^ 0x88888888u;
+    for (int i = 0; i < S / 4; ++i) {
+      const uint32_t w = unit_word<S>(u, i) ^ 0x88888888u;
 #pragma unroll
-      for (int n = 0; n < 8; ++n) f[i * 8 + n] = (float)((u >> (4 * n)) & 0xFu);
+      for (int n = 0; n < 8; ++n) f[i * 8 + n] = (float)((w >> (4 * n)) & 0xFu);
     }
   }
 }
 
-// The lane's 1/8 slice of the G query vectors.  bf16 queries stay packed (EK/2 dwords per head, fed to the bf16
-// dot instruction); binary32 queries are kept as EK floats.  qs is the slice's sum (Q modes only).
-template <int D, int G, bool QBF>
+// The lane's units of the G query vectors.  bf16 queries stay packed (fed to the bf16 dot instruction); binary32
+// queries are kept as floats.  qs is the sum over a unit (Q modes only).
+template <int D, int G, Mode M, bool QBF>
 struct QRegs {
-  static constexpr int EK = D / 8;
-  uint32_t qp[QBF ? G : 1][EK / 2];
-  float qf[QBF ? 1 : G][EK];
-  float qs[G];
+  using GE = Geo<D, M>;
+  uint32_t qp[QBF ? G : 1][GE::KU][GE::EUK / 2];
+  float qf[QBF ? 1 : G][GE::KU][GE::EUK];
+  float qs[G][GE::KU];
 };
 
-// G logits of one K row, reduced over the row's 8 lanes (every lane of the group gets them)
-template <int D, int G, Mode M, bool QBF>
-__device__ __forceinline__ void row_logits(const KRow<D, M>& kr, const QRegs<D, G, QBF>& q, float (&x)[G]) {
-  using GE = Geo<D, M>;
-  constexpr int EK = GE::EK;
-  if constexpr (M == F_BF16) {
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      float acc = 0.f;
-#pragma unroll
-      for (int c = 0; c < EK / 2; ++c)
-        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kr.w[c]), __builtin_bit_cast(bf16x2, q.qp[h][c]), acc, false);
-      x[h] = group_sum<8>(acc);
-    }
-  } else if constexpr (M == F_F32) {
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      float acc = 0.f;
-#pragma unroll
-      for (int c = 0; c < EK; ++c) acc = fmaf(__builtin_bit_cast(float, kr.w[c]), q.qf[h][c], acc);
-      x[h] = group_sum<8>(acc);
-    }
-  } else {
-    float kf[EK];
-    unpack_codes<M, GE::KDW>(kr.w, kf);
-    uint32_t kp[EK / 2];
-    if constexpr (QBF) {
-#pragma unroll
-      for (int c = 0; c < EK / 2; ++c) kp[c] = pack_bf16_pair(kf[2 * c], kf[2 * c + 1]);
-    }
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      float acc = -GE::OFF * q.qs[h];
-      if constexpr (QBF) {
-#pragma unroll
-        for (int c = 0; c < EK / 2; ++c)
-          acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[c]), __builtin_bit_cast(bf16x2, q.qp[h][c]), acc, false);
-      } else {
-#pragma unroll
-        for (int c = 0; c < EK; ++c) acc = fmaf(q.qf[h][c], kf[c], acc);
-      }
-      if constexpr (M == Q_INT4) acc *= kr.sc;      // per-group scale: before the cross-lane sum
-      x[h] = group_sum<8>(acc);
-      if constexpr (M == Q_INT8) x[h] *= kr.sc;     // per-row scale
-    }
-  }
-}
-
+template <int D, Mode M>
+struct KBatch { typename UnitT<Geo<D, M>::KS>::type u[Geo<D, M>::KU]; };
 template <int D, int G, Mode M>
-__device__ __forceinline__ void row_accumulate(const VRow<D, M>& vr, const float (&p)[GPad<G>::v],
-                                               float (&o)[G][Geo<D, M>::EV], float (&osub)[G]) {
-  constexpr int EV = Geo<D, M>::EV;
+struct VStep {
+  typename UnitT<Geo<D, M>::VS>::type u[Geo<D, M>::VU];
+  u32x4 p[GPad<G>::v / 4];
+};
+
+// G logits of one K row, reduced over the row's 8 lanes (every lane of the group gets them).
+// sc: INT8 the row's scale; INT4 the scale of the 32-code group of each of the lane's units.
+template <int D, int G, Mode M, bool QBF>
+__device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D, G, M, QBF>& q,
+                                           const float (&sc)[Geo<D, M>::KU], float (&x)[G]) {
+  using GE = Geo<D, M>;
+  constexpr int KU = GE::KU, KS = GE::KS, EUK = GE::EUK;
   if constexpr (M == F_BF16) {
-    float vf[8];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) { vf[2 * c] = bf_lo(vr.w[c]); vf[2 * c + 1] = bf_hi(vr.w[c]); }
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(p[h], vf[e], o[h][e]);
-  } else if constexpr (M == F_F32) {
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(p[h], __builtin_bit_cast(float, vr.w[e]), o[h][e]);
-  } else {
-    float vf[8];
-    unpack_codes<M, (M == Q_INT8) ? 2 : 1>(vr.w, vf);
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const float ps = p[h] * vr.sc;
-      osub[h] += ps;
+      float acc = 0.f;
 #pragma unroll
-      for (int e = 0; e < EV; ++e) o[h][e] = fmaf(ps, vf[e], o[h][e]);
+      for (int j = 0; j < KU; ++j)
+#pragma unroll
+        for (int c = 0; c < EUK / 2; ++c)
+          acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, unit_word<KS>(kr.u[j], c)),
+                                                __builtin_bit_cast(bf16x2, q.qp[h][j][c]), acc, false);
+      x[h] = group_sum<8>(acc);
+    }
+  } else if constexpr (M == F_F32) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < KU; ++j)
+#pragma unroll
+        for (int c = 0; c < EUK; ++c) acc = fmaf(__builtin_bit_cast(float, unit_word<KS>(kr.u[j], c)), q.qf[h][j][c], acc);
+      x[h] = group_sum<8>(acc);
+    }
+  } else {
+    float tot[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) tot[h] = 0.f;
+#pragma unroll
+    for (int j = 0; j < KU; ++j) {
+      float kf[EUK];
+      unpack_unit<M, KS, EUK>(kr.u[j], kf);
+      uint32_t kp[EUK / 2];
+      if constexpr (QBF) {
+#pragma unroll
+        for (int c = 0; c < EUK / 2; ++c) kp[c] = pack_bf16_pair(kf[2 * c], kf[2 * c + 1]);
+      }
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float acc = -GE::OFF * q.qs[h][j];
+        if constexpr (QBF) {
+#pragma unroll
+          for (int c = 0; c < EUK / 2; ++c)
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[c]), __builtin_bit_cast(bf16x2, q.qp[h][j][c]), acc, false);
+        } else {
+#pragma unroll
+          for (int c = 0; c < EUK; ++c) acc = fmaf(q.qf[h][j][c], kf[c], acc);
+        }
+        if constexpr (M == Q_INT4) tot[h] = fmaf(acc, sc[j], tot[h]);   // per-group scale: before the cross-lane sum
+        else tot[h] += acc;
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      x[h] = group_sum<8>(tot[h]);
+      if constexpr (M == Q_INT8) x[h] *= sc[0];                         // per-row scale
     }
   }
 }
 
-// ---- one workgroup: TOK_PER_BLOCK entries of list F or Q --------------------------------------------------
-// Leaves the workgroup's split partial in part_ml / part_o and the scaled logits in xs.
-template <int D, int G, Mode M, bool QBF>
-__device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float* sm_ml, float* pbuf_all,
-                                           int b, int kvh, int s, int ntok, const int* loc_list) {
+// o[h][e] += p[h] * v[e] for the lane's EV elements of one V row (Q modes: p scaled, offset handled through osub)
+template <int D, int G, Mode M>
+__device__ __forceinline__ void row_accumulate(const VStep<D, G, M>& vr, float sc, float (&o)[G][Geo<D, M>::EV], float (&osub)[G]) {
   using GE = Geo<D, M>;
-  constexpr int EV = GE::EV, LPRV = GE::LPRV, NITV = GE::NITV, EK = GE::EK;
-  constexpr int GP = GPad<G>::v;
-  constexpr int UK = TKV_UK, NBK = 8 / UK;            // K: 8 wave-wide loads per tile, in batches of UK
-  constexpr int UV = (TKV_UV * 2 <= NITV) ? TKV_UV : NITV / 2, NBV = NITV / UV;   // V: NITV loads per tile
-  static_assert(NITV % UV == 0 && NBV % 2 == 0 && NBK % 2 == 0, "batches come in pairs");
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int g8 = lane >> 3, r8 = lane & 7;           // K side: row group and slice
-  const int gv = lane / LPRV, rv = lane % LPRV;      // V side
-  float* pbuf = pbuf_all + wave * 64 * GP;
-
-  RowSrc ks, vs;
-  if constexpr (!GE::IS_Q) {
-    const uint32_t rb = D * (QBF ? 2u : 4u);
-    const size_t off = (size_t)(b * a.Hkv + kvh) * a.capF * rb;
-    ks.data = make_rsrc(a.fpK + off, (uint32_t)a.capF * rb); vs.data = make_rsrc(a.fpV + off, (uint32_t)a.capF * rb);
-    ks.scale = ks.data; vs.scale = vs.data;
-    ks.row_bytes = vs.row_bytes = rb; ks.scale_bytes = vs.scale_bytes = 0;
+  constexpr int EV = GE::EV, VU = GE::VU, VS = GE::VS, EUV = GE::EUV;
+  float p[GPad<G>::v];
+#pragma unroll
+  for (int c = 0; c < GPad<G>::v; ++c) p[c] = elem_f(vr.p[c / 4], c % 4);
+  float vf[EV];
+  if constexpr (M == F_BF16) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { const uint32_t wv = elem(vr.u[0], c); vf[2 * c] = bf_lo(wv); vf[2 * c + 1] = bf_hi(wv); }
+  } else if constexpr (M == F_F32) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) vf[c] = elem_f(vr.u[0], c);
   } else {
-    const size_t rows = (size_t)(b * a.Hkv + kvh) * a.cap2;
-    ks.data = make_rsrc(a.c2K + rows * a.cb, (uint32_t)a.cap2 * a.cb); vs.data = make_rsrc(a.c2V + rows * a.cb, (uint32_t)a.cap2 * a.cb);
-    ks.scale = make_rsrc(a.s2K + rows * a.sb, (uint32_t)a.cap2 * a.sb); vs.scale = make_rsrc(a.s2V + rows * a.sb, (uint32_t)a.cap2 * a.sb);
-    ks.row_bytes = vs.row_bytes = a.cb; ks.scale_bytes = vs.scale_bytes = a.sb;
-  }
-
-  // this lane's 1/8 slice of the G query vectors
-  QRegs<D, G, QBF> q;
-  {
-    constexpr int qes = QBF ? 2 : 4;
-    const char* qb = (const char*)a.q + ((size_t)(b * a.Hq + kvh * G) * D + r8 * EK) * qes;
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const char* qh = qb + (size_t)h * D * qes;
-      float sacc = 0.f;
-      if constexpr (QBF) {
+    for (int u = 0; u < VU; ++u) {
+      float t[EUV];
+      unpack_unit<M, VS, EUV>(vr.u[u], t);
 #pragma unroll
-        for (int c = 0; c < EK / 8; ++c) {
-          const u32x4 v = *(const u32x4*)(qh + 16 * c);
-          q.qp[h][4 * c] = v.x; q.qp[h][4 * c + 1] = v.y; q.qp[h][4 * c + 2] = v.z; q.qp[h][4 * c + 3] = v.w;
-        }
-        if constexpr (GE::IS_Q) {
-#pragma unroll
-          for (int c = 0; c < EK / 2; ++c) sacc += bf_lo(q.qp[h][c]) + bf_hi(q.qp[h][c]);
-        }
-      } else {
-#pragma unroll
-        for (int c = 0; c < EK / 4; ++c) {
-          const float4 v = *(const float4*)(qh + 16 * c);
-          q.qf[h][4 * c] = v.x; q.qf[h][4 * c + 1] = v.y; q.qf[h][4 * c + 2] = v.z; q.qf[h][4 * c + 3] = v.w;
-        }
-        if constexpr (GE::IS_Q) {
-#pragma unroll
-          for (int c = 0; c < EK; ++c) sacc += q.qf[h][c];
-        }
-      }
-      q.qs[h] = sacc;
+      for (int e = 0; e < EUV; ++e) vf[u * EUV + e] = t[e];
     }
   }
-
-  float o[G][EV], osub[G], m_run[G], l_run[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    osub[h] = 0.f; m_run[h] = -INFINITY; l_run[h] = 0.f;
+    float ph = p[h];
+    if constexpr (GE::IS_Q) { ph *= sc; osub[h] += ph; }
 #pragma unroll
-    for (int e = 0; e < EV; ++e) o[h][e] = 0.f;
+    for (int e = 0; e < EV; ++e) o[h][e] = fmaf(ph, vf[e], o[h][e]);
+  }
+}
+
+// LDS regions of one wave (pointers for the direct loads, byte addresses for the reads)
+struct WaveLds {
+  char* t; char* sk; char* sv; char* lt;   // tile buffer (K rows, then V rows, in turn), K scales, V scales, slot lists (2 x 64 ints)
+  uint32_t ta, ska, sva, lta, pa;          // the same as LDS addresses, and the probabilities
+};
+
+template <int SZ>
+__device__ __forceinline__ void dma(const __amdgpu_buffer_rsrc_t& rs, char* lds, uint32_t voff, int aux) {
+  static_assert(SZ == 16 || SZ == 4, "unit sizes");
+  if constexpr (SZ == 16) {
+    if (aux) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)lds, 16, voff, 0, 0, 2);
+    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)lds, 16, voff, 0, 0, 0);
+  } else {
+    if (aux) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)lds, 4, voff, 0, 0, 2);
+    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)lds, 4, voff, 0, 0, 0);
+  }
+}
+
+// ---- one wave: the tiles tile0, tile0 + tstride, ... of one list ------------------------------------------------
+// One tile buffer per wave holds the K rows of a tile, then its V rows, then the next tile's K rows: a K batch that
+// has been read is refilled with the V pieces that fall on the same bytes, a V step with K pieces of the next tile.
+// Issue order of one tile period (the vmcnt arguments below are counts of younger operations in this order):
+//   slot list of tile t+2 | K scales of t+1 | per K batch of t: the V pieces of t on its bytes |
+//   V scales of t+1 | per V step of t: the K pieces of t+1 on its bytes
+// Accumulates into o (offset-corrected for code rows), m_run, l_lane (per-lane partial sums of the softmax
+// denominator, relative to m_run); leaves the scaled logits in xs.
+template <int D, int G, Mode M, bool QBF>
+__device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, int b, int kvh, int lane,
+                                          int tile0, int tstride, int n_list, const int* loc_list, int xs_tile0,
+                                          float (&o)[G][Geo<D, M>::EV], float (&m_run)[G], float (&l_lane)[G]) {
+  using GE = Geo<D, M>;
+  constexpr int EV = GE::EV, LPRV = GE::LPRV, NITV = GE::NITV, KU = GE::KU, KS = GE::KS, VU = GE::VU, VS = GE::VS;
+  constexpr int EUK = GE::EUK, SCD = GE::SCD, RB = GE::RB, N_K = GE::N_K, N_V = GE::N_V;
+  constexpr int GP = GPad<G>::v;
+  constexpr int KIB = 64 * KS, VIB = 64 * VS;        // bytes of the tile buffer one K / V piece covers
+  constexpr int KBB = KU * KIB, VSB = VU * VIB;      // ... one K batch / one V step
+  static_assert(KBB % VIB == 0 && 8 * KBB == NITV * VSB, "K batches and V steps tile the same buffer");
+  constexpr int VPB = KBB / VIB;                     // V pieces issued after each K batch
+  const int g8 = lane >> 3, r8 = lane & 7;           // K side: row group and unit column
+  const int gv = lane / LPRV, rv = lane % LPRV;      // V side
+
+  __amdgpu_buffer_rsrc_t rk, rvv, rsk, rsv;
+  if constexpr (!GE::IS_Q) {
+    const size_t off = (size_t)(b * a.Hkv + kvh) * a.capF * RB;
+    rk = make_rsrc(a.fpK + off, (uint32_t)a.capF * RB); rvv = make_rsrc(a.fpV + off, (uint32_t)a.capF * RB);
+    rsk = rk; rsv = rvv;
+  } else {
+    const size_t rows = (size_t)(b * a.Hkv + kvh) * a.cap2;
+    rk = make_rsrc(a.c2K + rows * a.cb, (uint32_t)a.cap2 * a.cb); rvv = make_rsrc(a.c2V + rows * a.cb, (uint32_t)a.cap2 * a.cb);
+    rsk = make_rsrc(a.s2K + rows * a.sb, (uint32_t)a.cap2 * a.sb); rsv = make_rsrc(a.s2V + rows * a.sb, (uint32_t)a.cap2 * a.sb);
+  }
+  const __amdgpu_buffer_rsrc_t rl = make_rsrc(loc_list, (uint32_t)a.Nmax * 4u);
+
+  if (tile0 * 64 >= n_list) return;
+
+  // the lane's units of the G query vectors
+  QRegs<D, G, M, QBF> q;
+  {
+    constexpr int qes = QBF ? 2 : 4;
+    const char* qb = (const char*)a.q + (size_t)(b * a.Hq + kvh * G) * D * qes;
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int j = 0; j < KU; ++j) {
+        const char* src = qb + ((size_t)h * D + (size_t)(j * 8 + r8) * EUK) * qes;
+        float sacc = 0.f;
+        if constexpr (QBF) {
+#pragma unroll
+          for (int c = 0; c < EUK / 2; ++c) {
+            q.qp[h][j][c] = ((const uint32_t*)src)[c];
+            if constexpr (GE::IS_Q) sacc += bf_lo(q.qp[h][j][c]) + bf_hi(q.qp[h][j][c]);
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < EUK; ++c) {
+            q.qf[h][j][c] = ((const float*)src)[c];
+            if constexpr (GE::IS_Q) sacc += q.qf[h][j][c];
+          }
+        }
+        q.qs[h][j] = sacc;
+      }
   }
 
-  // Two schedules for the tile loop.  DEEP keeps a whole tile's K rows and V rows in flight (128 registers of
-  // buffers, two waves per SIMD) and fetches the next tile's rows while the current one is being computed; the
-  // batched schedule keeps two small batches in flight and fits three or four waves per SIMD.
-  constexpr bool DEEP = (TKV_DEEP != 0) && (G <= 6) && (M != F_F32);
-  if constexpr (DEEP) {
-    KRow<D, M> kb[8];
-    VRow<D, M> vb[NITV];
-    int locs[NTILE];
+  float osub[G];
 #pragma unroll
-    for (int tl = 0; tl < NTILE; ++tl) {
-      const int tb2 = wave * TPW + tl * 64;
-      locs[tl] = (tb2 + lane < ntok) ? loc_list[tb2 + lane] : -1;
+  for (int h = 0; h < G; ++h) osub[h] = 0.f;
+
+  // per-lane byte offsets of its units within a row, and its LDS read addresses
+  const uint32_t kcol = (uint32_t)r8 * KS, vcol = (uint32_t)rv * (VU * VS);
+  const uint32_t k_rd = w.ta + (uint32_t)lane * KS, v_rd = w.ta + (uint32_t)lane * VS;
+  const uint32_t p_wr = w.pa + (uint32_t)lane * (GP * 4), p_rd = w.pa + (uint32_t)(gv * LPRV) * (GP * 4);
+
+  // slots of the rows this lane fetches: lk / lrow belong to the tile whose K rows are fetched next, lv to the
+  // tile whose V rows are fetched next
+  int lk[8], lv[LPRV], lrow;
+  // reads the K-side slots (rows 8*g8 + i) and the lane's own row's slot of the list in LDS half `par`
+  auto read_locs_k = [&](int par, int nvalid) {
+    const uint32_t base = w.lta + (uint32_t)par * 256u;
+    if (nvalid < 64) {                                   // wave-uniform: a list's last tile
+      if (lane >= nvalid) lds_wr32(base + (uint32_t)lane * 4u, 0xffffffffu);   // no row: fetches land as zeros
     }
-    auto issue_k_all = [&](int myloc) {
+    u32x4 t0 = lds_rd128<0>(base + (uint32_t)g8 * 32u), t1 = lds_rd128<16>(base + (uint32_t)g8 * 32u);
+    uint32_t me = lds_rd32<0>(base + (uint32_t)lane * 4u);
+    lds_wait(); tie(t0); tie(t1); tie(me);
+    lk[0] = t0.x; lk[1] = t0.y; lk[2] = t0.z; lk[3] = t0.w; lk[4] = t1.x; lk[5] = t1.y; lk[6] = t1.z; lk[7] = t1.w;
+    lrow = (int)me;
+  };
+  auto read_locs_v = [&](int par) {
+    const uint32_t base = w.lta + (uint32_t)par * 256u + (uint32_t)(gv * LPRV) * 4u;
+    u32x4 t[LPRV / 4];
+    static_for<LPRV / 4>([&](auto cc) { constexpr int c = decltype(cc)::value; t[c] = lds_rd128<c * 16>(base); });
+    lds_wait(); tie(t);
 #pragma unroll
-      for (int it = 0; it < 8; ++it) kb[it] = load_krow<D, M>(ks, __shfl(myloc, g8 * 8 + it), r8);
-    };
-    auto issue_v_all = [&](int myloc) {
+    for (int c = 0; c < LPRV / 4; ++c) { lv[4 * c] = t[c].x; lv[4 * c + 1] = t[c].y; lv[4 * c + 2] = t[c].z; lv[4 * c + 3] = t[c].w; }
+  };
+  auto issue_loc = [&](int par, int tile) {
+    dma<4>(rl, w.lt + par * 256, (uint32_t)(tile * 64 + lane) * 4u, 0);
+  };
+  auto issue_kscale = [&]() {
 #pragma unroll
-      for (int it = 0; it < NITV; ++it) vb[it] = load_vrow<D, M>(vs, __shfl(myloc, gv * LPRV + it), rv);
-    };
-    issue_k_all(locs[0]);
-    issue_v_all(locs[0]);
+    for (int j = 0; j < SCD; ++j) dma<4>(rsk, w.sk + j * 256, (uint32_t)lrow * (uint32_t)a.sb + j * 4u, 0);
+  };
+  auto issue_vscale = [&]() {
 #pragma unroll
-    for (int tile = 0; tile < NTILE; ++tile) {
-      const int tbase = wave * TPW + tile * 64;
-      if (tbase >= ntok) break;                          // wave-uniform
-      const bool valid = tbase + lane < ntok;
-      float xt[G];
+    for (int j = 0; j < SCD; ++j) dma<4>(rsv, w.sv + j * 256, (uint32_t)lrow * (uint32_t)a.sb + j * 4u, 0);
+  };
+  auto issue_k_piece = [&](int s) {                      // K piece s = (batch s / KU, unit s % KU)
+    const int i = s / KU, j = s % KU;
+    dma<KS>(rk, w.t + s * KIB, (uint32_t)lk[i] * (uint32_t)RB + (uint32_t)j * (8 * KS) + kcol, 1);
+  };
+  auto issue_v_piece = [&](int v) {                      // V piece v = (step v / VU, unit v % VU)
+    const int it = v / VU, u = v % VU;
+    dma<VS>(rvv, w.t + v * VIB, (uint32_t)lv[it] * (uint32_t)RB + vcol + (uint32_t)u * VS, 1);
+  };
+
+  // ---- prologue: the first tile's slot list, then its scales and K rows in the order of a tile period
+  issue_loc(0, tile0);
+  wait_vm<0>();
+  read_locs_k(0, n_list - tile0 * 64);
+  issue_loc(1, tile0 + tstride);
+  issue_kscale();
+  issue_vscale();
 #pragma unroll
-      for (int h = 0; h < G; ++h) xt[h] = 0.f;
+  for (int s = 0; s < N_K; ++s) issue_k_piece(s);
+
+  int par = 1;                                           // LDS half that holds the next tile's slot list
+  bool first = true;
+  auto tile_body = [&](int tile, auto more_c) {
+    constexpr bool MORE = decltype(more_c)::value;
+    constexpr int X = MORE ? 1 : 0;                      // operations of the parts a last tile does not issue
+    const bool valid = tile * 64 + lane < n_list;
+    // -- V-side slots of this tile; K-side slots of the next one; fetch the list after that
+    read_locs_v(par ^ 1);
+    if constexpr (MORE) {
+      wait_vm<2 * SCD + N_K>();
+      read_locs_k(par, n_list - (tile + tstride) * 64);
+      issue_loc(par ^ 1, tile + 2 * tstride);
+    }
+    // -- K scales of this tile
+    float ksc[8][KU];
+    if constexpr (GE::IS_Q) {
+      wait_vm<SCD + N_K + X>();
+      u32x4 t[SCD][2];
+      static_for<SCD>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        t[j][0] = lds_rd128<j * 256>(w.ska + (uint32_t)g8 * 32u);
+        t[j][1] = lds_rd128<j * 256 + 16>(w.ska + (uint32_t)g8 * 32u);
+      });
+      lds_wait();
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        float x[G];
-        row_logits<D, G, M, QBF>(kb[it], q, x);
+      for (int j = 0; j < SCD; ++j) { tie(t[j][0]); tie(t[j][1]); }
+      if constexpr (MORE) issue_kscale();
 #pragma unroll
-        for (int h = 0; h < G; ++h) xt[h] = (r8 == it) ? x[h] : xt[h];
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (tile + 1 < NTILE) issue_k_all(locs[tile + 1 < NTILE ? tile + 1 : tile]);   // out-of-range slots cost nothing
-      float corr[G];
-      {
-        const size_t xbase = ((size_t)(b * a.Hq + kvh * G)) * a.xs_stride + (size_t)s * TB + tbase + lane;
+      for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-          const float x = valid ? xt[h] * a.softmax_scale : -INFINITY;
-          if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x;
-          const float tm = wave_max(x);
-          float mn;
-          if (tile == 0) { mn = tm; corr[h] = 0.f; }
-          else { mn = fmaxf(m_run[h], tm); corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E); }
-          const float p = valid ? __builtin_amdgcn_exp2f((x - mn) * LOG2E) : 0.f;
-          const float ps = wave_sum(p);
-          l_run[h] = (tile == 0) ? ps : fmaf(l_run[h], corr[h], ps);
-          m_run[h] = mn;
-          pbuf[lane * GP + h] = p;
+        for (int j = 0; j < KU; ++j) {
+          if constexpr (M == Q_INT8) ksc[i][j] = elem_f(t[0][i / 4], i % 4);
+          else ksc[i][j] = half_of(elem(t[j][i / 4], i % 4), (r8 >> 2) & 1);   // unit j*8 + r8 lies in group 2*j + r8/4
         }
+    }
+    // -- K rows: read batch i+1 while batch i is computed; a batch that has been read is refilled with V pieces
+    float xt[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) xt[h] = 0.f;
+    KBatch<D, M> kb[2];
+    auto read_k = [&](auto ic, KBatch<D, M>& dst) {
+      constexpr int i = decltype(ic)::value;
+      // younger than this batch's pieces: the later K pieces, the list and K-scale fetches of this period, the V pieces so far
+      wait_vm<N_K - 1 - ((i + 1) * KU - 1) + X * (1 + SCD) + i * VPB>();
+      static_for<KU>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        if constexpr (KS == 16) dst.u[j] = lds_rd128<(i * KU + j) * KIB>(k_rd);
+        else dst.u[j] = lds_rd32<(i * KU + j) * KIB>(k_rd);
+      });
+    };
+    read_k(std::integral_constant<int, 0>{}, kb[0]);
+    static_for<8>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      lds_wait(); tie(kb[i & 1].u);
+#pragma unroll
+      for (int v = i * VPB; v < (i + 1) * VPB; ++v) issue_v_piece(v);
+      if constexpr (i + 1 < 8) read_k(std::integral_constant<int, (i + 1 < 8 ? i + 1 : 7)>{}, kb[(i + 1) & 1]);
+      float x[G];
+      row_logits<D, G, M, QBF>(kb[i & 1], q, ksc[i], x);
+#pragma unroll
+      for (int h = 0; h < G; ++h) xt[h] = (r8 == i) ? x[h] : xt[h];   // lane 8*g8 + i keeps entry 8*g8 + i
+    });
+    // -- online softmax, one entry per lane; the denominator is summed per lane and reduced once at the end
+    float corr[G];
+    {
+      const size_t xbase = ((size_t)(b * a.Hq + kvh * G)) * a.xs_stride + (size_t)(xs_tile0 + tile) * 64 + lane;
+      float pv[GP];
+#pragma unroll
+      for (int h = 0; h < GP; ++h) pv[h] = 0.f;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float x = valid ? xt[h] * a.softmax_scale : -INFINITY;
+        if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x;
+        const float tm = wave_max(x);
+        float mn;
+        if (first) { mn = tm; corr[h] = 0.f; }
+        else { mn = fmaxf(m_run[h], tm); corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E); }
+        const float p = valid ? __builtin_amdgcn_exp2f((x - mn) * LOG2E) : 0.f;
+        l_lane[h] = first ? p : fmaf(l_lane[h], corr[h], p);
+        m_run[h] = mn;
+        pv[h] = p;
       }
-      __builtin_amdgcn_wave_barrier();
-      if (tile > 0) {
+      static_for<GP / 4>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        u32x4 t;
+        t.x = __builtin_bit_cast(uint32_t, pv[4 * c]); t.y = __builtin_bit_cast(uint32_t, pv[4 * c + 1]);
+        t.z = __builtin_bit_cast(uint32_t, pv[4 * c + 2]); t.w = __builtin_bit_cast(uint32_t, pv[4 * c + 3]);
+        lds_wr128<c * 16>(p_wr, t);
+      });
+    }
+    if (!first) {
+      // the running maxima are wave-uniform; once they have settled no head needs rescaling (x * 1.0f is exact)
+      bool moved = false;
+#pragma unroll
+      for (int h = 0; h < G; ++h) moved = moved || (corr[h] != 1.0f);
+      if (moved) {
 #pragma unroll
         for (int h = 0; h < G; ++h) {
           osub[h] *= corr[h];
@@ -427,196 +584,204 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, float* sm_o, float
           for (int e = 0; e < EV; ++e) o[h][e] *= corr[h];
         }
       }
-#pragma unroll
-      for (int it = 0; it < NITV; ++it) {
-        float p[GP];
-#pragma unroll
-        for (int c = 0; c < GP; c += 4) {
-          const float4 pv = *(const float4*)(pbuf + (gv * LPRV + it) * GP + c);
-          p[c] = pv.x; p[c + 1] = pv.y; p[c + 2] = pv.z; p[c + 3] = pv.w;
-        }
-        row_accumulate<D, G, M>(vb[it], p, o, osub);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (tile + 1 < NTILE) issue_v_all(locs[tile + 1 < NTILE ? tile + 1 : tile]);
-      __builtin_amdgcn_wave_barrier();
     }
-  } else {
+    // -- V scales of this tile
+    float vsc[LPRV];
+    if constexpr (GE::IS_Q) {
+      wait_vm<N_K + X * (1 + SCD) + N_V>();
+      const uint32_t base = w.sva + (uint32_t)(gv * LPRV) * 4u + ((M == Q_INT4) ? (uint32_t)(rv >> 3) * 256u : 0u);
+      u32x4 t[LPRV / 4];
+      static_for<LPRV / 4>([&](auto cc) { constexpr int c = decltype(cc)::value; t[c] = lds_rd128<c * 16>(base); });
+      lds_wait(); tie(t);
+      if constexpr (MORE) issue_vscale();
 #pragma unroll
-  for (int tile = 0; tile < NTILE; ++tile) {
-    const int tbase = wave * TPW + tile * 64;          // first entry of the tile, relative to the workgroup
-    if (tbase >= ntok) break;                          // wave-uniform
-    const bool valid = tbase + lane < ntok;
-    const int myloc = valid ? loc_list[tbase + lane] : -1;   // slot of tile entry `lane`
+      for (int it = 0; it < LPRV; ++it) {
+        if constexpr (M == Q_INT8) vsc[it] = elem_f(t[it / 4], it % 4);
+        else vsc[it] = half_of(elem(t[it / 4], it % 4), (rv >> 2) & 1);        // unit rv lies in group rv/4
+      }
+    }
+    // -- V rows: a step that has been read is refilled with the next tile's K pieces that fall on its bytes
+    VStep<D, G, M> vb[2];
+    auto read_v = [&](auto ic, VStep<D, G, M>& dst) {
+      constexpr int it = decltype(ic)::value;
+      // younger than this step's pieces: the later V pieces, the V-scale fetches of this period, the K pieces so far
+      wait_vm<N_V - 1 - ((it + 1) * VU - 1) + X * (SCD + (it * VSB) / KIB)>();
+      static_for<VU>([&](auto uc) {
+        constexpr int u = decltype(uc)::value;
+        if constexpr (VS == 16) dst.u[u] = lds_rd128<(it * VU + u) * VIB>(v_rd);
+        else dst.u[u] = lds_rd32<(it * VU + u) * VIB>(v_rd);
+      });
+      static_for<GP / 4>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        dst.p[c] = lds_rd128<it * GP * 4 + c * 16>(p_rd);
+      });
+    };
+    read_v(std::integral_constant<int, 0>{}, vb[0]);
+    static_for<NITV>([&](auto ic) {
+      constexpr int it = decltype(ic)::value;
+      lds_wait(); tie(vb[it & 1].u); tie(vb[it & 1].p);
+      if constexpr (MORE) {
+#pragma unroll
+        for (int s = (it * VSB) / KIB; s < ((it + 1) * VSB) / KIB; ++s) issue_k_piece(s);
+      }
+      if constexpr (it + 1 < NITV) read_v(std::integral_constant<int, (it + 1 < NITV ? it + 1 : NITV - 1)>{}, vb[(it + 1) & 1]);
+      row_accumulate<D, G, M>(vb[it & 1], GE::IS_Q ? vsc[it] : 0.f, o, osub);
+    });
+    first = false;
+    par ^= 1;
+  };
 
-    // ---- K rows: entry g8*8 + it is loaded by lane group g8 at iteration it, two batches in flight
-    KRow<D, M> kb0[UK], kb1[UK];
-    auto issue_k = [&](int batch, KRow<D, M> (&dst)[UK]) {
-#pragma unroll
-      for (int u = 0; u < UK; ++u) dst[u] = load_krow<D, M>(ks, __shfl(myloc, g8 * 8 + batch * UK + u), r8);
-    };
-    float xt[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h) xt[h] = 0.f;
-    auto logits = [&](int batch, const KRow<D, M> (&src)[UK]) {
-#pragma unroll
-      for (int u = 0; u < UK; ++u) {
-        float x[G];
-        row_logits<D, G, M, QBF>(src[u], q, x);
-        const int it = batch * UK + u;
-#pragma unroll
-        for (int h = 0; h < G; ++h) xt[h] = (r8 == it) ? x[h] : xt[h];   // lane g8*8+it keeps entry g8*8+it
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    };
-    issue_k(0, kb0);
-    issue_k(1, kb1);
-#pragma unroll 1
-    for (int k = 0; k < NBK; k += 2) {
-      logits(k, kb0);
-      if (k + 2 < NBK) issue_k(k + 2, kb0);
-      logits(k + 1, kb1);
-      if (k + 3 < NBK) issue_k(k + 3, kb1);
-    }
-    // ---- V rows: entry gv*LPRV + it is loaded by lane group gv at iteration it; the first two batches fly
-    //      while the softmax is computed
-    VRow<D, M> vb0[UV], vb1[UV];
-    auto issue_v = [&](int batch, VRow<D, M> (&dst)[UV]) {
-#pragma unroll
-      for (int u = 0; u < UV; ++u) dst[u] = load_vrow<D, M>(vs, __shfl(myloc, gv * LPRV + batch * UV + u), rv);
-    };
-    issue_v(0, vb0);
-    issue_v(1, vb1);
-    // ---- online softmax, one entry per lane
-    float corr[G];
-    {
-      const size_t xbase = ((size_t)(b * a.Hq + kvh * G)) * a.xs_stride + (size_t)s * TB + tbase + lane;
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float x = valid ? xt[h] * a.softmax_scale : -INFINITY;
-        if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x;
-        const float tm = wave_max(x);
-        float mn;
-        if (tile == 0) { mn = tm; corr[h] = 0.f; }
-        else { mn = fmaxf(m_run[h], tm); corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E); }
-        const float p = valid ? __builtin_amdgcn_exp2f((x - mn) * LOG2E) : 0.f;
-        const float ps = wave_sum(p);
-        l_run[h] = (tile == 0) ? ps : fmaf(l_run[h], corr[h], ps);
-        m_run[h] = mn;
-        pbuf[lane * GP + h] = p;
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-    if (tile > 0) {
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        osub[h] *= corr[h];
-#pragma unroll
-        for (int e = 0; e < EV; ++e) o[h][e] *= corr[h];
-      }
-    }
-    // probabilities of entry (gv, it): read one row ahead of their use, so only two rows' worth stay in registers
-    auto load_p = [&](int it, float (&p)[GP]) {
-#pragma unroll
-      for (int c = 0; c < GP; c += 4) {
-        const float4 pv = *(const float4*)(pbuf + (gv * LPRV + it) * GP + c);
-        p[c] = pv.x; p[c + 1] = pv.y; p[c + 2] = pv.z; p[c + 3] = pv.w;
-      }
-    };
-    auto accum = [&](int batch, const VRow<D, M> (&src)[UV]) {
-      float pc[GP];
-      load_p(batch * UV, pc);
-#pragma unroll
-      for (int u = 0; u < UV; ++u) {
-        float pn[GP];
-        if (u + 1 < UV) load_p(batch * UV + u + 1, pn);
-        __builtin_amdgcn_sched_barrier(0);   // rows stay in order: bounds the live p / widened-V registers
-        row_accumulate<D, G, M>(src[u], pc, o, osub);
-        __builtin_amdgcn_sched_barrier(0);
-        if (u + 1 < UV) {
-#pragma unroll
-          for (int c = 0; c < GP; ++c) pc[c] = pn[c];
-        }
-      }
-    };
-#pragma unroll 1
-    for (int k = 0; k < NBV; k += 2) {
-      accum(k, vb0);
-      if (k + 2 < NBV) issue_v(k + 2, vb0);
-      accum(k + 1, vb1);
-      if (k + 3 < NBV) issue_v(k + 3, vb1);
-    }
-    __builtin_amdgcn_wave_barrier();
-  }
-  }
+  int tile = tile0;
+  for (; (tile + tstride) * 64 < n_list; tile += tstride) tile_body(tile, std::true_type{});
+  tile_body(tile, std::false_type{});
+
   if constexpr (GE::IS_Q) {
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
       for (int e = 0; e < EV; ++e) o[h][e] = fmaf(-GE::OFF, osub[h], o[h][e]);
   }
-  // ---- wave partial: sum the row groups, then merge the four waves through LDS
-#pragma unroll
-  for (int st = LPRV; st < 64; st <<= 1) {
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-      for (int e = 0; e < EV; ++e) o[h][e] += __shfl_xor(o[h][e], st);
+}
+
+template <int D, bool BF16>
+struct KernelGeo {
+  static constexpr Mode MF = BF16 ? F_BF16 : F_F32;
+  static constexpr int RB = Geo<D, MF>::RB;
+  static constexpr int NW = RB > 256 ? 2 : 4;          // waves per workgroup; two workgroups share a compute unit's LDS
+  static constexpr int EV = Geo<D, MF>::EV;
+  static constexpr int LPRV = Geo<D, MF>::LPRV;
+};
+
+// Waves of a (sequence, kv head) pair that serve the Q list, out of nwv, for nft F tiles and nqt Q tiles: the split
+// that minimises the longest wave.  A code tile moves fewer bytes than a full-precision one but costs more vector
+// instructions (unpacking); it is priced QCOST_Q against QCOST_F for an F tile.  Depends on the list lengths only.
+constexpr int QCOST_F = 4, QCOST_Q = 5;
+__host__ __device__ inline int q_waves(int nwv, int nft, int nqt) {
+  if (nqt == 0) return 0;
+  if (nft == 0) return nwv;
+  int best = 1, best_cost = 0x7fffffff;
+  for (int n = 1; n < nwv; ++n) {
+    const int cf = ((nft + (nwv - n) - 1) / (nwv - n)) * QCOST_F, cq = ((nqt + n - 1) / n) * QCOST_Q;
+    const int c = cf > cq ? cf : cq;
+    if (c < best_cost) { best_cost = c; best = n; }
   }
-  if (lane < LPRV) {
+  return best;
+}
+
+template <int D, int G, bool BF16>
+__global__ __launch_bounds__((KernelGeo<D, BF16>::NW * 64), 2) void k_attn_tiered(const AttnArgs a) {
+  using KG = KernelGeo<D, BF16>;
+  constexpr int NW = KG::NW, EV = KG::EV, LPRV = KG::LPRV, GP = GPad<G>::v;
+  constexpr int TILE_BYTES = 64 * KG::RB;
+  static_assert(G * D * 4 <= TILE_BYTES, "a wave's output partial is parked in its tile buffer");
+  __shared__ __attribute__((aligned(16))) char sm_t[NW * TILE_BYTES];
+  __shared__ __attribute__((aligned(16))) char sm_sc[NW * 2 * 512];
+  __shared__ __attribute__((aligned(16))) char sm_lt[NW * 512];
+  __shared__ __attribute__((aligned(16))) float sm_p[NW * 64 * GP];
+  __shared__ float sm_ml[NW * 16];
+  const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  int nF, nQ;
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  const int nft = (nF + 63) >> 6, nqt = (nQ + 63) >> 6;
+  const int nwv = a.S * NW;
+  const int nwq = (a.B <= ATTN_ARG_SEQS) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
+  const int u = s * NW + wave;
+
+  WaveLds w;
+  w.t = sm_t + wave * TILE_BYTES;
+  w.sk = sm_sc + wave * 1024; w.sv = w.sk + 512; w.lt = sm_lt + wave * 512;
+  w.ta = lds_addr(w.t); w.ska = lds_addr(w.sk); w.sva = lds_addr(w.sv); w.lta = lds_addr(w.lt);
+  w.pa = lds_addr(sm_p + wave * 64 * GP);
+  float* my_o = (float*)w.t;          // after the wave's last tile: its output partial, [G][D]
+
+  float o[G][EV], m_run[G], l_lane[G];
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+  for (int h = 0; h < G; ++h) {
+    m_run[h] = -INFINITY; l_lane[h] = 0.f;
 #pragma unroll
-      for (int e = 0; e < EV; ++e) sm_o[(wave * G + h) * D + lane * EV + e] = o[h][e];
+    for (int e = 0; e < EV; ++e) o[h][e] = 0.f;
   }
-  if (lane == 0) {
+  bool o_written = false;
+  if (u < nwf) {
+    attn_wave<D, G, KG::MF, BF16>(a, w, b, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, 0, o, m_run, l_lane);
+  } else {
+    if constexpr (EV == 8) {
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o, m_run, l_lane);
+    } else {
+      // binary32 rows use 4 elements per lane, code rows 8: separate accumulators, parked directly
+      float o8[G][8];
 #pragma unroll
-    for (int h = 0; h < G; ++h) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = l_run[h]; }
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o8[h][e] = 0.f;
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o8, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o8, m_run, l_lane);
+      constexpr int L8 = D / 8;
+#pragma unroll
+      for (int st = L8; st < 64; st <<= 1)
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o8[h][e] += __shfl_xor(o8[h][e], st);
+      if (lane < L8) {
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) my_o[h * D + lane * 8 + e] = o8[h][e];
+      }
+      o_written = true;
+    }
+  }
+  // ---- wave partial: sum the row groups and the per-lane denominators, then merge the waves through LDS
+  if (!o_written) {
+#pragma unroll
+    for (int st = LPRV; st < 64; st <<= 1)
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < EV; ++e) o[h][e] += __shfl_xor(o[h][e], st);
+    if (lane < LPRV) {
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < EV; ++e) my_o[h * D + lane * EV + e] = o[h][e];
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    const float ls = wave_sum(l_lane[h]);
+    if (lane == 0) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = ls; }
   }
   __syncthreads();
   float* po = a.part_o + ((size_t)((b * a.Hkv + kvh) * a.S + s) * G) * D;
-  for (int i = t; i < G * D; i += ATTN_THREADS) {
+  for (int i = t; i < G * D; i += NW * 64) {
     const int h = i / D;
     float mb = sm_ml[h];
 #pragma unroll
-    for (int w = 1; w < NWAVE; ++w) mb = fmaxf(mb, sm_ml[w * 16 + h]);
+    for (int ww = 1; ww < NW; ++ww) mb = fmaxf(mb, sm_ml[ww * 16 + h]);
     float acc = 0.f;
+    if (mb > -INFINITY) {
 #pragma unroll
-    for (int w = 0; w < NWAVE; ++w) acc = fmaf(__builtin_amdgcn_exp2f((sm_ml[w * 16 + h] - mb) * LOG2E), sm_o[w * G * D + i], acc);
+      for (int ww = 0; ww < NW; ++ww)
+        acc = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 16 + h] - mb) * LOG2E), ((const float*)(sm_t + ww * TILE_BYTES))[i], acc);
+    }
     po[i] = acc;
   }
   if (t < G) {
     float mb = sm_ml[t];
 #pragma unroll
-    for (int w = 1; w < NWAVE; ++w) mb = fmaxf(mb, sm_ml[w * 16 + t]);
+    for (int ww = 1; ww < NW; ++ww) mb = fmaxf(mb, sm_ml[ww * 16 + t]);
     float ll = 0.f;
+    if (mb > -INFINITY) {
 #pragma unroll
-    for (int w = 0; w < NWAVE; ++w) ll = fmaf(__builtin_amdgcn_exp2f((sm_ml[w * 16 + t] - mb) * LOG2E), sm_ml[w * 16 + 8 + t], ll);
+      for (int ww = 0; ww < NW; ++ww) ll = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 16 + t] - mb) * LOG2E), sm_ml[ww * 16 + 8 + t], ll);
+    }
     float* pm = a.part_ml + ((size_t)((b * a.Hkv + kvh) * a.S + s) * 2) * G;
     pm[t] = mb;
     pm[G + t] = ll;
-  }
-}
-
-template <int D, int G, bool BF16>
-__global__ __launch_bounds__(ATTN_THREADS) TKV_WPE void k_attn_tiered(const AttnArgs a) {
-  constexpr int GP = GPad<G>::v;
-  __shared__ __attribute__((aligned(16))) float pbuf[NWAVE * 64 * GP];
-  __shared__ float sm_o[NWAVE * G * D];
-  __shared__ float sm_ml[NWAVE * 16];
-  const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  int nF, nQ;
-  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
-  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
-  const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = cf + cq;
-  if (s >= ns) return;
-  if (s < cf) {
-    const int j0 = s * TB;
-    attn_block<D, G, BF16 ? F_BF16 : F_F32, BF16>(a, sm_o, sm_ml, pbuf, b, kvh, s, min(TB, nF - j0), a.f_loc + (size_t)b * a.Nmax + j0);
-  } else {
-    const int j0 = (s - cf) * TB;
-    if (a.t2fmt == 0) attn_block<D, G, Q_INT8, BF16>(a, sm_o, sm_ml, pbuf, b, kvh, s, min(TB, nQ - j0), a.q_loc + (size_t)b * a.Nmax + j0);
-    else attn_block<D, G, Q_INT4, BF16>(a, sm_o, sm_ml, pbuf, b, kvh, s, min(TB, nQ - j0), a.q_loc + (size_t)b * a.Nmax + j0);
   }
 }
 
@@ -631,7 +796,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   int nF, nQ;
   if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
   else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
-  const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = cf + cq;
+  const int cf = (nF + TB - 1) / TB, ns = a.S;
   const bool is_tile = (int)blockIdx.x < n_tiles;
   if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
   // (m, l) of every split of this sequence: part_ml[b][kvh][s][2][G], s < ns
@@ -710,20 +875,16 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------------
-// With a pair of events the launch is timed by the dispatch's own begin / end timestamps (no bracket overhead).
-template <int D, int G, bool BF16>
-static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  dim3 grid(a.S, a.Hkv, a.B);
-  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(ATTN_THREADS), 0, st, ev0, ev1, 0, a);
-  else hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(ATTN_THREADS), 0, st, a);
-  return hipGetLastError();
-}
-template <int D, int G, bool BF16>
-static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
-  const int tiles = (a.S * TB + 63) / 64;
-  hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, a, tiles);
-  return hipGetLastError();
-}
+// The file is compiled once per part (TKV_ATTN_PART = 0..3: one (head_dim, KV dtype) pair of attn_tiered each,
+// 4: attn_finish and the launchers), so the parts build in parallel; without the macro it is one translation unit.
+// TKV_ATTN_ONLY_BF16_128 (kernel experiments) builds one unit with the bf16, head_dim 128 kernels alone.
+#if defined(TKV_ATTN_ONLY_BF16_128)
+#define TKV_HAS_PART(p) ((p) == 0 || (p) == 4)
+#elif defined(TKV_ATTN_PART)
+#define TKV_HAS_PART(p) (TKV_ATTN_PART == (p))
+#else
+#define TKV_HAS_PART(p) 1
+#endif
 
 #define TKV_DISPATCH_G(FN, D_, BF_, ...)                    \
   switch (G) {                                              \
@@ -738,17 +899,68 @@ static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
     default: return hipErrorInvalidValue;                   \
   }
 
+// With a pair of events the launch is timed by the dispatch's own begin / end timestamps (no bracket overhead).
+template <int D, int G, bool BF16>
+static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  dim3 grid(a.S, a.Hkv, a.B);
+  constexpr int threads = KernelGeo<D, BF16>::NW * 64;
+  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
+  else hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(threads), 0, st, a);
+  return hipGetLastError();
+}
+template <int D, bool BF16>
+hipError_t tiered_by_group(const AttnArgs& a, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+#define TKV_DEFINE_PART(D_, BF_)                                                                                   \
+  template <>                                                                                                      \
+  hipError_t tiered_by_group<D_, BF_>(const AttnArgs& a, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {  \
+    TKV_DISPATCH_G(run_tiered, D_, BF_, a, st, ev0, ev1)                                                           \
+  }
+#if TKV_HAS_PART(0)
+TKV_DEFINE_PART(128, true)
+#endif
+#if TKV_HAS_PART(1)
+TKV_DEFINE_PART(128, false)
+#endif
+#if TKV_HAS_PART(2)
+TKV_DEFINE_PART(64, true)
+#endif
+#if TKV_HAS_PART(3)
+TKV_DEFINE_PART(64, false)
+#endif
+
+#if TKV_HAS_PART(4)
+#if defined(TKV_ATTN_ONLY_BF16_128)
+template <int D, bool BF16>
+hipError_t tiered_by_group(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipErrorInvalidValue; }
+#else
+template <> hipError_t tiered_by_group<128, true>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<128, false>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<64, true>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<64, false>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+#endif
+
+template <int D, int G, bool BF16>
+static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
+  const int tiles = a.n_tiles;
+  hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, a, tiles);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  if (D == 128 && bf16) { TKV_DISPATCH_G(run_tiered, 128, true, a, st, ev0, ev1) }
-  if (D == 128 && !bf16) { TKV_DISPATCH_G(run_tiered, 128, false, a, st, ev0, ev1) }
-  if (D == 64 && bf16) { TKV_DISPATCH_G(run_tiered, 64, true, a, st, ev0, ev1) }
-  if (D == 64 && !bf16) { TKV_DISPATCH_G(run_tiered, 64, false, a, st, ev0, ev1) }
+  if (D == 128 && bf16) return tiered_by_group<128, true>(a, G, st, ev0, ev1);
+  if (D == 128 && !bf16) return tiered_by_group<128, false>(a, G, st, ev0, ev1);
+  if (D == 64 && bf16) return tiered_by_group<64, true>(a, G, st, ev0, ev1);
+  if (D == 64 && !bf16) return tiered_by_group<64, false>(a, G, st, ev0, ev1);
   return hipErrorInvalidValue;
 }
+int attn_waves_per_group(int D, bool bf16) { return D * (bf16 ? 2 : 4) > 256 ? 2 : 4; }
+int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
+
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {
   if (D == 128) { TKV_DISPATCH_G(run_finish, 128, true, a, st) }
   if (D == 64) { TKV_DISPATCH_G(run_finish, 64, true, a, st) }
   return hipErrorInvalidValue;
 }
+#endif
 
 }  // namespace tkv

@@ -26,6 +26,9 @@ struct EvPair { hipEvent_t a, b; int64_t bytes; int dir; };  // dir 0 = D2H, 1 =
 
 }  // namespace
 
+// one bounce-buffer piece of a layer's demoted rows: gather -> D2H -> H2D -> scatter
+struct XferJob { int layer; int r0; int nrows; int piece; int64_t host_row; bool last_of_layer; };
+
 struct tkv_cache {
   tkv_config cfg{};
   DevView dv{};
@@ -51,6 +54,9 @@ struct tkv_cache {
   hipEvent_t ev_plan = nullptr, ev_piece[RING] = {};
   std::vector<hipEvent_t> ev_ready;
   std::vector<char> layer_wait;
+  std::vector<char> layer_enq;      // ev_ready[l] has been recorded for the current re-tiering event
+  std::vector<XferJob> jobs;        // transfer pieces of the current event, in layer order
+  size_t jobs_next = 0;
   char* bounceA = nullptr; char* bounceB = nullptr;
   size_t bounce_bytes = 0;
   bool transfers_in_flight = false;
@@ -139,7 +145,54 @@ EvPair* next_pair(std::vector<EvPair>& pool, size_t& used) {
 }
 
 // waits for the side streams and folds the copy timings into the stats
+tkv_status enqueue_job(tkv_cache* c, const XferJob& j) {
+  const DevView& v = c->dv;
+  const size_t slot_bytes = c->bounce_bytes / RING;
+  const size_t bytes = (size_t)j.nrows * c->tok_bytes;
+  char* ba = c->bounceA + (size_t)(j.piece % RING) * slot_bytes;
+  char* bb = c->bounceB + (size_t)(j.piece % RING) * slot_bytes;
+  char* hp = c->hstore + ((size_t)j.layer * c->host_rows + (size_t)j.host_row) * c->tok_bytes;
+  if (!next_pair(c->copy_events, c->copy_events_used) || !next_pair(c->copy_events, c->copy_events_used))
+    return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+  EvPair* ea = &c->copy_events[c->copy_events_used - 2];
+  EvPair* eb = &c->copy_events[c->copy_events_used - 1];
+  ea->dir = 0; eb->dir = 1; ea->bytes = eb->bytes = (int64_t)bytes;
+  HIPCHK(c, launch_gather(v, j.layer, j.r0, j.nrows, ba, c->sA));
+  HIPCHK(c, hipEventRecord(ea->a, c->sA));
+  HIPCHK(c, hipMemcpyAsync(hp, ba, bytes, hipMemcpyDeviceToHost, c->sA));
+  HIPCHK(c, hipEventRecord(ea->b, c->sA));
+  HIPCHK(c, hipEventRecord(c->ev_piece[j.piece % RING], c->sA));
+  HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_piece[j.piece % RING], 0));
+  HIPCHK(c, hipEventRecord(eb->a, c->sB));
+  HIPCHK(c, hipMemcpyAsync(bb, hp, bytes, hipMemcpyHostToDevice, c->sB));
+  HIPCHK(c, hipEventRecord(eb->b, c->sB));
+  HIPCHK(c, launch_scatter(v, j.layer, j.r0, j.nrows, bb, c->sB));
+  c->st.d2h_bytes += (int64_t)bytes; c->st.h2d_bytes += (int64_t)bytes;
+  c->st.d2h_copies++; c->st.h2d_copies++;
+  if (j.last_of_layer) {
+    HIPCHK(c, hipEventRecord(c->ev_ready[j.layer], c->sB));
+    c->layer_enq[j.layer] = 1;
+  }
+  return TKV_OK;
+}
+
+// issues the queued transfer pieces of up to `n_layers` further layers on the side streams
+tkv_status pump_transfers(tkv_cache* c, int n_layers) {
+  while (c->jobs_next < c->jobs.size() && n_layers > 0) {
+    const XferJob& j = c->jobs[c->jobs_next++];
+    tkv_status s = enqueue_job(c, j);
+    if (s != TKV_OK) return s;
+    if (j.last_of_layer) --n_layers;
+  }
+  return TKV_OK;
+}
+
 tkv_status drain_transfers(tkv_cache* c) {
+  if (c->jobs_next < c->jobs.size()) {
+    tkv_status s = pump_transfers(c, c->cfg.n_layers);
+    if (s != TKV_OK) return s;
+  }
+  c->jobs.clear(); c->jobs_next = 0;
   if (c->transfers_in_flight) {
     HIPCHK(c, hipStreamSynchronize(c->sA));
     HIPCHK(c, hipStreamSynchronize(c->sB));
@@ -154,6 +207,7 @@ tkv_status drain_transfers(tkv_cache* c) {
   }
   c->copy_events_used = 0;
   std::fill(c->layer_wait.begin(), c->layer_wait.end(), 0);
+  std::fill(c->layer_enq.begin(), c->layer_enq.end(), 0);
   return TKV_OK;
 }
 
@@ -250,8 +304,13 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   ok = ok && dalloc(c, v.g_seq, BN) && dalloc(c, v.g_src, BN) && dalloc(c, v.g_dst, BN);
   ok = ok && dalloc(c, c->d_host_base, (size_t)B);
   v.host_base = c->d_host_base;
-  c->S_alloc = N / TOK_PER_BLOCK + 2;
-  c->xs_stride = c->S_alloc * TOK_PER_BLOCK;
+  {
+    // two attention workgroups fit a compute unit's LDS: that many per (sequence, kv head) pair, as far as the pairs go round
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess || cus <= 0) cus = 256;
+    c->S_alloc = std::max(1, 2 * cus / std::max(1, B * Hkv));
+  }
+  c->xs_stride = (N / TOK_PER_BLOCK + 2) * TOK_PER_BLOCK;
   ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
   ok = ok && dalloc(c, c->part_ml, (size_t)B * Hkv * c->S_alloc * 2 * G);
   ok = ok && dalloc(c, c->part_o, (size_t)B * Hkv * c->S_alloc * G * D);
@@ -274,6 +333,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   c->ntier.assign(4, 0);
   c->ev_ready.assign(L, nullptr);
   c->layer_wait.assign(L, 0);
+  c->layer_enq.assign(L, 0);
   // default-priority streams only
   if (hipStreamCreateWithFlags(&c->sA, hipStreamNonBlocking) != hipSuccess ||
       hipStreamCreateWithFlags(&c->sB, hipStreamNonBlocking) != hipSuccess)
@@ -342,20 +402,28 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   bool use_old = false;
   if (c->layer_wait[layer]) {
     if (c->cfg.prefetch_mode == TKV_PREFETCH_WAIT) {
+      while (!c->layer_enq[layer] && c->jobs_next < c->jobs.size()) {
+        tkv_status ps = pump_transfers(c, 1);
+        if (ps != TKV_OK) return ps;
+      }
       HIPCHK(c, hipStreamWaitEvent(st, c->ev_ready[layer], 0));
       c->layer_wait[layer] = 0;
       c->st.attend_waits++;
     } else {
-      hipError_t e = hipEventQuery(c->ev_ready[layer]);
+      // a layer whose pieces are still queued on the host keeps its old slots, like one whose copies are in flight
+      hipError_t e = c->layer_enq[layer] ? hipEventQuery(c->ev_ready[layer]) : hipErrorNotReady;
       if (e == hipSuccess) c->layer_wait[layer] = 0;
       else if (e == hipErrorNotReady) { use_old = true; c->st.lazy_old_reads++; }
       else return fail(c, TKV_EDEVICE, "hipEventQuery failed: %s", hipGetErrorString(e));
     }
   }
-  int S = 1;
+  int n_tiles = 1;
   for (int b = 0; b < v.B; ++b)
-    S = std::max(S, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK + (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
-  if (S > c->S_alloc) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal split count %d > %d", S, c->S_alloc);
+    n_tiles = std::max(n_tiles, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK + (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
+  if (n_tiles * TOK_PER_BLOCK > c->xs_stride) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal tile count %d exceeds the scratch", n_tiles);
+  // no more workgroups per pair than there are tiles for their waves
+  const int nw = attn_waves_per_group(v.D, c->bf16);
+  const int S = std::max(1, std::min(c->S_alloc, (n_tiles + nw - 1) / nw));
   AttnArgs a{};
   const size_t lrows = (size_t)layer * v.B * v.Hkv;
   a.fpK = v.fpK + lrows * v.capF * v.D * v.es; a.fpV = v.fpV + lrows * v.capF * v.D * v.es;
@@ -365,9 +433,13 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   a.f_loc = use_old ? v.f_loc_old : v.f_loc; a.f_pos = v.f_pos; a.q_loc = v.q_loc; a.q_pos = v.q_pos;
   a.cnt = v.cnt; a.score = v.score; a.xs = c->xs; a.part_ml = c->part_ml; a.part_o = c->part_o;
   a.q_es = c->es;
-  if (v.B <= ATTN_ARG_SEQS) for (int b = 0; b < v.B; ++b) { a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b]; }
+  if (v.B <= ATTN_ARG_SEQS)
+    for (int b = 0; b < v.B; ++b) {
+      a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b];
+      a.nWq[b] = attn_q_waves(S * nw, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK, (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
+    }
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capF; a.cap2 = v.cap2;
-  a.S = S; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
+  a.S = S; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
   EvPair* pe = nullptr;
   if (c->cfg.profile) {
@@ -376,6 +448,9 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   }
   HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
+  // lazy mode spreads the issue of a re-tiering event's copies over the following attention calls, one layer each,
+  // so the compute stream is never left empty while the host queues them
+  if (c->jobs_next < c->jobs.size()) return pump_transfers(c, 1);
   return TKV_OK;
 }
 
@@ -484,33 +559,18 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     const size_t slot_bytes = c->bounce_bytes / RING;
     const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
     int piece = 0;
+    c->jobs.clear(); c->jobs_next = 0;
     for (int l = 0; l < L; ++l) {
       for (int64_t r0 = 0; r0 < total_new_t1; r0 += piece_rows, ++piece) {
         const int nrows = (int)std::min<int64_t>(piece_rows, total_new_t1 - r0);
-        const size_t bytes = (size_t)nrows * c->tok_bytes;
-        char* ba = c->bounceA + (size_t)(piece % RING) * slot_bytes;
-        char* bb = c->bounceB + (size_t)(piece % RING) * slot_bytes;
-        char* hp = c->hstore + ((size_t)l * c->host_rows + (size_t)(c->host_next + r0)) * c->tok_bytes;
-        if (!next_pair(c->copy_events, c->copy_events_used) || !next_pair(c->copy_events, c->copy_events_used))
-          return fail(c, TKV_EDEVICE, "hipEventCreate failed");
-        EvPair* ea = &c->copy_events[c->copy_events_used - 2];
-        EvPair* eb = &c->copy_events[c->copy_events_used - 1];
-        ea->dir = 0; eb->dir = 1; ea->bytes = eb->bytes = (int64_t)bytes;
-        HIPCHK(c, launch_gather(v, l, (int)r0, nrows, ba, c->sA));
-        HIPCHK(c, hipEventRecord(ea->a, c->sA));
-        HIPCHK(c, hipMemcpyAsync(hp, ba, bytes, hipMemcpyDeviceToHost, c->sA));
-        HIPCHK(c, hipEventRecord(ea->b, c->sA));
-        HIPCHK(c, hipEventRecord(c->ev_piece[piece % RING], c->sA));
-        HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_piece[piece % RING], 0));
-        HIPCHK(c, hipEventRecord(eb->a, c->sB));
-        HIPCHK(c, hipMemcpyAsync(bb, hp, bytes, hipMemcpyHostToDevice, c->sB));
-        HIPCHK(c, hipEventRecord(eb->b, c->sB));
-        HIPCHK(c, launch_scatter(v, l, (int)r0, nrows, bb, c->sB));
-        c->st.d2h_bytes += (int64_t)bytes; c->st.h2d_bytes += (int64_t)bytes;
-        c->st.d2h_copies++; c->st.h2d_copies++;
+        c->jobs.push_back(XferJob{l, (int)r0, nrows, piece, c->host_next + r0, r0 + piece_rows >= total_new_t1});
       }
-      HIPCHK(c, hipEventRecord(c->ev_ready[l], c->sB));
       c->layer_wait[l] = 1;
+      c->layer_enq[l] = 0;
+    }
+    if (c->cfg.prefetch_mode == TKV_PREFETCH_WAIT) {
+      tkv_status ps = pump_transfers(c, L);
+      if (ps != TKV_OK) return ps;
     }
     c->transfers_in_flight = true;
     c->host_next += total_new_t1;

@@ -21,14 +21,7 @@ enum Cnt : int {
   CNT_N = 28
 };
 
-#ifndef TKV_TOK_PER_BLOCK
-#define TKV_TOK_PER_BLOCK 256
-#endif
-constexpr int TOK_PER_BLOCK = TKV_TOK_PER_BLOCK;  // list entries one attention workgroup owns (split granularity)
-#ifndef TKV_ATTN_THREADS
-#define TKV_ATTN_THREADS 256
-#endif
-constexpr int ATTN_THREADS = TKV_ATTN_THREADS;
+constexpr int TOK_PER_BLOCK = 64;    // list entries per attention tile (one per lane of a wave)
 constexpr int PLAN_THREADS = 1024;
 constexpr int MAX_G = 8;
 constexpr int ATTN_ARG_SEQS = 64;    // list lengths travel as kernel arguments up to this batch size
@@ -76,17 +69,22 @@ struct AttnArgs {
   const int* f_loc; const int* f_pos; const int* q_loc; const int* q_pos;
   const int* cnt;
   float* score;
-  float* xs;        // [B][Hkv][G][xs_stride] scaled logits by list index (F entries, then Q entries from f_pad)
-  float* part_ml;   // [B][Hkv][S][2][G]  (m, l) of each split
+  float* xs;        // [B][Hkv][G][xs_stride] scaled logits by list index (F tiles, then Q tiles)
+  float* part_ml;   // [B][Hkv][S][2][G]  (m, l) of each split (= workgroup)
   float* part_o;    // [B][Hkv][S][G][D]
-  int B, Hq, Hkv, Nmax, capF, cap2, S, xs_stride, cb, sb, t2fmt, out_bf16, q_es;
+  int S;            // workgroups per (sequence, kv head)
+  int n_tiles;      // max over the sequences of F tiles + Q tiles
+  int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_bf16, q_es;
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
+  int nWq[ATTN_ARG_SEQS];                     // waves of each (sequence, kv head) pair that serve the Q list (same condition)
 };
 
 // launchers (defined in the .hip files)
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
+int attn_waves_per_group(int D, bool bf16);   // waves per attention workgroup for this row size
+int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles);   // how many of a pair's waves serve the Q list
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
 hipError_t launch_append_step(const DevView& v, const void* k, const void* v_, int pos, hipStream_t st);
