@@ -647,10 +647,13 @@ template <int D, bool BF16>
 struct KernelGeo {
   static constexpr Mode MF = BF16 ? F_BF16 : F_F32;
   static constexpr int RB = Geo<D, MF>::RB;
-  static constexpr int NW = RB > 256 ? 2 : 4;          // waves per workgroup; two workgroups share a compute unit's LDS
+  static constexpr int NW = RB > 256 ? 2 : 4;          // waves per workgroup; two workgroups fit a compute unit's LDS
   static constexpr int EV = Geo<D, MF>::EV;
   static constexpr int LPRV = Geo<D, MF>::LPRV;
 };
+// Workgroups per compute unit the kernel is compiled for: two while a wave's registers (query slices and output
+// accumulators grow with the group size) fit half a SIMD's file, else one.
+constexpr int groups_per_cu(int G) { return G <= 5 ? 2 : 1; }
 
 // Waves of a (sequence, kv head) pair that serve the Q list, out of nwv, for nft F tiles and nqt Q tiles: the split
 // that minimises the longest wave.  A code tile moves fewer bytes than a full-precision one but costs more vector
@@ -669,7 +672,7 @@ __host__ __device__ inline int q_waves(int nwv, int nft, int nqt) {
 }
 
 template <int D, int G, bool BF16>
-__global__ __launch_bounds__((KernelGeo<D, BF16>::NW * 64), 2) void k_attn_tiered(const AttnArgs a) {
+__global__ __launch_bounds__((KernelGeo<D, BF16>::NW * 64), groups_per_cu(G)) void k_attn_tiered(const AttnArgs a) {
   using KG = KernelGeo<D, BF16>;
   constexpr int NW = KG::NW, EV = KG::EV, LPRV = KG::LPRV, GP = GPad<G>::v;
   constexpr int TILE_BYTES = 64 * KG::RB;
@@ -955,6 +958,7 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStr
 }
 int attn_waves_per_group(int D, bool bf16) { return D * (bf16 ? 2 : 4) > 256 ? 2 : 4; }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
+int attn_groups_per_cu(int G) { return groups_per_cu(G); }
 
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {
   if (D == 128) { TKV_DISPATCH_G(run_finish, 128, true, a, st) }

@@ -305,10 +305,10 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   ok = ok && dalloc(c, c->d_host_base, (size_t)B);
   v.host_base = c->d_host_base;
   {
-    // two attention workgroups fit a compute unit's LDS: that many per (sequence, kv head) pair, as far as the pairs go round
+    // as many attention workgroups per (sequence, kv head) pair as the chip holds at once, as far as the pairs go round
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess || cus <= 0) cus = 256;
-    c->S_alloc = std::max(1, 2 * cus / std::max(1, B * Hkv));
+    c->S_alloc = std::max(1, attn_groups_per_cu(G) * cus / std::max(1, B * Hkv));
   }
   c->xs_stride = (N / TOK_PER_BLOCK + 2) * TOK_PER_BLOCK;
   ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
