@@ -124,15 +124,31 @@ __device__ __forceinline__ float rdlane(float x, int l) {
 
 // whole-wave reductions: 16-lane rows by DPP, rows 0/1 and 2/3 by row_bcast15, halves by row_bcast31; lane 63 has
 // the result, which is returned in a scalar register
-template <int CTRL>
-__device__ __forceinline__ float dpp_ninf(float x) {     // lanes without a source read -inf, the identity of max
-  return __builtin_amdgcn_update_dpp(-INFINITY, x, CTRL, 0xf, 0xf, false);
-}
-__device__ __forceinline__ float wave_max(float x) {
-  x = fmaxf(x, dpp_ninf<0xB1>(x)); x = fmaxf(x, dpp_ninf<0x4E>(x)); x = fmaxf(x, dpp_ninf<0x141>(x)); x = fmaxf(x, dpp_ninf<0x140>(x));
-  x = fmaxf(x, dpp_rows<0x142, 0xA>(x));
-  x = fmaxf(x, dpp_rows<0x143, 0xC>(x));
-  return rdlane(x, 63);
+// Whole-wave maxima of G values at once: 16-lane rows by DPP (quad swaps, half mirror, mirror), then row_bcast15
+// (lane 15 of a row into the next row) and row_bcast31 (lane 31 into the upper half); afterwards LANE 63 ALONE holds
+// the maximum of each value (the other lanes are not kept consistent by the last two steps).  The DPP form of v_max
+// is written out because the compiler would put a quieting v_max and a separate DPP move around every step.  A DPP
+// operand may not be read in the two instructions after the one that wrote it: the steps go value by value, so with
+// three or more values the other values' instructions fill that gap, otherwise an s_nop does.  Source and
+// destination are separate operands, so the register allocator has no reason to slip a copy in front of a step.
+template <int G>
+__device__ __forceinline__ void wave_max_all(float (&x)[G]) {
+#define TKV_MAX_STEP(CTRL)                                                                             \
+  _Pragma("unroll") for (int h = 0; h < G; ++h) {                                                      \
+    float r;                                                                                           \
+    if (G < 3 || h == 0) asm volatile("s_nop 1");                                                      \
+    asm volatile("v_max_f32_dpp %0, %1, %1 " CTRL : "=v"(r) : "v"(x[h]));                              \
+    x[h] = r;                                                                                          \
+  }
+  // every value is in its register before the first step (the s_nop of that step then covers the last writer)
+  _Pragma("unroll") for (int h = 0; h < G; ++h) asm volatile("" : : "v"(x[h]));
+  TKV_MAX_STEP("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+  TKV_MAX_STEP("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+  TKV_MAX_STEP("row_half_mirror row_mask:0xf bank_mask:0xf")
+  TKV_MAX_STEP("row_mirror row_mask:0xf bank_mask:0xf")
+  TKV_MAX_STEP("row_bcast:15 row_mask:0xa bank_mask:0xf")
+  TKV_MAX_STEP("row_bcast:31 row_mask:0xc bank_mask:0xf")
+#undef TKV_MAX_STEP
 }
 __device__ __forceinline__ float wave_sum(float x) {
   x = group_sum<16>(x);
@@ -482,7 +498,6 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   for (int s = 0; s < N_K; ++s) issue_k_piece(s);
 
   int par = 1;                                           // LDS half that holds the next tile's slot list
-  bool first = true;
   auto tile_body = [&](int tile, auto more_c) {
     constexpr bool MORE = decltype(more_c)::value;
     constexpr int X = MORE ? 1 : 0;                      // operations of the parts a last tile does not issue
@@ -550,16 +565,22 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
       float pv[GP];
 #pragma unroll
       for (int h = 0; h < GP; ++h) pv[h] = 0.f;
+      float x[G], xm[G];
 #pragma unroll
       for (int h = 0; h < G; ++h) {
-        const float x = valid ? xt[h] * a.softmax_scale : -INFINITY;
-        if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x;
-        const float tm = wave_max(x);
-        float mn;
-        if (first) { mn = tm; corr[h] = 0.f; }
-        else { mn = fmaxf(m_run[h], tm); corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E); }
-        const float p = valid ? __builtin_amdgcn_exp2f((x - mn) * LOG2E) : 0.f;
-        l_lane[h] = first ? p : fmaf(l_lane[h], corr[h], p);
+        x[h] = valid ? xt[h] * a.softmax_scale : -INFINITY;
+        if (valid) a.xs[xbase + (size_t)h * a.xs_stride] = x[h];
+        xm[h] = x[h];
+      }
+      wave_max_all<G>(xm);
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        // m_run starts at -inf and every tile has a live entry, so the first tile needs no special case:
+        // corr = exp2(-inf) = 0 there, against zero accumulators
+        const float mn = fmaxf(m_run[h], rdlane(xm[h], 63));
+        corr[h] = __builtin_amdgcn_exp2f((m_run[h] - mn) * LOG2E);
+        const float p = valid ? __builtin_amdgcn_exp2f((x[h] - mn) * LOG2E) : 0.f;
+        l_lane[h] = fmaf(l_lane[h], corr[h], p);
         m_run[h] = mn;
         pv[h] = p;
       }
@@ -571,7 +592,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
         lds_wr128<c * 16>(p_wr, t);
       });
     }
-    if (!first) {
+    {
       // the running maxima are wave-uniform; once they have settled no head needs rescaling (x * 1.0f is exact)
       bool moved = false;
 #pragma unroll
@@ -627,7 +648,6 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
       if constexpr (it + 1 < NITV) read_v(std::integral_constant<int, (it + 1 < NITV ? it + 1 : NITV - 1)>{}, vb[(it + 1) & 1]);
       row_accumulate<D, G, M>(vb[it & 1], GE::IS_Q ? vsc[it] : 0.f, o, osub);
     });
-    first = false;
     par ^= 1;
   };
 
@@ -802,6 +822,19 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   const int cf = (nF + TB - 1) / TB, ns = a.S;
   const bool is_tile = (int)blockIdx.x < n_tiles;
   if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
+  // tile workgroups: the entry's position and its first kv head's logits are fetched before the (m, l) merge, so
+  // their latency runs beside it
+  const int e = t & 63, hg = t >> 6;
+  const int j = blockIdx.x * 64 + e;
+  int pos = -1;
+  float x0[G];
+  if (is_tile) {
+    const bool live = j < nF || (j >= cf * TB && j - cf * TB < nQ);
+    if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
+    else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
+#pragma unroll
+    for (int g = 0; g < G; ++g) x0[g] = (live && hg < a.Hkv) ? a.xs[((size_t)b * a.Hq + hg * G + g) * a.xs_stride + j] : 0.f;
+  }
   // (m, l) of every split of this sequence: part_ml[b][kvh][s][2][G], s < ns
   const float* pmb = a.part_ml + (size_t)b * a.Hkv * a.S * 2 * G;
   const int per_kvh = ns * 2 * G;
@@ -827,17 +860,12 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   if (is_tile) {
     // 64 list entries per workgroup; thread (e, hg) sums the softmax weights of kv heads hg, hg+4, ... (all G members
     // of each), then the four partial sums of an entry are added in the fixed order hg = 0, 1, 2, 3
-    const int e = t & 63, hg = t >> 6;
-    const int j = blockIdx.x * 64 + e;
-    int pos = -1;
-    if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
-    else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
     float acc = 0.f;
     if (pos >= 0) {
       for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
         float x[G];
 #pragma unroll
-        for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)b * a.Hq + kvh * G + g) * a.xs_stride + j];
+        for (int g = 0; g < G; ++g) x[g] = (kvh == hg) ? x0[g] : a.xs[((size_t)b * a.Hq + kvh * G + g) * a.xs_stride + j];
 #pragma unroll
         for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[kvh * G + g]) * LOG2E) * IL[kvh * G + g];
       }
