@@ -150,6 +150,23 @@ __device__ __forceinline__ void wave_max_all(float (&x)[G]) {
   TKV_MAX_STEP("row_bcast:31 row_mask:0xc bank_mask:0xf")
 #undef TKV_MAX_STEP
 }
+// Sums of G values over aligned groups of 8 lanes, every lane of a group receiving the result; same scheme (and the
+// same reason for writing the DPP form out) as wave_max_all.
+template <int G>
+__device__ __forceinline__ void group_sum8_all(float (&x)[G]) {
+#define TKV_ADD_STEP(CTRL)                                                                             \
+  _Pragma("unroll") for (int h = 0; h < G; ++h) {                                                      \
+    float r;                                                                                           \
+    if (G < 3 || h == 0) asm volatile("s_nop 1");                                                      \
+    asm volatile("v_add_f32_dpp %0, %1, %1 " CTRL : "=v"(r) : "v"(x[h]));                              \
+    x[h] = r;                                                                                          \
+  }
+  _Pragma("unroll") for (int h = 0; h < G; ++h) asm volatile("" : : "v"(x[h]));
+  TKV_ADD_STEP("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+  TKV_ADD_STEP("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+  TKV_ADD_STEP("row_half_mirror row_mask:0xf bank_mask:0xf")
+#undef TKV_ADD_STEP
+}
 __device__ __forceinline__ float wave_sum(float x) {
   x = group_sum<16>(x);
   const float a = rdlane(x, 0) + rdlane(x, 16), b = rdlane(x, 32) + rdlane(x, 48);
@@ -271,8 +288,9 @@ __device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D
         for (int c = 0; c < EUK / 2; ++c)
           acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, unit_word<KS>(kr.u[j], c)),
                                                 __builtin_bit_cast(bf16x2, q.qp[h][j][c]), acc, false);
-      x[h] = group_sum<8>(acc);
+      x[h] = acc;
     }
+    group_sum8_all<G>(x);
   } else if constexpr (M == F_F32) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -281,8 +299,9 @@ __device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D
       for (int j = 0; j < KU; ++j)
 #pragma unroll
         for (int c = 0; c < EUK; ++c) acc = fmaf(__builtin_bit_cast(float, unit_word<KS>(kr.u[j], c)), q.qf[h][j][c], acc);
-      x[h] = group_sum<8>(acc);
+      x[h] = acc;
     }
+    group_sum8_all<G>(x);
   } else {
     float tot[G];
 #pragma unroll
@@ -311,9 +330,10 @@ __device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D
         else tot[h] += acc;
       }
     }
+    group_sum8_all<G>(tot);
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      x[h] = group_sum<8>(tot[h]);
+      x[h] = tot[h];
       if constexpr (M == Q_INT8) x[h] *= sc[0];                         // per-row scale
     }
   }
