@@ -129,8 +129,10 @@ __device__ __forceinline__ float rdlane(float x, int l) {
 // the maximum of each value (the other lanes are not kept consistent by the last two steps).  The DPP form of v_max
 // is written out because the compiler would put a quieting v_max and a separate DPP move around every step.  A DPP
 // operand may not be read in the two instructions after the one that wrote it: the steps go value by value, so with
-// three or more values the other values' instructions fill that gap, otherwise an s_nop does.  Source and
-// destination are separate operands, so the register allocator has no reason to slip a copy in front of a step.
+// three or more values the other values' instructions fill that gap, otherwise an s_nop does.  The values may come
+// straight out of dot instructions, whose results an ordinary VALU instruction may not read for three instructions
+// (the compiler pads its own code for this, not inline asm): hence the longer s_nop before the first step.  Source
+// and destination are separate operands, so the register allocator has no reason to slip a copy in front of a step.
 template <int G>
 __device__ __forceinline__ void wave_max_all(float (&x)[G]) {
 #define TKV_MAX_STEP(CTRL)                                                                             \
@@ -140,8 +142,9 @@ __device__ __forceinline__ void wave_max_all(float (&x)[G]) {
     asm volatile("v_max_f32_dpp %0, %1, %1 " CTRL : "=v"(r) : "v"(x[h]));                              \
     x[h] = r;                                                                                          \
   }
-  // every value is in its register before the first step (the s_nop of that step then covers the last writer)
+  // every value is in its register before the first step, and its writer is far enough behind
   _Pragma("unroll") for (int h = 0; h < G; ++h) asm volatile("" : : "v"(x[h]));
+  asm volatile("s_nop 3");
   TKV_MAX_STEP("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
   TKV_MAX_STEP("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
   TKV_MAX_STEP("row_half_mirror row_mask:0xf bank_mask:0xf")
@@ -162,6 +165,7 @@ __device__ __forceinline__ void group_sum8_all(float (&x)[G]) {
     x[h] = r;                                                                                          \
   }
   _Pragma("unroll") for (int h = 0; h < G; ++h) asm volatile("" : : "v"(x[h]));
+  asm volatile("s_nop 3");
   TKV_ADD_STEP("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
   TKV_ADD_STEP("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
   TKV_ADD_STEP("row_half_mirror row_mask:0xf bank_mask:0xf")

@@ -31,6 +31,8 @@ def _mass(cfg, calls):
     ("bf16", 64, 16, 2, 256),    # group 8, exactly one split
     ("bf16", 128, 6, 2, 1),      # single token
     ("bf16", 64, 6, 3, 255),     # group 2
+    ("bf16", 128, 4, 4, 300),    # group 1 on bf16 rows: dot-instruction results feed the hand-written DPP steps directly
+    ("bf16", 64, 3, 3, 65),      # group 1, head_dim 64
 ])
 def test_all_t0_attention_and_scores(kv_dtype, D, Hq, Hkv, ctx):
     from gpu_common import assert_out_close, assert_scores_close

@@ -88,3 +88,20 @@ def test_decode_step_equals_per_layer_calls():
     assert np.array_equal(a.gpu.get_scores().view(np.uint32), b.gpu.get_scores().view(np.uint32))
     assert np.array_equal(a.gpu.get_tiers(), b.gpu.get_tiers())
     a.close(); b.close()
+
+
+def test_many_tiles_per_wave():
+    """256 (sequence, kv head) pairs leave two workgroups per pair: every wave walks 8+ tiles of list F and the Q waves
+    several of list Q, so the steady-state part of the fetch pipeline (not only its first and last tile) is compared
+    element by element."""
+    cfg = small_config(name="deep", n_layers=1, batch=32, n_q_heads=8, n_kv_heads=8, head_dim=64, kv_dtype="bf16",
+                       context=4200, decode_steps=3, policy_ppm=(300_000, 400_000, 270_000, 30_000), k_window=64)
+    _run_shape(cfg, "lazy", steps_before=1, steps_after=1)
+
+
+def test_batch_above_the_kernel_argument_limit():
+    """More than 64 sequences: list lengths and the wave split are read from device counters instead of kernel
+    arguments."""
+    cfg = small_config(name="wide", n_layers=1, batch=70, n_q_heads=4, n_kv_heads=2, head_dim=64, kv_dtype="f32",
+                       context=200, decode_steps=3, policy_ppm=(400_000, 300_000, 250_000, 50_000), k_window=16)
+    _run_shape(cfg, "wait", steps_before=1, steps_after=1)
