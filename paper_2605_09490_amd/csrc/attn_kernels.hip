@@ -687,17 +687,23 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   }
 }
 
-template <int D, bool BF16>
+// Waves per SIMD the kernel is compiled for: two while a wave's registers (query slices and output accumulators grow
+// with the group size) fit half a SIMD's file, else one.
+constexpr int waves_per_simd(int G) { return G <= 5 ? 2 : 1; }
+// One workgroup per compute unit: as many waves as the register budget allows (4 SIMDs) and as fit the LDS with a
+// whole-tile buffer each (64 rows: 16 KB at 256-byte rows, 32 KB at 512-byte rows).
+constexpr int waves_per_group(int row_bytes, int G) {
+  return (row_bytes > 256 && waves_per_simd(G) * 4 > 4) ? 4 : waves_per_simd(G) * 4;
+}
+
+template <int D, int G, bool BF16>
 struct KernelGeo {
   static constexpr Mode MF = BF16 ? F_BF16 : F_F32;
   static constexpr int RB = Geo<D, MF>::RB;
-  static constexpr int NW = RB > 256 ? 2 : 4;          // waves per workgroup; two workgroups fit a compute unit's LDS
+  static constexpr int NW = waves_per_group(RB, G);
   static constexpr int EV = Geo<D, MF>::EV;
   static constexpr int LPRV = Geo<D, MF>::LPRV;
 };
-// Workgroups per compute unit the kernel is compiled for: two while a wave's registers (query slices and output
-// accumulators grow with the group size) fit half a SIMD's file, else one.
-constexpr int groups_per_cu(int G) { return G <= 5 ? 2 : 1; }
 
 // Waves of a (sequence, kv head) pair that serve the Q list, out of nwv, for nft F tiles and nqt Q tiles: the split
 // that minimises the longest wave.  A code tile moves fewer bytes than a full-precision one but costs more vector
@@ -716,8 +722,8 @@ __host__ __device__ inline int q_waves(int nwv, int nft, int nqt) {
 }
 
 template <int D, int G, bool BF16>
-__global__ __launch_bounds__((KernelGeo<D, BF16>::NW * 64), groups_per_cu(G)) void k_attn_tiered(const AttnArgs a) {
-  using KG = KernelGeo<D, BF16>;
+__global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, BF16>::NW / 4)) void k_attn_tiered(const AttnArgs a) {
+  using KG = KernelGeo<D, G, BF16>;
   constexpr int NW = KG::NW, EV = KG::EV, LPRV = KG::LPRV, GP = GPad<G>::v;
   constexpr int TILE_BYTES = 64 * KG::RB;
   static_assert(G * D * 4 <= TILE_BYTES, "a wave's output partial is parked in its tile buffer");
@@ -846,18 +852,19 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   const int cf = (nF + TB - 1) / TB, ns = a.S;
   const bool is_tile = (int)blockIdx.x < n_tiles;
   if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
-  // tile workgroups: the entry's position and its first kv head's logits are fetched before the (m, l) merge, so
-  // their latency runs beside it
+  // tile workgroups: the entry's position, its first kv head's logits and its score so far are fetched before the
+  // (m, l) merge, so their latency runs beside it
   const int e = t & 63, hg = t >> 6;
   const int j = blockIdx.x * 64 + e;
   int pos = -1;
-  float x0[G];
+  float x0[G], score_old = 0.f;
   if (is_tile) {
     const bool live = j < nF || (j >= cf * TB && j - cf * TB < nQ);
     if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
     else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
 #pragma unroll
     for (int g = 0; g < G; ++g) x0[g] = (live && hg < a.Hkv) ? a.xs[((size_t)b * a.Hq + hg * G + g) * a.xs_stride + j] : 0.f;
+    if (hg == 0 && pos >= 0) score_old = a.score[(size_t)b * a.Nmax + pos];
   }
   // (m, l) of every split of this sequence: part_ml[b][kvh][s][2][G], s < ns
   const float* pmb = a.part_ml + (size_t)b * a.Hkv * a.S * 2 * G;
@@ -899,7 +906,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
     __syncthreads();
     if (hg == 0 && pos >= 0) {
       const float tot = ((sm_pm[e] + sm_pm[64 + e]) + sm_pm[128 + e]) + sm_pm[192 + e];
-      a.score[(size_t)b * a.Nmax + pos] += a.score_scale * tot;
+      a.score[(size_t)b * a.Nmax + pos] = score_old + a.score_scale * tot;
     }
   } else {
     // one workgroup per query head: thread (d, sg) sums the splits sg, sg+NSG, ... of output element d, then the NSG
@@ -958,7 +965,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 template <int D, int G, bool BF16>
 static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   dim3 grid(a.S, a.Hkv, a.B);
-  constexpr int threads = KernelGeo<D, BF16>::NW * 64;
+  constexpr int threads = KernelGeo<D, G, BF16>::NW * 64;
   if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
   else hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(threads), 0, st, a);
   return hipGetLastError();
@@ -1008,9 +1015,8 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStr
   if (D == 64 && !bf16) return tiered_by_group<64, false>(a, G, st, ev0, ev1);
   return hipErrorInvalidValue;
 }
-int attn_waves_per_group(int D, bool bf16) { return D * (bf16 ? 2 : 4) > 256 ? 2 : 4; }
+int attn_waves_per_group(int D, bool bf16, int G) { return waves_per_group(D * (bf16 ? 2 : 4), G); }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
-int attn_groups_per_cu(int G) { return groups_per_cu(G); }
 
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {
   if (D == 128) { TKV_DISPATCH_G(run_finish, 128, true, a, st) }

@@ -305,10 +305,10 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   ok = ok && dalloc(c, c->d_host_base, (size_t)B);
   v.host_base = c->d_host_base;
   {
-    // as many attention workgroups per (sequence, kv head) pair as the chip holds at once, as far as the pairs go round
+    // one attention workgroup per compute unit: that many per (sequence, kv head) pair, as far as the pairs go round
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess || cus <= 0) cus = 256;
-    c->S_alloc = std::max(1, attn_groups_per_cu(G) * cus / std::max(1, B * Hkv));
+    c->S_alloc = std::max(1, cus / std::max(1, B * Hkv));
   }
   c->xs_stride = (N / TOK_PER_BLOCK + 2) * TOK_PER_BLOCK;
   ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
@@ -422,7 +422,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
     n_tiles = std::max(n_tiles, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK + (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
   if (n_tiles * TOK_PER_BLOCK > c->xs_stride) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal tile count %d exceeds the scratch", n_tiles);
   // no more workgroups per pair than there are tiles for their waves
-  const int nw = attn_waves_per_group(v.D, c->bf16);
+  const int nw = attn_waves_per_group(v.D, c->bf16, c->G);
   const int S = std::max(1, std::min(c->S_alloc, (n_tiles + nw - 1) / nw));
   AttnArgs a{};
   const size_t lrows = (size_t)layer * v.B * v.Hkv;

@@ -83,8 +83,7 @@ struct AttnArgs {
 // launchers (defined in the .hip files)
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
-int attn_waves_per_group(int D, bool bf16);   // waves per attention workgroup for this row size
-int attn_groups_per_cu(int G);                 // attention workgroups resident per compute unit
+int attn_waves_per_group(int D, bool bf16, int G);   // waves per attention workgroup (one workgroup per compute unit)
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles);   // how many of a pair's waves serve the Q list
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
