@@ -3,13 +3,14 @@
 //   attn_tiered : grid (S, Hkv, B), one workgroup per compute unit.  The per-sequence lists F (T0 u T1 rows at full
 //                 precision, ascending position) and Q (T2 rows, int8 / int4 codes) are cut into tiles of 64 entries;
 //                 T3 positions are in neither list.  The S * NW waves of a (sequence, kv head) pair are divided
-//                 between the two lists in proportion to their cost, and every wave walks its tiles with a stride,
+//                 between the two lists so that the longest wave is shortest, and every wave walks its tiles with a stride,
 //                 on its own, with no workgroup barrier until the end.
 //                 Rows never pass through registers on their way in: every lane fetches 16-byte (4-byte for short
-//                 code rows) pieces straight into the wave's LDS buffers (buffer_load ... lds), one K buffer and one
-//                 V buffer of a whole tile each.  As soon as a piece has been read for tile t the same lane refills
-//                 it with the piece of tile t+1, so a wave keeps close to two tiles' worth of rows in flight while
-//                 it computes; waits are vmcnt counts derived from the fixed issue order of one tile period.
+//                 code rows) pieces straight into the wave's LDS tile buffer (buffer_load ... lds).  The one buffer
+//                 holds the K rows of a tile, then its V rows, then the next tile's K rows: as soon as a piece has
+//                 been read, the bytes it occupied are refilled with the pieces due next, so a wave keeps about a
+//                 tile's worth of rows in flight while it computes; waits are vmcnt counts derived from the fixed
+//                 issue order of one tile period.
 //                   K rows  - 8 lanes per row; the G logits of a row are reduced over its 8 lanes by DPP and kept
 //                             by the lane whose index equals the entry's index in the tile;
 //                   softmax - online, one entry per lane (exact tile maximum, exp2, running m and l);
