@@ -217,9 +217,10 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_count(DevView v, int n) {
   __syncthreads();
   const uint8_t* tier = v.tier + (size_t)b * v.Nmax;
   const uint8_t* tnew = v.tier_new + (size_t)b * v.Nmax;
-  // index: 0..8 = M01 M02 M03 M10 M12 M13 M20 M21 M23, 9 = bad, 10..13 = planned tier counts
-  int loc[14];
-  for (int k = 0; k < 14; ++k) loc[k] = 0;
+  const int* hloc = v.hloc + (size_t)b * v.Nmax;
+  // index: 0..8 = M01 M02 M03 M10 M12 M13 M20 M21 M23, 9 = bad, 10..13 = planned tier counts, 14 = M01 with a valid host copy
+  int loc[15];
+  for (int k = 0; k < 15; ++k) loc[k] = 0;
   for (int i = t; i < n; i += PLAN_THREADS) {
     const int a = tier[i], d = tnew[i];
     if (d > 3) { loc[9]++; continue; }
@@ -228,13 +229,15 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_count(DevView v, int n) {
     if (a == 3) { loc[9]++; continue; }
     const int k = a * 3 + (d > a ? d - 1 : d);   // (a,d) -> 0..8 in the order above
     loc[k]++;
+    if (a == 0 && d == 1 && hloc[i] >= 0) loc[14]++;
   }
-  for (int k = 0; k < 14; ++k) if (loc[k]) atomicAdd(&c[k], loc[k]);
+  for (int k = 0; k < 15; ++k) if (loc[k]) atomicAdd(&c[k], loc[k]);
   __syncthreads();
   int* cnt = v.cnt + b * CNT_N;
   if (t < 9) cnt[C_M01 + t] = c[t];
   if (t == 9) cnt[C_BAD] = c[9];
   if (t >= 10 && t < 14) cnt[C_P0 + (t - 10)] = c[t];
+  if (t == 14) { cnt[C_M01R] = c[14]; cnt[C_MCOPY] = c[3] + c[14]; }
 }
 hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st) {
   hipLaunchKernelGGL(k_plan_count, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
@@ -298,7 +301,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
   if (nfree0 > v.cap0) nfree0 = v.cap0;
   __syncthreads();
 
-  // running totals: t0 t1 t2 t3 | e0 e1 e2 r0i | r0p r1 r2 m10 | md
+  // running totals: t0 t1 t2 t3 | e0 e1 e2 r0i | r0p r1 r2 mcp | md
+  // (r0p doubles as the count of rows that need a transfer: each reads one HBM slot that is released a migrate later)
   int run[13];
   for (int k = 0; k < 13; ++k) run[k] = 0;
   const int hbase = v.host_base[b];
@@ -307,14 +311,16 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
     const bool in = i < n;
     const int a = in ? v.tier[o + i] : 0, c = in ? v.tier_new[o + i] : 0;
     const bool ch = in && a != c;
+    // a row that returns to T1 while the pinned store still holds its bits needs no transfer
+    const bool back = ch && a == 0 && c == 1 && v.hloc[o + i] >= 0;
     const int e0 = ch && ((a == 1 && c == 0) || (a == 2 && (c == 0 || c == 1)));
     const int e1 = ch && c == 1;
     const int e2 = ch && c == 2;
-    const int r0i = ch && a == 0 && (c == 2 || c == 3);
-    const int r0p = ch && c == 1;                // (a == 0 or a == 2): the HBM slot read by the offload
+    const int r0i = (ch && a == 0 && (c == 2 || c == 3)) || back;
+    const int r0p = ch && c == 1 && !back;       // (a == 0 or a == 2): the HBM slot read by the offload
     const int r1 = ch && a == 1;
     const int r2 = ch && a == 2;
-    const int m10 = ch && a == 1 && c == 0;
+    const int m10 = (ch && a == 1 && c == 0) || back;   // copied inside the F slot space
     const int md = ch && a == 2 && (c == 0 || c == 1);
     Pack4 pk;
     pk.p[0] = (unsigned long long)(in && c == 0) | ((unsigned long long)(in && c == 1) << 16) |
@@ -336,16 +342,22 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
       if (e0) { const int k = nfree0 - 1 - rk[4]; slot0 = (k >= 0) ? free0[k] : -1; }
       if (ch) {
         if (c == 0) {
-          new_loc = slot0; new_hloc = -1;
+          new_loc = slot0;
+          if (a != 1) new_hloc = -1;             // up from T1: the host copy stays valid
         } else if (c == 1) {
-          const int src0 = (a == 0) ? old_loc : slot0;
           const int k1 = nfree1 - 1 - rk[5];
           const int s1 = (k1 >= 0) ? free1[k1] : -1;
-          const int hl = hbase + rk[5];
-          new_loc = s1; new_hloc = hl; loc_for_old_list = src0;
-          const int gi = hl - v.event_base;
-          v.g_seq[gi] = b; v.g_src[gi] = src0; v.g_dst[gi] = s1;
-          v.pend[o + rk[8]] = src0;
+          new_loc = s1;
+          if (back) {
+            v.mv10_src[o + rk[11]] = old_loc; v.mv10_dst[o + rk[11]] = s1;
+          } else {
+            const int src0 = (a == 0) ? old_loc : slot0;
+            const int hl = hbase + rk[8];
+            new_hloc = hl; loc_for_old_list = src0;
+            const int gi = hl - v.event_base;
+            v.g_seq[gi] = b; v.g_src[gi] = src0; v.g_dst[gi] = s1;
+            v.pend[o + rk[8]] = src0;
+          }
         } else if (c == 2) {
           const int k2 = nfree2 - 1 - rk[6];
           const int s2 = (k2 >= 0) ? free2[k2] : -1;
@@ -357,7 +369,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
         if (r0i) v.rel0[o + rk[7]] = old_loc;
         if (r1) v.rel1[o + rk[9]] = old_loc;
         if (r2) v.rel2[o + rk[10]] = old_loc;
-        if (m10) { v.mv10_src[o + rk[11]] = old_loc; v.mv10_dst[o + rk[11]] = slot0; }
+        if (m10 && !back) { v.mv10_src[o + rk[11]] = old_loc; v.mv10_dst[o + rk[11]] = slot0; }
         if (md) { v.mvd_src[o + rk[12]] = old_loc; v.mvd_dst[o + rk[12]] = slot0; }
         v.loc[o + i] = new_loc; v.hloc[o + i] = new_hloc; v.tier[o + i] = (uint8_t)c;
       }
@@ -398,12 +410,13 @@ __device__ __forceinline__ size_t t2_row(const DevView& v, int layer, int b, int
   return (((size_t)layer * v.B + b) * v.Hkv + kvh) * v.cap2 + slot;
 }
 
-// T1 -> T0: staging slot -> HBM slot, bits preserved.  grid (pieces, Hkv*2, L*B)
+// Copies inside the F slot space, bits preserved: T1 -> T0 (staging slot -> HBM slot) and T0 -> T1 of rows whose host
+// copy is still valid (HBM slot -> staging slot).  grid (pieces, Hkv*2, L*B)
 __global__ void k_move_copy(DevView v) {
   const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
   const int cpr = v.D * v.es / 16;
-  const int n = v.cnt[b * CNT_N + C_M10];
+  const int n = v.cnt[b * CNT_N + C_MCOPY];
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   const int j = i / cpr, c = i % cpr;
   if (j >= n) return;

@@ -529,8 +529,8 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     if (e1 > k[C_FREE1]) return fail(c, TKV_ECAPACITY, "tkv_migrate: staging buffer of sequence %d: %d rows enter, %d slots free", b, e1, k[C_FREE1]);
     if (e2 > k[C_FREE2]) return fail(c, TKV_ECAPACITY, "tkv_migrate: compressed pool of sequence %d: %d rows enter, %d slots free", b, e2, k[C_FREE2]);
     c->pin_base[b] = (int)(c->host_next + total_new_t1);
-    total_new_t1 += e1;
-    max10 = std::max(max10, k[C_M10]); maxq = std::max(maxq, e2); maxd = std::max(maxd, k[C_M20] + k[C_M21]);
+    total_new_t1 += e1 - k[C_M01R];              // rows that return to T1 with a valid host copy are not transferred
+    max10 = std::max(max10, k[C_MCOPY]); maxq = std::max(maxq, e2); maxd = std::max(maxd, k[C_M20] + k[C_M21]);
   }
   if (c->host_next + total_new_t1 > c->host_rows)
     return fail(c, TKV_ECAPACITY, "tkv_migrate: pinned T1 store: %lld rows enter, %lld of %lld left",
@@ -546,8 +546,8 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     c->nF[b] = k[C_P0] + k[C_P1]; c->nQ[b] = k[C_P2];
     for (int t = 0; t < 4; ++t) c->ntier[t] += k[C_P0 + t];
     const int e0 = k[C_M10] + k[C_M20] + k[C_M21], e1 = k[C_M01] + k[C_M21], e2 = k[C_M02] + k[C_M12];
-    c->free0[b] = k[C_FREE0] + k[C_PEND] - e0 + k[C_M02] + k[C_M03];
-    c->pend[b] = e1;
+    c->free0[b] = k[C_FREE0] + k[C_PEND] - e0 + k[C_M02] + k[C_M03] + k[C_M01R];
+    c->pend[b] = e1 - k[C_M01R];
     c->free1[b] = k[C_FREE1] - e1 + k[C_M10] + k[C_M12] + k[C_M13];
     c->free2[b] = k[C_FREE2] - e2 + k[C_M20] + k[C_M21] + k[C_M23];
   }

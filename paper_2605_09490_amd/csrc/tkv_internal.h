@@ -18,6 +18,8 @@ enum Cnt : int {
   C_BAD,         // positions that would leave T3 (invalid plan)
   C_LEN,         // positions assigned so far
   C_P0, C_P1, C_P2, C_P3,   // planned positions per tier (plan_count)
+  C_M01R,        // of the T0->T1 moves, rows whose copy in the pinned store is still valid (no transfer: copied inside HBM)
+  C_MCOPY,       // rows copied inside HBM: T1->T0 plus the T0->T1 moves counted in C_M01R
   CNT_N = 28
 };
 
@@ -42,7 +44,8 @@ struct DevView {
   uint8_t* tier;            // [B][Nmax] current
   uint8_t* tier_new;        // [B][Nmax] pending
   int* loc;                 // [B][Nmax] slot in the pool of the position's tier (T0/T1: unified F slot; T2: T2 slot; T3: -1)
-  int* hloc;                // [B][Nmax] row in the pinned host store (T1 only), else -1
+  int* hloc;                // [B][Nmax] row in the pinned host store that holds the position's current bits (every T1 row,
+                            // and T0 rows that came up from T1), else -1
   float* score;             // [B][Nmax]
   int* f_pos; int* f_loc;   // [B][Nmax] list F: position, slot
   int* f_loc_old;           // [B][Nmax] list F with the pre-offload slot of rows whose staged copy is still in flight
@@ -53,7 +56,8 @@ struct DevView {
   int* pend;                // [B][Nmax]
   int* rel0; int* rel1; int* rel2;     // [B][Nmax] scratch: slots released by the plan being committed
   // move lists written by plan_commit (per sequence, [B][Nmax] each, counts in cnt)
-  int* mv10_src; int* mv10_dst;    // staging slot -> HBM slot
+  int* mv10_src; int* mv10_dst;    // copies inside the F slot space: staging slot -> HBM slot, and HBM slot -> staging slot for
+                                   // rows that return to T1 with a valid host copy
   int* mvq_src; int* mvq_dst;      // F slot -> T2 slot (encode)
   int* mvd_src; int* mvd_dst;      // T2 slot -> HBM slot (decode)
   // rows going to the host store at this migrate, global order = host row order

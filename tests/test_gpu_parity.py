@@ -181,6 +181,53 @@ def test_prop1_t1_placement_is_bit_invisible(mode, kv_dtype, D, Hq, Hkv):
     assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
 
 
+@pytest.mark.parametrize("mode", ["wait", "lazy"])
+def test_rows_returning_to_t1_reuse_their_host_copy(mode):
+    """A row that goes T1 -> T0 -> T1 is not transferred a second time (its bits in the pinned store are still
+    current): no bytes move, the row is copied inside HBM into a staging slot, and attention stays bit-identical to
+    the all-T0 twin; rows that pass through T2 on the way lose the host copy and are transferred again."""
+    from gpu_common import Pair
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=700,
+                       decode_steps=6, sigma=1.0)
+    rng = np.random.default_rng(21)
+    n = cfg.context
+    t_a = _random_tiers(rng, cfg.batch, n, frac=(0.4, 0.6, 0.0, 0.0))
+    cand = t_a == 1
+    flip = cand & (rng.random(t_a.shape) < 0.5)
+    t_b = np.where(flip, 0, t_a).astype(np.uint8)                 # half of the T1 rows come up to T0
+    via_t2 = flip & (rng.random(t_a.shape) < 0.3)
+    t_c = np.where(via_t2, 2, t_b).astype(np.uint8)               # some of those go on to T2 ...
+    t_d = t_a.copy()                                              # ... and everything returns to where it started
+    twin_seq = [np.where(t == 1, 0, t).astype(np.uint8) for t in (t_a, t_b, t_c, t_d)]
+    outs = []
+    for seq_t in ((t_a, t_b, t_c, t_d), twin_seq):
+        p = Pair(cfg, prefetch_mode=mode)
+        res, moved = [], []
+        step = 0
+        for tt in seq_t:
+            p.gpu.set_tiers(tt)
+            before = p.gpu.get_stats()["h2d_bytes"]
+            p.gpu.migrate()
+            for l in range(cfg.n_layers):
+                k, v = p.wl.step_kv(step, l)
+                p.gpu.append(l, k, v)
+                res.append(p.gpu.attend_and_score(l, p.wl.step_q(step, l)).cpu())
+            step += 1
+            p.gpu.wait_prefetch()
+            moved.append(p.gpu.get_stats()["h2d_bytes"] - before)
+        outs.append((torch.stack(res), p.gpu.get_scores().copy(), moved))
+        p.close()
+    row_bytes = cfg.n_kv_heads * 2 * cfg.head_dim * 2 * cfg.n_layers
+    moved = outs[0][2]
+    print(f"[case] reuse {mode}: bytes per migrate {moved}", flush=True)
+    assert moved[0] == int(cand.sum()) * row_bytes
+    assert moved[1] == 0 and moved[2] == 0
+    assert moved[3] == int(via_t2.sum()) * row_bytes              # only the rows whose values changed in T2
+    assert outs[1][2] == [0, 0, 0, 0]
+    assert torch.equal(outs[0][0].view(torch.uint8), outs[1][0].view(torch.uint8))
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_classify_bit_exact_given_scores(seed):
     """Tier assignment is an integer function of the binary32 score array: the GPU's radix select must
