@@ -23,7 +23,7 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 # scaled by the same counter's reading for the library's plain row-copy kernel of known size (the context preload:
 # 134 217 728 bytes read and written per launch; FETCH_SIZE reads 1 per 2031 bytes, WRITE_SIZE 1 per KiB).
 # See profiles/attn_tiered_14b_hbm_traffic.txt.
-MEASURED_TRAFFIC = {"14b": {"fetch_bytes": 122_340_000, "write_bytes": 6_470_000}}
+MEASURED_TRAFFIC = {"14b": {"fetch_bytes": 122_190_000, "write_bytes": 5_800_000}}
 LINK_PEAK_GBPS = 64.0       # PCIe Gen5 x16, one direction
 
 
