@@ -212,6 +212,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    probe = link_probe()     # before the caches exist: the largest workload leaves little pinned memory to spare
     base = CONFIGS[args.workload]
     warmup = max(args.warmup, 1)
     cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps)
@@ -281,7 +282,7 @@ def main():
                "attend_waits": main_res["attend_waits"], "lazy_old_reads": main_res["lazy_old_reads"], **extra},
         "tier_count": main_res["tier_count"],
         "score_top20_share": round(main_res.get("top20_share", 0), 3), "score_bottom50_share": round(main_res.get("bottom50_share", 0), 3),
-        "probe": link_probe(), "host_cores": os.cpu_count(),
+        "probe": probe, "host_cores": os.cpu_count(),
     }
     print(json.dumps(line), flush=True)
 

@@ -840,7 +840,7 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
 }
 
 // ---- finish: global softmax statistics, scores, output ------------------------------------------------------
-constexpr int FIN_LDS_FLOATS = 8192;   // room for the (m, l) of all splits of one sequence: Hkv * S * 2 * G floats
+constexpr int FIN_LDS_FLOATS = 2048;   // room for the (m, l) of all splits of one sequence, Hkv * S * 2 * G floats, in all but the smallest batches (else they are read from memory)
 
 template <int D, int G>
 __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_tiles) {

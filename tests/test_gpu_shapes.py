@@ -105,3 +105,11 @@ def test_batch_above_the_kernel_argument_limit():
     cfg = small_config(name="wide", n_layers=1, batch=70, n_q_heads=4, n_kv_heads=2, head_dim=64, kv_dtype="f32",
                        context=200, decode_steps=3, policy_ppm=(400_000, 300_000, 250_000, 50_000), k_window=16)
     _run_shape(cfg, "wait", steps_before=1, steps_after=1)
+
+
+def test_one_sequence_many_splits():
+    """A single long sequence with 8 kv heads of 8 query heads each is split 32 ways per kv head: the per-split softmax
+    statistics (8 x 32 x 2 x 8 floats) exceed the finishing kernel's LDS copy and are read from memory instead."""
+    cfg = small_config(name="solo", n_layers=1, batch=1, n_q_heads=64, n_kv_heads=8, head_dim=64, kv_dtype="bf16",
+                       context=9000, decode_steps=3, policy_ppm=(300_000, 400_000, 270_000, 30_000), k_window=64)
+    _run_shape(cfg, "wait", steps_before=1, steps_after=1)
