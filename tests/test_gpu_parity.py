@@ -228,6 +228,60 @@ def test_rows_returning_to_t1_reuse_their_host_copy(mode):
     assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
 
 
+@pytest.mark.parametrize("mode,kv_dtype,D,Hq,Hkv,t2", [
+    ("lazy", "bf16", 128, 10, 2, "int8_row"),
+    ("wait", "bf16", 128, 10, 2, "int4_g32"),
+    ("lazy", "f32", 64, 8, 2, "int8_row"),
+])
+def test_random_walk_of_plans(mode, kv_dtype, D, Hq, Hkv, t2):
+    """Eight forced plans in a row, each moving a random 40 % of the surviving positions to a random tier (every
+    transition, rows that return to T1 with or without a detour through T2, slots freed and taken again), with
+    tokens appended in between; after every plan the tier array, the four index lists, one attention call per layer
+    and the stored bits of a few T0 / T1 rows are compared with the oracle, and the scores at the end."""
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+                       context=500, decode_steps=8, t2_format=t2, sigma=1.0)
+    p = _pair(cfg, prefetch_mode=mode)
+    rng = np.random.default_rng(77)
+    n = cfg.context
+    tiers = np.zeros((cfg.batch, n), np.uint8)
+    calls = 0
+    for rnd in range(8):
+        move = (rng.random((cfg.batch, n)) < 0.4) & (tiers != 3)
+        prop = _random_tiers(rng, cfg.batch, n, frac=(0.3, 0.35, 0.25, 0.1), protect=(4, 8))
+        tiers = np.where(move, prop, tiers).astype(np.uint8)
+        tiers[:, :4] = 0
+        tiers[:, n - 8:] = 0
+        print(f"[case] walk {mode} {kv_dtype} round {rnd} n={n} counts={np.bincount(tiers.ravel(), minlength=4)}", flush=True)
+        p.force_tiers(tiers)
+        assert np.array_equal(p.gpu.get_tiers()[:, :n], tiers)
+        for b in range(cfg.batch):
+            for t in range(4):
+                assert np.array_equal(p.gpu.get_index_list(t, b), np.nonzero(tiers[b] == t)[0])
+        # stored bits of a few full-precision rows (T0 in HBM, T1 in the pinned store)
+        for t in (0, 1):
+            pos_t = np.nonzero(tiers[1] == t)[0]
+            for pos in rng.choice(pos_t, size=min(3, len(pos_t)), replace=False):
+                for which, store in ((0, p.orc.K), (1, p.orc.V)):
+                    row = p.gpu.get_row(1, 1, 1, int(pos), which)
+                    if kv_dtype == "bf16":
+                        row = (row.astype(np.uint32) << 16).view(np.float32)
+                    assert np.array_equal(row.astype(np.float64), store[1][1, 1, int(pos)]), (rnd, t, pos, which)
+        for l in range(cfg.n_layers):
+            k, v = p.wl.step_kv(rnd, l)
+            p.append(l, k, v)
+            got, ref = p.attend(l, p.wl.step_q(rnd, l))
+            calls += 1
+            assert_out_close(got, ref, kv_dtype, f"round {rnd} layer {l}")
+        n += 1
+        tiers = np.concatenate([tiers, np.zeros((cfg.batch, 1), np.uint8)], axis=1)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _mass(cfg, calls))
+    p.gpu.wait_prefetch()
+    st = p.gpu.get_stats()
+    assert st["tier_count"] == [int(c) for c in np.bincount(tiers[:, :n - 1].ravel(), minlength=4) + np.array([cfg.batch, 0, 0, 0])]
+    p.close()
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_classify_bit_exact_given_scores(seed):
     """Tier assignment is an integer function of the binary32 score array: the GPU's radix select must
