@@ -122,6 +122,10 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label):
         sc = np.sort(gpu.get_scores()[:, :n].astype(np.float64), axis=1)[:, ::-1]
         res["top20_share"] = float((sc[:, : n // 5].sum(1) / sc.sum(1)).mean())
         res["bottom50_share"] = float((sc[:, n // 2:].sum(1) / sc.sum(1)).mean())
+        # Eq. 1 at full size: every attention call adds one unit of probability per query head, so with the scale
+        # 1/(L*Hq) each sequence's scores (evicted positions keep theirs) sum to the number of decode steps so far
+        steps_done = 1 + (warmup - 1) + steps + profile_steps
+        res["score_mass_rel_err"] = float(np.abs(sc.sum(1) / steps_done - 1.0).max())
     res["gpu"] = gpu
     res["wl"] = wl
     return res
@@ -282,6 +286,7 @@ def main():
                "attend_waits": main_res["attend_waits"], "lazy_old_reads": main_res["lazy_old_reads"], **extra},
         "tier_count": main_res["tier_count"],
         "score_top20_share": round(main_res.get("top20_share", 0), 3), "score_bottom50_share": round(main_res.get("bottom50_share", 0), 3),
+        "score_mass_rel_err": main_res.get("score_mass_rel_err"),
         "probe": probe, "host_cores": os.cpu_count(),
     }
     print(json.dumps(line), flush=True)

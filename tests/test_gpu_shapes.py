@@ -113,3 +113,39 @@ def test_one_sequence_many_splits():
     cfg = small_config(name="solo", n_layers=1, batch=1, n_q_heads=64, n_kv_heads=8, head_dim=64, kv_dtype="bf16",
                        context=9000, decode_steps=3, policy_ppm=(300_000, 400_000, 270_000, 30_000), k_window=64)
     _run_shape(cfg, "wait", steps_before=1, steps_after=1)
+
+
+def test_14b_full_depth_score_mass():
+    """The benchmark's own configuration at full depth (48 layers, batch 8, 4096-token context, lazy prefetch): after
+    s decode steps with one re-tiering in between, every sequence's cumulative scores sum to s (Eq. 1 with the scale
+    1/(L*Hq): each call adds one unit of probability per query head; evicted positions keep what they had), and an
+    evicted position's score does not change any more."""
+    import paper_2605_09490_amd as tkv
+    from tkv_synth import Workload
+    cfg = dataclasses.replace(CONFIGS["14b"], decode_steps=4)
+    print(f"[case] 14b full depth L={cfg.n_layers} B={cfg.batch} ctx={cfg.context}", flush=True)
+    wl = Workload(cfg, device="cuda")
+    gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
+                       kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, k_sink=cfg.k_sink, k_window=cfg.k_window,
+                       prefetch_mode="lazy")
+    for l in range(cfg.n_layers):
+        k, v = wl.context_kv(l)
+        gpu.append(l, k, v)
+    del k, v
+    k_all, v_all, q_all = wl.decode_inputs(0, 4)
+    gpu.decode_step(k_all[0], v_all[0], q_all[0])
+    gpu.classify(cfg.policy_ppm)
+    gpu.migrate()
+    n = gpu.layer_length(0)
+    tiers = gpu.get_tiers()[:, :n]
+    frozen = gpu.get_scores()[:, :n][tiers == 3].copy()
+    assert frozen.size > 0
+    for s in range(1, 4):
+        gpu.decode_step(k_all[s], v_all[s], q_all[s])
+    sc = gpu.get_scores().astype(np.float64)
+    n2 = gpu.layer_length(0)
+    assert np.abs(sc[:, :n2].sum(1) / 4.0 - 1.0).max() < 1e-4
+    assert np.array_equal(gpu.get_scores()[:, :n][tiers == 3], frozen)
+    st = gpu.get_stats()
+    assert st["tier_count"][1] > 0 and st["tier_count"][2] > 0 and st["tier_count"][3] > 0
+    gpu.close()
