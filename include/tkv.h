@@ -80,7 +80,10 @@ typedef struct {
   float softmax_scale;                 /* 0 -> 1/sqrt(head_dim) (Eq. 3) */
   int32_t t0_rows, staging_rows, t2_rows; /* per-sequence capacity (in positions) of the HBM pool, the T1 staging
                                           buffer and the compressed pool; 0 -> max_tokens */
-  int64_t host_rows;                   /* capacity of the pinned T1 store in positions, all sequences; 0 -> batch*max_tokens */
+  int64_t host_rows;                   /* capacity of the pinned T1 store in positions, all sequences; 0 -> batch*max_tokens.
+                                          Rows are handed out in order; when they run out tkv_migrate rewrites the store with
+                                          the rows T1 holds at that moment (one full D2H of T1), so it must hold the T1 set
+                                          of one plan plus the rows entering it, not the history of all plans */
   int64_t bounce_bytes;                /* size of each of the two device bounce rings used for T1 traffic; 0 -> 64 MiB */
   int32_t prefetch_mode;               /* tkv_prefetch_mode */
   int32_t profile;                     /* != 0: time every attention kernel with HIP events (tkv_get_stats) */
@@ -108,6 +111,8 @@ typedef struct {
   int64_t attend_waits;       /* WAIT mode: attention calls that were ordered behind a prefetch event */
   int64_t lazy_old_reads;     /* LAZY mode: attention calls that still read pre-offload slots */
   int64_t n_classify, n_migrate;
+  int64_t n_rehome;           /* times the pinned T1 store ran full and was rewritten, packed, from the staged copies */
+  int64_t host_rows_used;     /* rows of the pinned T1 store handed out since the last rewrite (all sequences) */
 } tkv_stats;
 
 /* ---- life cycle ------------------------------------------------------------------------------ */

@@ -587,6 +587,40 @@ __global__ void k_scatter(DevView v, int layer, int r0, int nrows, const char* _
   char* base = which ? v.fpV : v.fpK;
   *(u32x4*)(base + fp_row(v, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
 }
+// Re-homing of the pinned store (it is filled by bump allocation and has run out): the rows T1 holds now get the
+// host rows host_base[b], host_base[b] + 1, ... in position order, every other position loses its host row, and
+// the gather list names each row's staging slot, so the store can be rewritten from the staged copies.
+__global__ __launch_bounds__(PLAN_THREADS) void k_rehome(DevView v, int n) {
+  __shared__ unsigned long long wsum[PLAN_THREADS / 64][4];
+  const int b = blockIdx.x, t = threadIdx.x;
+  const size_t o = (size_t)b * v.Nmax;
+  const int hbase = v.host_base[b];
+  int run = 0;
+  for (int base = 0; base < n; base += PLAN_THREADS) {
+    const int i = base + t;
+    const bool in = i < n;
+    const bool f = in && v.tier[o + i] == 1;
+    Pack4 pk;
+    pk.p[0] = (unsigned long long)f; pk.p[1] = 0; pk.p[2] = 0; pk.p[3] = 0;
+    Pack4 tot;
+    const Pack4 ex = block_excl_scan(pk, tot, wsum);
+    if (in) {
+      if (f) {
+        const int hl = hbase + run + fld(ex.p[0], 0);
+        v.hloc[o + i] = hl;
+        v.g_seq[hl] = b; v.g_src[hl] = v.loc[o + i]; v.g_dst[hl] = -1;
+      } else {
+        v.hloc[o + i] = -1;
+      }
+    }
+    run += fld(tot.p[0], 0);
+  }
+}
+hipError_t launch_rehome(const DevView& v, int n, hipStream_t st) {
+  hipLaunchKernelGGL(k_rehome, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st) {
   const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);
   hipLaunchKernelGGL(k_gather, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, layer, r0, nrows, bounce);

@@ -224,6 +224,39 @@ tkv_status harvest_profile(tkv_cache* c) {
   return TKV_OK;
 }
 
+// The pinned store hands out rows in order and has none left: give the rows T1 holds now the rows 0, 1, ... (per
+// sequence, in position order) and rewrite the store from their staged copies, one D2H per layer and bounce piece.
+// All transfers have been drained, so every T1 row is in its staging slot and nothing reads the store.  T0 rows
+// lose their (reusable) host copy.  pin_cnt holds the counters plan_count has just left.
+tkv_status rehome_store(tkv_cache* c, int n, hipStream_t st) {
+  DevView& v = c->dv;
+  const int B = v.B, L = v.L;
+  int64_t total = 0;
+  for (int b = 0; b < B; ++b) { c->pin_base[b] = (int)total; total += c->pin_cnt[b * CNT_N + C_N1]; }
+  HIPCHK(c, hipMemcpyAsync(c->d_host_base, c->pin_base, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
+  HIPCHK(c, launch_rehome(v, n, st));
+  HIPCHK(c, hipEventRecord(c->ev_plan, st));
+  HIPCHK(c, hipStreamWaitEvent(c->sA, c->ev_plan, 0));
+  const size_t slot_bytes = c->bounce_bytes / RING;
+  const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
+  int piece = 0;
+  for (int l = 0; l < L; ++l) {
+    for (int64_t r0 = 0; r0 < total; r0 += piece_rows, ++piece) {
+      const int nrows = (int)std::min<int64_t>(piece_rows, total - r0);
+      const size_t bytes = (size_t)nrows * c->tok_bytes;
+      char* ba = c->bounceA + (size_t)(piece % RING) * slot_bytes;     // one stream: a ring slot is refilled after its copy
+      HIPCHK(c, launch_gather(v, l, (int)r0, nrows, ba, c->sA));
+      HIPCHK(c, hipMemcpyAsync(c->hstore + ((size_t)l * c->host_rows + (size_t)r0) * c->tok_bytes, ba, bytes,
+                               hipMemcpyDeviceToHost, c->sA));
+      c->st.d2h_bytes += (int64_t)bytes; c->st.d2h_copies++;
+    }
+  }
+  HIPCHK(c, hipStreamSynchronize(c->sA));
+  c->host_next = total;
+  c->st.n_rehome++;
+  return TKV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -516,11 +549,14 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
   // the previous migrate's transfers must have landed before its HBM slots are recycled
   tkv_status s = drain_transfers(c);
   if (s != TKV_OK) return s;
+  int64_t total_new_t1 = 0;
+  int max10 = 0, maxq = 0, maxd = 0;
+  for (int pass = 0;; ++pass) {
   HIPCHK(c, launch_plan_count(v, n, st));
   HIPCHK(c, hipMemcpyAsync(c->pin_cnt, v.cnt, (size_t)B * CNT_N * sizeof(int), hipMemcpyDeviceToHost, st));
   HIPCHK(c, hipStreamSynchronize(st));
-  int64_t total_new_t1 = 0;
-  int max10 = 0, maxq = 0, maxd = 0;
+  total_new_t1 = 0; max10 = maxq = maxd = 0;
+  int64_t live1 = 0, enter1 = 0;
   for (int b = 0; b < B; ++b) {
     const int* k = c->pin_cnt + b * CNT_N;
     if (k[C_BAD]) return fail(c, TKV_ESTATE, "tkv_migrate: the plan moves %d position(s) of sequence %d out of T3 or names an invalid tier", k[C_BAD], b);
@@ -530,11 +566,18 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     if (e2 > k[C_FREE2]) return fail(c, TKV_ECAPACITY, "tkv_migrate: compressed pool of sequence %d: %d rows enter, %d slots free", b, e2, k[C_FREE2]);
     c->pin_base[b] = (int)(c->host_next + total_new_t1);
     total_new_t1 += e1 - k[C_M01R];              // rows that return to T1 with a valid host copy are not transferred
+    live1 += k[C_N1]; enter1 += e1;
     max10 = std::max(max10, k[C_MCOPY]); maxq = std::max(maxq, e2); maxd = std::max(maxd, k[C_M20] + k[C_M21]);
   }
-  if (c->host_next + total_new_t1 > c->host_rows)
-    return fail(c, TKV_ECAPACITY, "tkv_migrate: pinned T1 store: %lld rows enter, %lld of %lld left",
-                (long long)total_new_t1, (long long)(c->host_rows - c->host_next), (long long)c->host_rows);
+  if (c->host_next + total_new_t1 <= c->host_rows) break;
+  // The store hands out rows in order and has too few left.  Packed, it needs the rows T1 holds now plus every row
+  // that enters (none of which keeps a host copy across the rewrite); if that fits, rewrite it and count again.
+  if (pass > 0 || live1 + enter1 > c->host_rows)
+    return fail(c, TKV_ECAPACITY, "tkv_migrate: pinned T1 store: %lld rows in T1, %lld enter, capacity %lld",
+                (long long)live1, (long long)enter1, (long long)c->host_rows);
+  tkv_status rs = rehome_store(c, n, st);
+  if (rs != TKV_OK) return rs;
+  }
   HIPCHK(c, hipMemcpyAsync(c->d_host_base, c->pin_base, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
   v.event_base = (int)c->host_next;
   HIPCHK(c, launch_plan_commit(v, n, st));
@@ -706,6 +749,7 @@ tkv_status tkv_get_stats(tkv_cache* c, tkv_stats* out) {
   if (!c || !out) return c ? fail(c, TKV_EINVAL, "tkv_get_stats: NULL") : TKV_EINVAL;
   tkv_status s = harvest_profile(c); if (s) return s;
   for (int t = 0; t < 4; ++t) c->st.tier_count[t] = c->ntier[t];
+  c->st.host_rows_used = c->host_next;
   *out = c->st;
   return TKV_OK;
 }

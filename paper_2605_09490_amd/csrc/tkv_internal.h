@@ -96,6 +96,7 @@ hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStre
 hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st);
 hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st);
 hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st);
+hipError_t launch_rehome(const DevView& v, int n, hipStream_t st);
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st);
 hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st);
 hipError_t launch_init_state(const DevView& v, hipStream_t st);

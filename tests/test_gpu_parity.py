@@ -238,15 +238,30 @@ def test_random_walk_of_plans(mode, kv_dtype, D, Hq, Hkv, t2):
     transition, rows that return to T1 with or without a detour through T2, slots freed and taken again), with
     tokens appended in between; after every plan the tier array, the four index lists, one attention call per layer
     and the stored bits of a few T0 / T1 rows are compared with the oracle, and the scores at the end."""
+    st = _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2)
+    assert st["n_rehome"] == 0
+
+
+@pytest.mark.parametrize("mode", ["wait", "lazy"])
+def test_pinned_store_is_rewritten_when_it_runs_out(mode):
+    """A longer walk of the same kind with a pinned store of 520 rows: T1 holds ~300 rows and ~100 enter at every plan, so the store
+    (rows are handed out in order) runs out every second or third plan and is rewritten from the staged copies; after every
+    plan EVERY T1 row of one (layer, kv head) is read back from the pinned store and compared bit by bit."""
+    st = _plan_walk(mode, "bf16", 128, 10, 2, "int8_row", host_rows=520, all_t1_rows=True, rounds=16)
+    print(f"[case] store rewritten {st['n_rehome']} times, {st['host_rows_used']} rows in use", flush=True)
+    assert st["n_rehome"] >= 2 and st["host_rows_used"] <= 520
+
+
+def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False, rounds=8):
     from gpu_common import assert_out_close, assert_scores_close
     cfg = small_config(n_layers=2, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
-                       context=500, decode_steps=8, t2_format=t2, sigma=1.0)
-    p = _pair(cfg, prefetch_mode=mode)
+                       context=500, decode_steps=rounds, t2_format=t2, sigma=1.0)
+    p = _pair(cfg, prefetch_mode=mode, **({"host_rows": host_rows} if host_rows else {}))
     rng = np.random.default_rng(77)
     n = cfg.context
     tiers = np.zeros((cfg.batch, n), np.uint8)
     calls = 0
-    for rnd in range(8):
+    for rnd in range(rounds):
         move = (rng.random((cfg.batch, n)) < 0.4) & (tiers != 3)
         prop = _random_tiers(rng, cfg.batch, n, frac=(0.3, 0.35, 0.25, 0.1), protect=(4, 8))
         tiers = np.where(move, prop, tiers).astype(np.uint8)
@@ -261,7 +276,7 @@ def test_random_walk_of_plans(mode, kv_dtype, D, Hq, Hkv, t2):
         # stored bits of a few full-precision rows (T0 in HBM, T1 in the pinned store)
         for t in (0, 1):
             pos_t = np.nonzero(tiers[1] == t)[0]
-            for pos in rng.choice(pos_t, size=min(3, len(pos_t)), replace=False):
+            for pos in (pos_t if (t == 1 and all_t1_rows) else rng.choice(pos_t, size=min(3, len(pos_t)), replace=False)):
                 for which, store in ((0, p.orc.K), (1, p.orc.V)):
                     row = p.gpu.get_row(1, 1, 1, int(pos), which)
                     if kv_dtype == "bf16":
@@ -280,6 +295,7 @@ def test_random_walk_of_plans(mode, kv_dtype, D, Hq, Hkv, t2):
     st = p.gpu.get_stats()
     assert st["tier_count"] == [int(c) for c in np.bincount(tiers[:, :n - 1].ravel(), minlength=4) + np.array([cfg.batch, 0, 0, 0])]
     p.close()
+    return st
 
 
 @pytest.mark.parametrize("seed", range(4))
