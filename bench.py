@@ -41,7 +41,7 @@ def call_bytes(cfg, n_full, n_t2, out_es=4):
     return kv + B * Hq * D * (es + out_es) + (n_full + n_t2) * 4 * 2
 
 
-def run_job(cfg, policy, mode, steps, warmup, profile_steps, label):
+def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
     import torch
     import paper_2605_09490_amd as tkv
     from tkv_synth import Workload
@@ -61,7 +61,7 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label):
     gpu.decode_step(k_all[0], v_all[0], q_all[0], out_all)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    gpu.classify(policy)
+    gpu.classify(policy, count_rule=rule)
     gpu.migrate()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -81,7 +81,7 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label):
                 tc[0] += cfg.batch
             gpu.decode_step(k_all[s], v_all[s], q_all[s], out_all)
             if (s + 1) % delta == 0:
-                gpu.classify(policy)
+                gpu.classify(policy, count_rule=rule)
                 gpu.migrate()
                 if count_bytes:
                     gpu_counts[0] = list(gpu.get_stats()["tier_count"])
@@ -207,6 +207,10 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
+    ap.add_argument("--delta", type=int, default=0, help="re-tier every DELTA steps (default: the workload's own)")
+    ap.add_argument("--k-window", type=int, default=-1, help="protected recent window (default: the workload's own)")
+    ap.add_argument("--count-rule", default="total", choices=["total", "alg1"],
+                    help="band sizes as fixed fractions of all candidates, or Algorithm 1's floors (evicts again at every event)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
@@ -219,7 +223,10 @@ def main():
     probe = link_probe()     # before the caches exist: the largest workload leaves little pinned memory to spare
     base = CONFIGS[args.workload]
     warmup = max(args.warmup, 1)
-    cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps)
+    cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps,
+                              reclassify_every=args.delta or base.reclassify_every,
+                              k_window=base.k_window if args.k_window < 0 else args.k_window)
+    rule = 1 if args.count_rule == "alg1" else 0
     pol = cfg.policy_ppm
     twin_pol = (pol[0] + pol[1], 0, pol[2], pol[3])
     log(f"[bench] workload {cfg.name}: L={cfg.n_layers} B={cfg.batch} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} D={cfg.head_dim} "
@@ -236,7 +243,7 @@ def main():
     for kind in kinds:
         is_main = kind == args.mode and main_res is None
         r = run_job(cfg, twin_pol if kind == "twin" else pol, args.mode if kind == "twin" else kind,
-                    args.steps, warmup, args.profile_steps if is_main else 0, kind)
+                    args.steps, warmup, args.profile_steps if is_main else 0, kind, rule)
         runs[kind].append(r["wall_s"])
         runs_all_in[kind].append(r["wall_s"] + r["cold_fill_ms"] * 1e-3)
         log(f"[bench] {kind}: {r['ms_per_step']:.3f} ms/step" + (f", cold fill {r['cold_fill_ms']:.1f} ms" if is_main else ""))
@@ -267,7 +274,9 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if cfg.kv_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}-shaped: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d {cfg.head_dim}, "
                                f"{cfg.kv_dtype} KV, batch {cfg.batch}, {cfg.context}-token context, tiers ppm {list(pol)}, "
-                               f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"},
+                               f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"
+                               + (f", k_window {cfg.k_window}" if args.k_window >= 0 else "")
+                               + (", Algorithm-1 count rule" if rule else "")},
         "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),
         "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
         "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,

@@ -95,10 +95,16 @@ typedef struct {
   void* alloc_ctx;
 } tkv_config;
 
-/* Band sizes as parts per million of the candidate set U (non-protected positions, evicted ones included);
- * must sum to 1 000 000.  n3, n2, n0 are floors, T1 takes the remainder (Sec. 3.3; Algorithm 1's
- * n_evict and n_hbm with f3 = r, f0 = beta*(1-r), f2 = 0 agree to within one token). */
-typedef struct { uint32_t f_t0_ppm, f_t1_ppm, f_t2_ppm, f_t3_ppm; } tkv_policy;
+/* Band sizes as parts per million; the four fractions must sum to 1 000 000.
+ * count_rule TKV_COUNT_TOTAL (0): fractions of the whole candidate set U (non-protected positions, evicted ones
+ *   included): n3, n2, n0 are floors, T1 takes the remainder; positions evicted earlier count towards n3, so the
+ *   evicted share stays at f3 however many events there are (Sec. 3.3 "bottom r_evict %").
+ * count_rule TKV_COUNT_ALG1 (1): Algorithm 1 as printed, which evicts again at every event: of the `live` candidates
+ *   still in the cache floor(f3 * live) more are evicted, and of the s survivors floor(f0/(1-f3) * s) stay in HBM,
+ *   floor(f2/(1-f3) * s) are compressed, the rest goes to T1.  With f3 = r, f0 = beta*(1-r), f2 = 0 these are
+ *   n_evict = floor(r|U|), n_hbm = floor(beta(|U| - n_evict)) of Algorithm 1. */
+typedef enum { TKV_COUNT_TOTAL = 0, TKV_COUNT_ALG1 = 1 } tkv_count_rule;
+typedef struct { uint32_t f_t0_ppm, f_t1_ppm, f_t2_ppm, f_t3_ppm; uint32_t count_rule; } tkv_policy;
 
 typedef struct {
   int64_t tier_count[4];      /* positions per tier, summed over sequences */
@@ -182,7 +188,8 @@ int32_t tkv_layer_length(const tkv_cache* c, int32_t layer); /* -1 on bad argume
 const char* tkv_last_error(const tkv_cache* c);
 
 /* Pure host helper: band sizes (n0, n1, n2, n3) among m candidates of which n_already_evicted are already in
- * T3 (those never come back; a surplus is taken from n2, then n1, then n0).  EINVAL on a bad policy. */
+ * T3 (those never come back; under TKV_COUNT_TOTAL a surplus is taken from n2, then n1, then n0).  EINVAL on a
+ * bad policy. */
 tkv_status tkv_tier_counts(const tkv_policy* policy, int64_t m, int64_t n_already_evicted, int64_t out[4]);
 
 #ifdef __cplusplus

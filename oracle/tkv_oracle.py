@@ -250,8 +250,32 @@ def tier_counts(m: int, policy_ppm, n_already_evicted: int = 0):
     return n0, n1, n2, n3
 
 
+def tier_counts_alg1(m: int, policy_ppm, n_already_evicted: int = 0):
+    """Sizes (n0, n1, n2, n3) by Algorithm 1 read literally (tier management step).
+
+    The candidate set the algorithm ranks is what is still in the cache:
+    live = m - n_already_evicted.  n_evict = floor(r * live) of them are removed
+    at THIS event (so eviction compounds from event to event), and of the
+    survivors n_hbm = floor(beta * (live - n_evict)) stay in HBM.  In the four
+    parts-per-million fractions r = f3 and beta = f0 / (1 - f3); the compressed
+    band, which Algorithm 1 does not have, takes floor(f2 / (1 - f3) * survivors)
+    in the same way, and T1 the remainder.
+    """
+    f0, f1, f2, f3 = (int(v) for v in policy_ppm)
+    assert f0 + f1 + f2 + f3 == PPM
+    live = m - n_already_evicted
+    n_evict = (f3 * live) // PPM
+    survivors = live - n_evict
+    if f3 == PPM:
+        n_hbm = n_cmp = 0
+    else:
+        n_hbm = (f0 * survivors) // (PPM - f3)
+        n_cmp = (f2 * survivors) // (PPM - f3)
+    return n_hbm, survivors - n_hbm - n_cmp, n_cmp, n_already_evicted + n_evict
+
+
 def classify_sequence(score_f32: np.ndarray, tier_prev: np.ndarray, n: int,
-                      n_prompt: int, k_sink: int, k_window: int, policy_ppm) -> np.ndarray:
+                      n_prompt: int, k_sink: int, k_window: int, policy_ppm, count_rule: int = 0) -> np.ndarray:
     """New tier of each of the n positions of one sequence.
 
     Candidates are ranked ascending by the key (live, score_bits, position):
@@ -268,7 +292,7 @@ def classify_sequence(score_f32: np.ndarray, tier_prev: np.ndarray, n: int,
     if m == 0:
         return tier_new
     evicted = int(np.sum(tier_prev[lo:hi] == T3))
-    n0, n1, n2, n3 = tier_counts(m, policy_ppm, evicted)
+    n0, n1, n2, n3 = (tier_counts_alg1 if count_rule == 1 else tier_counts)(m, policy_ppm, evicted)
     keys = [((0 if tier_prev[i] == T3 else 1), int(bits[i]), i) for i in range(lo, hi)]
     order = [k[2] for k in sorted(keys)]
     for rank, i in enumerate(order):
@@ -346,7 +370,7 @@ class OracleCache:
         return out
 
     # -- tier management ----------------------------------------------------------
-    def classify(self, policy_ppm, score_f32=None):
+    def classify(self, policy_ppm, score_f32=None, count_rule=0):
         """Plan new tiers.  `score_f32` (e.g. the GPU's array) replaces the oracle's own
         scores rounded to binary32, so the assignment can be checked bit-exactly."""
         ns = set(self.length.values())
@@ -357,7 +381,7 @@ class OracleCache:
         new = np.zeros_like(self.tier)
         for b in range(self.B):
             new[b, :n] = classify_sequence(s32[b], self.tier[b], n, self.n_prompt, self.k_sink,
-                                           self.k_window, policy_ppm)
+                                           self.k_window, policy_ppm, count_rule)
         self.tier_pending = new
         return new
 

@@ -18,6 +18,7 @@ TKV_OK, TKV_EINVAL, TKV_ENOMEM, TKV_ECAPACITY, TKV_ESTATE, TKV_EDEVICE = 0, -1, 
 TKV_F32, TKV_BF16 = 0, 1
 TKV_T2_INT8_ROW, TKV_T2_INT4_G32 = 0, 1
 TKV_PREFETCH_WAIT, TKV_PREFETCH_LAZY = 0, 1
+TKV_COUNT_TOTAL, TKV_COUNT_ALG1 = 0, 1
 STATUS_NAMES = {0: "TKV_OK", -1: "TKV_EINVAL", -2: "TKV_ENOMEM", -3: "TKV_ECAPACITY", -4: "TKV_ESTATE", -5: "TKV_EDEVICE"}
 
 ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
@@ -40,7 +41,8 @@ class tkv_config(C.Structure):
 
 
 class tkv_policy(C.Structure):
-    _fields_ = [("f_t0_ppm", C.c_uint32), ("f_t1_ppm", C.c_uint32), ("f_t2_ppm", C.c_uint32), ("f_t3_ppm", C.c_uint32)]
+    _fields_ = [("f_t0_ppm", C.c_uint32), ("f_t1_ppm", C.c_uint32), ("f_t2_ppm", C.c_uint32), ("f_t3_ppm", C.c_uint32),
+                ("count_rule", C.c_uint32)]
 
 
 class tkv_stats(C.Structure):
@@ -103,9 +105,9 @@ class TkvError(RuntimeError):
         self.status = status
 
 
-def tier_counts(policy_ppm, m, n_already_evicted=0):
+def tier_counts(policy_ppm, m, n_already_evicted=0, count_rule=0):
     lib = load_library()
-    pol = tkv_policy(*[int(x) for x in policy_ppm])
+    pol = tkv_policy(*[int(x) for x in policy_ppm], int(count_rule))
     out = (C.c_int64 * 4)()
     st = lib.tkv_tier_counts(C.byref(pol), int(m), int(n_already_evicted), out)
     if st != TKV_OK:
@@ -230,8 +232,8 @@ class TieredKV:
     def set_profile(self, on):
         self._check(self.lib.tkv_set_profile(self._h, 1 if on else 0))
 
-    def classify(self, policy_ppm, stream=None):
-        pol = tkv_policy(*[int(x) for x in policy_ppm])
+    def classify(self, policy_ppm, stream=None, count_rule=0):
+        pol = tkv_policy(*[int(x) for x in policy_ppm], int(count_rule))
         self._check(self.lib.tkv_classify(self._h, C.byref(pol), self._stream(stream)))
 
     def migrate(self, stream=None):

@@ -8,7 +8,7 @@ namespace tkv {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-struct Ppm { uint32_t f[4]; };
+struct Ppm { uint32_t f[4]; uint32_t rule; };
 
 // ---------------------------------------------------------------------------------------------------------
 __global__ void k_init_state(DevView v) {
@@ -116,6 +116,15 @@ __device__ __forceinline__ uint64_t rank_key(uint8_t tier_prev, float score, int
 }
 
 __device__ void band_counts(const Ppm& p, long long m, long long evicted, long long out[4]) {
+  if (p.rule == 1) {
+    // Algorithm 1 as printed: a further floor(r * live) evictions among the candidates still in the cache, the
+    // other bands as shares of the survivors
+    const long long live = m - evicted, n_new = ((long long)p.f[3] * live) / 1000000, s = live - n_new;
+    const long long den = 1000000 - (long long)p.f[3];
+    const long long n0 = den > 0 ? ((long long)p.f[0] * s) / den : 0, n2 = den > 0 ? ((long long)p.f[2] * s) / den : 0;
+    out[0] = n0; out[1] = s - n0 - n2; out[2] = n2; out[3] = evicted + n_new;
+    return;
+  }
   long long n3 = ((long long)p.f[3] * m) / 1000000, n2 = ((long long)p.f[2] * m) / 1000000;
   long long n0 = ((long long)p.f[0] * m) / 1000000, n1 = m - n0 - n2 - n3;
   long long extra = evicted - n3;
@@ -205,6 +214,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_classify(DevView v, int n, Ppm
 }
 hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStream_t st) {
   Ppm p; for (int i = 0; i < 4; ++i) p.f[i] = ppm[i];
+  p.rule = ppm[4];
   hipLaunchKernelGGL(k_classify, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n, p);
   return hipGetLastError();
 }

@@ -113,10 +113,17 @@ bool dalloc(tkv_cache* c, T*& p, size_t count) {
 }
 
 bool policy_ok(const tkv_policy* p) {
-  return p && (uint64_t)p->f_t0_ppm + p->f_t1_ppm + p->f_t2_ppm + p->f_t3_ppm == 1000000ull;
+  return p && (uint64_t)p->f_t0_ppm + p->f_t1_ppm + p->f_t2_ppm + p->f_t3_ppm == 1000000ull && p->count_rule <= 1u;
 }
 
 void band_counts_host(const tkv_policy* p, int64_t m, int64_t evicted, int64_t out[4]) {
+  if (p->count_rule == TKV_COUNT_ALG1) {
+    const int64_t live = m - evicted, n_new = ((int64_t)p->f_t3_ppm * live) / 1000000, s = live - n_new;
+    const int64_t den = 1000000 - (int64_t)p->f_t3_ppm;
+    const int64_t n0 = den > 0 ? ((int64_t)p->f_t0_ppm * s) / den : 0, n2 = den > 0 ? ((int64_t)p->f_t2_ppm * s) / den : 0;
+    out[0] = n0; out[1] = s - n0 - n2; out[2] = n2; out[3] = evicted + n_new;
+    return;
+  }
   int64_t n3 = ((int64_t)p->f_t3_ppm * m) / 1000000, n2 = ((int64_t)p->f_t2_ppm * m) / 1000000;
   int64_t n0 = ((int64_t)p->f_t0_ppm * m) / 1000000, n1 = m - n0 - n2 - n3;
   int64_t extra = evicted - n3;
@@ -523,13 +530,13 @@ tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, c
 
 tkv_status tkv_classify(tkv_cache* c, const tkv_policy* policy, void* hip_stream) {
   if (!c) return TKV_EINVAL;
-  if (!policy_ok(policy)) return fail(c, TKV_EINVAL, "tkv_classify: policy fractions must sum to 1000000 ppm");
+  if (!policy_ok(policy)) return fail(c, TKV_EINVAL, "tkv_classify: policy fractions must sum to 1000000 ppm and count_rule be 0 or 1");
   const int n = common_length(c);
   if (n < 0 || n != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_classify: layers differ in length");
   if (n == 0) return fail(c, TKV_ESTATE, "tkv_classify: cache is empty");
   const auto t0 = std::chrono::steady_clock::now();
   hipStream_t st = (hipStream_t)hip_stream;
-  const uint32_t ppm[4] = {policy->f_t0_ppm, policy->f_t1_ppm, policy->f_t2_ppm, policy->f_t3_ppm};
+  const uint32_t ppm[5] = {policy->f_t0_ppm, policy->f_t1_ppm, policy->f_t2_ppm, policy->f_t3_ppm, policy->count_rule};
   HIPCHK(c, launch_classify(c->dv, n, ppm, st));
   c->plan_pending = true;
   c->st.n_classify++;

@@ -84,5 +84,6 @@ def test_tier_counts_agree_with_oracle_and_reject_bad_policy():
         pol = (int(cut[0]), int(cut[1] - cut[0]), int(cut[2] - cut[1]), int(10 ** 6 - cut[2]))
         ev = int(rng.integers(0, m + 1)) if rng.random() < 0.3 else 0
         assert tkv.tier_counts(pol, m, ev) == O.tier_counts(m, pol, ev)
+        assert tkv.tier_counts(pol, m, ev, count_rule=1) == O.tier_counts_alg1(m, pol, ev)
     with pytest.raises(tkv.TkvError):
         tkv.tier_counts((1, 2, 3, 4), 10)

@@ -298,10 +298,12 @@ def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False
     return st
 
 
+@pytest.mark.parametrize("rule", [0, 1])
 @pytest.mark.parametrize("seed", range(4))
-def test_classify_bit_exact_given_scores(seed):
+def test_classify_bit_exact_given_scores(seed, rule):
     """Tier assignment is an integer function of the binary32 score array: the GPU's radix select must
-    reproduce the oracle's explicit sort, ties and already-evicted positions included."""
+    reproduce the oracle's explicit sort, ties and already-evicted positions included; with both count rules (fixed
+    fractions of all candidates, and Algorithm 1's floors that evict again at every event)."""
     from gpu_common import Pair
     rng = np.random.default_rng(seed)
     ctx = int(rng.integers(300, 2500))
@@ -317,11 +319,13 @@ def test_classify_bit_exact_given_scores(seed):
     pols = [(300000, 520000, 150000, 30000), (500000, 300000, 150000, 50000), (100000, 100000, 100000, 700000),
             (0, 0, 0, 1000000)]
     tier_prev = np.zeros((cfg.batch, n), np.uint8)
-    for pol in pols[: 3 if seed % 2 else 4]:
-        p.gpu.classify(pol)
+    if rule == 1:
+        pols = [pols[0], pols[0], pols[1], pols[0], pols[2]] + ([pols[3]] if seed % 2 == 0 else [])   # repeated events compound
+    for pol in pols[: 3 if (seed % 2 and rule == 0) else len(pols)]:
+        p.gpu.classify(pol, count_rule=rule)
         got = p.gpu.get_pending_tiers()[:, :n]
         for b in range(cfg.batch):
-            want = O.classify_sequence(s[b], tier_prev[b], n, cfg.n_prompt, cfg.k_sink, cfg.k_window, pol)
+            want = O.classify_sequence(s[b], tier_prev[b], n, cfg.n_prompt, cfg.k_sink, cfg.k_window, pol, rule)
             assert np.array_equal(got[b], want), f"seq {b} policy {pol}: {(got[b] != want).sum()} positions differ"
         p.gpu.migrate()
         tier_prev = p.gpu.get_tiers()[:, :n].copy()

@@ -272,6 +272,56 @@ def test_tier_counts_against_algorithm1_golden():
         assert abs(n0 - n_hbm) <= 1 and abs(n1 - n_ddr) <= 1
 
 
+def test_alg1_rule_reproduces_the_golden_floors_exactly():
+    # Algorithm 1's floors, evaluated by hand in the fixture, with r = f3 and beta = f0 / (1 - f3)
+    with open(os.path.join(GOLDEN, "alg1_counts.txt")) as f:
+        rows = [tuple(int(t) for t in ln.split()) for ln in f if ln.strip() and not ln.startswith("#")]
+    for m, beta, r, n_hbm, n_ddr, n_evict in rows:
+        f3 = r * 10000
+        f0 = beta * (100 - r) * 100
+        assert O.tier_counts_alg1(m, (f0, 10 ** 6 - f0 - f3, 0, f3)) == (n_hbm, n_ddr, 0, n_evict)
+
+
+def test_alg1_rule_compounds_and_partitions():
+    # event after event on a fixed candidate set the live part shrinks by floor(r * live): the recurrence written
+    # out with exact fractions, against the function; the four bands always partition the candidates
+    pol = (400000, 350000, 150000, 100000)
+    m, ev = 3000, 0
+    for _ in range(12):
+        n0, n1, n2, n3 = O.tier_counts_alg1(m, pol, ev)
+        live = m - ev
+        new = math.floor(Fraction(1, 10) * live)
+        surv = live - new
+        assert n3 == ev + new
+        assert n0 == math.floor(Fraction(400000, 900000) * surv) and n2 == math.floor(Fraction(150000, 900000) * surv)
+        assert n0 + n1 + n2 + n3 == m and n1 >= 0
+        ev = n3
+    # 3000 -> 2700 -> 2430 -> 2187 -> 1969 -> 1773 -> 1596 -> 1437 -> 1294 -> 1165 -> 1049 -> 945 -> 851 alive
+    assert ev == 3000 - 851
+    # no eviction: the rule reduces to plain floors of the fractions; everything evicted: nothing else
+    assert O.tier_counts_alg1(1000, (500000, 300000, 200000, 0), 0) == (500, 300, 200, 0)
+    assert O.tier_counts_alg1(1000, (0, 0, 0, 1000000), 0) == (0, 0, 0, 1000)
+    assert O.tier_counts_alg1(10, (500000, 300000, 150000, 50000), 10) == (0, 0, 0, 10)
+
+
+def test_alg1_rule_in_the_classifier_evicts_the_lowest_live_scores():
+    # two events on 200 candidates with distinct scores: the second event evicts floor(0.1 * 180) = 18 more, and
+    # they are the 18 lowest scores among the positions still alive
+    rng = np.random.default_rng(3)
+    n = 200 + 4 + 8
+    s = rng.permutation(n).astype(np.float32) + 1.0
+    pol = (450000, 450000, 0, 100000)
+    t1 = O.classify_sequence(s, np.zeros(n, np.uint8), n, 0, 4, 8, pol, count_rule=1)
+    assert (t1 == 3).sum() == 20 and (t1 == 0).sum() == 90 + 12 and (t1 == 1).sum() == 90
+    t2 = O.classify_sequence(s, t1, n, 0, 4, 8, pol, count_rule=1)
+    assert (t2 == 3).sum() == 38 and np.all(t2[t1 == 3] == 3)
+    cand = np.arange(4, n - 8)
+    alive = cand[t1[cand] != 3]
+    lowest = alive[np.argsort(s[alive])[:18]]
+    assert np.all(t2[lowest] == 3)
+    assert (t2 == 0).sum() == 81 + 12 and (t2 == 1).sum() == 81
+
+
 def test_tier_counts_keep_evicted():
     assert O.tier_counts(100, (500000, 300000, 150000, 50000), n_already_evicted=3) == (50, 30, 15, 5)
     assert O.tier_counts(100, (500000, 300000, 150000, 50000), n_already_evicted=12) == (50, 30, 8, 12)
