@@ -63,8 +63,13 @@ typedef enum { TKV_T2_INT8_ROW = 0, TKV_T2_INT4_G32 = 1 } tkv_t2_format;
  *  WAIT: the first tkv_attend_and_score of a layer waits (on the GPU, event-ordered) until that layer's
  *        newly offloaded rows have made the trip device -> pinned host -> staging buffer;
  *  LAZY: attention keeps reading such rows from their old HBM slot until the staged copy has arrived
- *        (polled without blocking) and then switches; outputs are bit-identical either way (Prop. 1). */
-typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1 } tkv_prefetch_mode;
+ *        (polled without blocking) and then switches; outputs are bit-identical either way (Prop. 1).
+ *  STREAM: T1 rows are not kept in HBM at all between uses: the staging buffer is two layer-sized frames shared by
+ *        all layers, and every tkv_attend_and_score reads its layer's T1 rows from a frame that was refilled from the
+ *        pinned store (hipMemcpyAsync on the prefetch stream, event-ordered) while the previous layers were attended.
+ *        HBM then holds T0, T2 and two frames; every decode step moves all of T1 over the host link.  In this mode
+ *        the pinned store is not rewritten when it runs out (TKV_ECAPACITY): size host_rows for the run. */
+typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1, TKV_PREFETCH_STREAM = 2 } tkv_prefetch_mode;
 
 typedef struct {
   int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64, 128}; n_q_heads % n_kv_heads == 0,

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libtkv.so")
 TKV_OK, TKV_EINVAL, TKV_ENOMEM, TKV_ECAPACITY, TKV_ESTATE, TKV_EDEVICE = 0, -1, -2, -3, -4, -5
 TKV_F32, TKV_BF16 = 0, 1
 TKV_T2_INT8_ROW, TKV_T2_INT4_G32 = 0, 1
-TKV_PREFETCH_WAIT, TKV_PREFETCH_LAZY = 0, 1
+TKV_PREFETCH_WAIT, TKV_PREFETCH_LAZY, TKV_PREFETCH_STREAM = 0, 1, 2
 TKV_COUNT_TOTAL, TKV_COUNT_ALG1 = 0, 1
 STATUS_NAMES = {0: "TKV_OK", -1: "TKV_EINVAL", -2: "TKV_ENOMEM", -3: "TKV_ECAPACITY", -4: "TKV_ESTATE", -5: "TKV_EDEVICE"}
 
@@ -141,7 +141,7 @@ class TieredKV:
         cfg.score_scale, cfg.softmax_scale = float(score_scale or 0.0), float(softmax_scale or 0.0)
         cfg.t0_rows, cfg.staging_rows, cfg.t2_rows = t0_rows, staging_rows, t2_rows
         cfg.host_rows, cfg.bounce_bytes = host_rows, bounce_bytes
-        cfg.prefetch_mode = TKV_PREFETCH_LAZY if prefetch_mode == "lazy" else TKV_PREFETCH_WAIT
+        cfg.prefetch_mode = {"wait": TKV_PREFETCH_WAIT, "lazy": TKV_PREFETCH_LAZY, "stream": TKV_PREFETCH_STREAM}[prefetch_mode]
         cfg.profile = 1 if profile else 0
         cfg.device = device
         if use_torch_allocator:

@@ -735,9 +735,13 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
   __shared__ float sm_ml[NW * 16];
   const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  int nF, nQ;
-  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
-  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  int nF, nQ, xsb = 0;
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; if (a.second) xsb = a.xs_base[b]; }
+  else if (!a.second) { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  else {
+    nF = a.cnt[b * CNT_N + C_NS]; nQ = 0;
+    xsb = ((a.cnt[b * CNT_N + C_NF] + 63) >> 6) + ((a.cnt[b * CNT_N + C_NQ] + 63) >> 6);
+  }
   const int nft = (nF + 63) >> 6, nqt = (nQ + 63) >> 6;
   const int nwv = a.S * NW;
   const int nwq = (a.B <= ATTN_ARG_SEQS) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
@@ -759,11 +763,11 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
   }
   bool o_written = false;
   if (u < nwf) {
-    attn_wave<D, G, KG::MF, BF16>(a, w, b, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, 0, o, m_run, l_lane);
+    attn_wave<D, G, KG::MF, BF16>(a, w, b, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
   } else {
     if constexpr (EV == 8) {
-      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o, m_run, l_lane);
-      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o, m_run, l_lane);
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
     } else {
       // binary32 rows use 4 elements per lane, code rows 8: separate accumulators, parked directly
       float o8[G][8];
@@ -771,8 +775,8 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o8[h][e] = 0.f;
-      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o8, m_run, l_lane);
-      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, nft, o8, m_run, l_lane);
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
       constexpr int L8 = D / 8;
 #pragma unroll
       for (int st = L8; st < 64; st <<= 1)
@@ -810,7 +814,7 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
     if (lane == 0) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = ls; }
   }
   __syncthreads();
-  float* po = a.part_o + ((size_t)((b * a.Hkv + kvh) * a.S + s) * G) * D;
+  float* po = a.part_o + ((size_t)((b * a.Hkv + kvh) * a.S_total + a.s0 + s) * G) * D;
   for (int i = t; i < G * D; i += NW * 64) {
     const int h = i / D;
     float mb = sm_ml[h];
@@ -833,7 +837,7 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) ll = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 16 + t] - mb) * LOG2E), sm_ml[ww * 16 + 8 + t], ll);
     }
-    float* pm = a.part_ml + ((size_t)((b * a.Hkv + kvh) * a.S + s) * 2) * G;
+    float* pm = a.part_ml + ((size_t)((b * a.Hkv + kvh) * a.S_total + a.s0 + s) * 2) * G;
     pm[t] = mb;
     pm[G + t] = ll;
   }
@@ -847,12 +851,13 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   __shared__ float sm_pm[FIN_LDS_FLOATS];
   __shared__ float M[128], IL[128];
   const int t = threadIdx.x, b = blockIdx.y;
-  int nF, nQ;
-  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
-  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
-  const int cf = (nF + TB - 1) / TB, ns = a.S;
+  int nF, nQ, nS;
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; nS = a.nS[b]; }
+  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; nS = a.s_pos ? a.cnt[b * CNT_N + C_NS] : 0; }
+  // logits columns: F tiles, Q tiles, then (streamed T1) the T1 list's tiles
+  const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = a.S_total;
   const bool is_tile = (int)blockIdx.x < n_tiles;
-  if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
+  if (is_tile && (int)blockIdx.x * 64 >= (nS > 0 ? (cf + cq) * TB + nS : cf * TB + nQ)) return;
   // tile workgroups: the entry's position, its first kv head's logits and its score so far are fetched before the
   // (m, l) merge, so their latency runs beside it
   const int e = t & 63, hg = t >> 6;
@@ -860,27 +865,28 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   int pos = -1;
   float x0[G], score_old = 0.f;
   if (is_tile) {
-    const bool live = j < nF || (j >= cf * TB && j - cf * TB < nQ);
     if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
     else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
+    else if (j >= (cf + cq) * TB && j - (cf + cq) * TB < nS) pos = a.s_pos[(size_t)b * a.Nmax + (j - (cf + cq) * TB)];
+    const bool live = pos >= 0;
 #pragma unroll
     for (int g = 0; g < G; ++g) x0[g] = (live && hg < a.Hkv) ? a.xs[((size_t)b * a.Hq + hg * G + g) * a.xs_stride + j] : 0.f;
     if (hg == 0 && pos >= 0) score_old = a.score[(size_t)b * a.Nmax + pos];
   }
   // (m, l) of every split of this sequence: part_ml[b][kvh][s][2][G], s < ns
-  const float* pmb = a.part_ml + (size_t)b * a.Hkv * a.S * 2 * G;
+  const float* pmb = a.part_ml + (size_t)b * a.Hkv * a.S_total * 2 * G;
   const int per_kvh = ns * 2 * G;
   const bool in_lds = a.Hkv * per_kvh <= FIN_LDS_FLOATS;
   if (in_lds) {
     for (int i = t; i < a.Hkv * per_kvh; i += 256) {
       const int kvh = i / per_kvh, rem = i % per_kvh;
-      sm_pm[i] = pmb[(size_t)kvh * a.S * 2 * G + rem];
+      sm_pm[i] = pmb[(size_t)kvh * a.S_total * 2 * G + rem];
     }
     __syncthreads();
   }
   if (t < a.Hq) {
     const int kvh = t / G, g = t % G;
-    const float* src = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S * 2 * G);
+    const float* src = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S_total * 2 * G);
     float mm = -INFINITY;
     for (int k = 0; k < ns; ++k) mm = fmaxf(mm, src[k * 2 * G + g]);
     float ll = 0.f;
@@ -915,8 +921,8 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
     constexpr int NSG = 256 / D;
     const int hq = blockIdx.x - n_tiles, kvh = hq / G, h = hq % G;
     const int d = t % D, sg = t / D;
-    const float* pm = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S * 2 * G);
-    const float* pob = a.part_o + ((size_t)(b * a.Hkv + kvh) * a.S * G) * D + h * D + d;
+    const float* pm = in_lds ? (sm_pm + kvh * per_kvh) : (pmb + (size_t)kvh * a.S_total * 2 * G);
+    const float* pob = a.part_o + ((size_t)(b * a.Hkv + kvh) * a.S_total * G) * D + h * D + d;
     const float mg = M[hq];
     float acc = 0.f;
 #pragma unroll 8

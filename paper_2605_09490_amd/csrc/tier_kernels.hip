@@ -67,8 +67,8 @@ __global__ void k_append_rows(DevView v, int layer, const char* __restrict__ k, 
   const int j = (int)(r % n_new);
   const int b = (int)(r / n_new);
   const int slot = v.loc[(size_t)b * v.Nmax + pos0 + j];
-  if (slot < 0 || slot >= v.capF) return;
-  const size_t dst = ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capF + slot) * row_bytes + (size_t)c * 16;
+  if (slot < 0 || slot >= v.capP) return;
+  const size_t dst = ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capP + slot) * row_bytes + (size_t)c * 16;
   const size_t src = (size_t)i * 16;
   *(u32x4*)(v.fpK + dst) = *(const u32x4*)(k + src);
   *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + src);
@@ -86,8 +86,8 @@ __global__ void k_append_step(DevView v, const char* __restrict__ k, const char*
   const int b = (int)(r % v.B);
   const int layer = (int)(r / v.B);
   const int slot = v.loc[(size_t)b * v.Nmax + pos];
-  if (slot < 0 || slot >= v.capF) return;
-  const size_t dst = ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capF + slot) * row_bytes + (size_t)c * 16;
+  if (slot < 0 || slot >= v.capP) return;
+  const size_t dst = ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capP + slot) * row_bytes + (size_t)c * 16;
   *(u32x4*)(v.fpK + dst) = *(const u32x4*)(k + (size_t)i * 16);
   *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + (size_t)i * 16);
 }
@@ -346,8 +346,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
     for (int k = 0; k < 13; ++k) { rk[k] = run[k] + fld(ex.p[k >> 2], k & 3); tt[k] = fld(tot.p[k >> 2], k & 3); }
     // a chunk total of exactly 1024 does not fit a 16-bit field only if > 65535: fine
     if (in) {
-      const int old_loc = v.loc[o + i];
-      int new_loc = old_loc, new_hloc = v.hloc[o + i], loc_for_old_list = -2;
+      const int old_loc = v.loc[o + i], old_hloc = v.hloc[o + i];
+      int new_loc = old_loc, new_hloc = old_hloc, loc_for_old_list = -2;
       int slot0 = -1;
       if (e0) { const int k = nfree0 - 1 - rk[4]; slot0 = (k >= 0) ? free0[k] : -1; }
       if (ch) {
@@ -359,13 +359,16 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
           const int s1 = (k1 >= 0) ? free1[k1] : -1;
           new_loc = s1;
           if (back) {
-            v.mv10_src[o + rk[11]] = old_loc; v.mv10_dst[o + rk[11]] = s1;
+            // streamed: the row is in the pinned store already and nothing is copied
+            v.mv10_src[o + rk[11]] = v.streamed ? -1 : old_loc; v.mv10_dst[o + rk[11]] = s1;
+            if (v.streamed) v.h_dst[old_hloc] = s1;
           } else {
             const int src0 = (a == 0) ? old_loc : slot0;
             const int hl = hbase + rk[8];
             new_hloc = hl; loc_for_old_list = src0;
             const int gi = hl - v.event_base;
             v.g_seq[gi] = b; v.g_src[gi] = src0; v.g_dst[gi] = s1;
+            if (v.streamed) { v.h_seq[hl] = b; v.h_dst[hl] = s1; }
             v.pend[o + rk[8]] = src0;
           }
         } else if (c == 2) {
@@ -377,15 +380,17 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
           new_loc = -1; new_hloc = -1;
         }
         if (r0i) v.rel0[o + rk[7]] = old_loc;
-        if (r1) v.rel1[o + rk[9]] = old_loc;
+        if (r1) { v.rel1[o + rk[9]] = old_loc; if (v.streamed) v.h_clr[o + rk[9]] = old_hloc; }
         if (r2) v.rel2[o + rk[10]] = old_loc;
         if (m10 && !back) { v.mv10_src[o + rk[11]] = old_loc; v.mv10_dst[o + rk[11]] = slot0; }
         if (md) { v.mvd_src[o + rk[12]] = old_loc; v.mvd_dst[o + rk[12]] = slot0; }
         v.loc[o + i] = new_loc; v.hloc[o + i] = new_hloc; v.tier[o + i] = (uint8_t)c;
       }
       v.idx[((size_t)c * v.B + b) * v.Nmax + rk[c]] = i;
-      if (c <= 1) {
-        const int j = rk[0] + rk[1];
+      if (c == 1 && v.streamed) {
+        v.s_pos[o + rk[1]] = i; v.s_loc[o + rk[1]] = new_loc - v.cap0;
+      } else if (c <= 1) {
+        const int j = v.streamed ? rk[0] : rk[0] + rk[1];
         v.f_pos[o + j] = i; v.f_loc[o + j] = new_loc;
         v.f_loc_old[o + j] = (loc_for_old_list != -2) ? loc_for_old_list : new_loc;
       } else if (c == 2) {
@@ -401,7 +406,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
   for (int j = t; j < run[9]; j += PLAN_THREADS) if (h1 + j >= 0 && h1 + j < v.cap1) free1[h1 + j] = v.rel1[o + j];
   for (int j = t; j < run[10]; j += PLAN_THREADS) if (h2 + j >= 0 && h2 + j < v.cap2) free2[h2 + j] = v.rel2[o + j];
   if (t == 0) {
-    cnt[C_NF] = run[0] + run[1]; cnt[C_NQ] = run[2];
+    cnt[C_NF] = v.streamed ? run[0] : run[0] + run[1]; cnt[C_NQ] = run[2]; cnt[C_NS] = v.streamed ? run[1] : 0;
     cnt[C_N0] = run[0]; cnt[C_N1] = run[1]; cnt[C_N2] = run[2]; cnt[C_N3] = run[3];
     cnt[C_FREE0] = h0 + run[7]; cnt[C_FREE1] = h1 + run[9]; cnt[C_FREE2] = h2 + run[10];
     cnt[C_PEND] = run[8];
@@ -413,8 +418,12 @@ hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st) {
 }
 
 // ---- row movers ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ size_t fp_row(const DevView& v, int layer, int b, int kvh, int slot) {
-  return ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capF + slot) * (size_t)(v.D * v.es);
+// a row of the unified F slot space: HBM pool, or (streamed T1, staging slots) the frame that holds the layer's T1 rows
+__device__ __forceinline__ char* fp_ptr(const DevView& v, int which, int layer, int b, int kvh, int slot) {
+  const size_t rb = (size_t)(v.D * v.es);
+  if (v.streamed && slot >= v.cap0)
+    return (which ? v.frV : v.frK) + (((size_t)b * v.Hkv + kvh) * v.cap1 + (slot - v.cap0)) * rb;
+  return (which ? v.fpV : v.fpK) + ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capP + slot) * rb;
 }
 __device__ __forceinline__ size_t t2_row(const DevView& v, int layer, int b, int kvh, int slot) {
   return (((size_t)layer * v.B + b) * v.Hkv + kvh) * v.cap2 + slot;
@@ -422,8 +431,8 @@ __device__ __forceinline__ size_t t2_row(const DevView& v, int layer, int b, int
 
 // Copies inside the F slot space, bits preserved: T1 -> T0 (staging slot -> HBM slot) and T0 -> T1 of rows whose host
 // copy is still valid (HBM slot -> staging slot).  grid (pieces, Hkv*2, L*B)
-__global__ void k_move_copy(DevView v) {
-  const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
+__global__ void k_move_copy(DevView v, int layer0) {
+  const int lb = blockIdx.z, layer = layer0 + lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
   const int cpr = v.D * v.es / 16;
   const int n = v.cnt[b * CNT_N + C_MCOPY];
@@ -432,8 +441,7 @@ __global__ void k_move_copy(DevView v) {
   if (j >= n) return;
   const int src = v.mv10_src[(size_t)b * v.Nmax + j], dst = v.mv10_dst[(size_t)b * v.Nmax + j];
   if (src < 0 || src >= v.capF || dst < 0 || dst >= v.capF) return;
-  char* base = which ? v.fpV : v.fpK;
-  *(u32x4*)(base + fp_row(v, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(base + fp_row(v, layer, b, kvh, src) + c * 16);
+  *(u32x4*)(fp_ptr(v, which, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(fp_ptr(v, which, layer, b, kvh, src) + c * 16);
 }
 
 // 8 consecutive elements of a stored row as binary32
@@ -470,8 +478,8 @@ __device__ __forceinline__ void store8(char* row, int e0, int es, const float (&
 
 // -> T2: encode the current stored row.  D/8 lanes per row (8 elements each), 64/(D/8) rows per wave.
 // grid (pieces, Hkv*2, L*B).  All arithmetic in binary32, round-to-nearest-even, true division.
-__global__ __launch_bounds__(256) void k_move_quant(DevView v) {
-  const int lb = blockIdx.z, layer = lb / v.B, b = lb % v.B;
+__global__ __launch_bounds__(256) void k_move_quant(DevView v, int layer0) {
+  const int lb = blockIdx.z, layer = layer0 + lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
   const int lane = threadIdx.x & 63, lpr = v.D / 8, rpw = 64 / lpr;
   const int g = lane / lpr, r = lane % lpr;
@@ -482,7 +490,7 @@ __global__ __launch_bounds__(256) void k_move_quant(DevView v) {
   if (act) { src = v.mvq_src[(size_t)b * v.Nmax + j]; dst = v.mvq_dst[(size_t)b * v.Nmax + j]; }
   const bool ok = act && src >= 0 && src < v.capF && dst >= 0 && dst < v.cap2;
   float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (ok) load8((which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, src), r * 8, v.es, x);
+  if (ok) load8(fp_ptr(v, which, layer, b, kvh, src), r * 8, v.es, x);
   float a = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(x[e]));
@@ -549,7 +557,7 @@ __global__ __launch_bounds__(256) void k_move_dequant(DevView v) {
       x[e] = (float)c * sc;
     }
   }
-  store8((which ? v.fpV : v.fpK) + fp_row(v, layer, b, kvh, dst), r * 8, v.es, x);
+  store8(fp_ptr(v, which, layer, b, kvh, dst), r * 8, v.es, x);
 }
 
 hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st) {
@@ -558,9 +566,39 @@ hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStre
   if (maxd > 0)
     hipLaunchKernelGGL(k_move_dequant, dim3((maxd + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
   if (max10 > 0)
-    hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+    hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v, 0);
   if (maxq > 0)
-    hipLaunchKernelGGL(k_move_quant, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+    hipLaunchKernelGGL(k_move_quant, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v, 0);
+  return hipGetLastError();
+}
+hipError_t launch_decode_moves(const DevView& v, int maxd, hipStream_t st) {
+  const int rpb = 4 * (64 / (v.D / 8));
+  if (maxd > 0)
+    hipLaunchKernelGGL(k_move_dequant, dim3((maxd + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
+  return hipGetLastError();
+}
+hipError_t launch_moves_layer(const DevView& v, int layer, int max10, int maxq, hipStream_t st) {
+  const int cpr = v.D * v.es / 16;
+  const int rpb = 4 * (64 / (v.D / 8));
+  if (max10 > 0)
+    hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.B), dim3(256), 0, st, v, layer);
+  if (maxq > 0)
+    hipLaunchKernelGGL(k_move_quant, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.B), dim3(256), 0, st, v, layer);
+  return hipGetLastError();
+}
+// streamed T1: the positions that left T1 in the plan just committed give up their entry in the host-row table
+__global__ void k_clear_host_rows(DevView v) {
+  const int b = blockIdx.y;
+  const int* cnt = v.cnt + b * CNT_N;
+  const int n = cnt[C_M10] + cnt[C_M12] + cnt[C_M13];
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const int h = v.h_clr[(size_t)b * v.Nmax + j];
+  if (h >= 0) v.h_dst[h] = -1;
+}
+hipError_t launch_clear_host_rows(const DevView& v, int max_leaving, hipStream_t st) {
+  if (max_leaving > 0)
+    hipLaunchKernelGGL(k_clear_host_rows, dim3((max_leaving + 255) / 256, v.B), dim3(256), 0, st, v);
   return hipGetLastError();
 }
 
@@ -578,8 +616,7 @@ __global__ void k_gather(DevView v, int layer, int r0, int nrows, char* __restri
   const int row = (int)(r / v.Hkv);
   const int b = v.g_seq[r0 + row], src = v.g_src[r0 + row];
   if (b < 0 || b >= v.B || src < 0 || src >= v.capF) return;
-  const char* base = which ? v.fpV : v.fpK;
-  *(u32x4*)(bounce + (size_t)i * 16) = *(const u32x4*)(base + fp_row(v, layer, b, kvh, src) + c * 16);
+  *(u32x4*)(bounce + (size_t)i * 16) = *(const u32x4*)(fp_ptr(v, which, layer, b, kvh, src) + c * 16);
 }
 // staging side of the prefetch: unpack a bounce piece (same layout) into the rows' staging slots
 __global__ void k_scatter(DevView v, int layer, int r0, int nrows, const char* __restrict__ bounce) {
@@ -594,8 +631,28 @@ __global__ void k_scatter(DevView v, int layer, int r0, int nrows, const char* _
   const int row = (int)(r / v.Hkv);
   const int b = v.g_seq[r0 + row], dst = v.g_dst[r0 + row];
   if (b < 0 || b >= v.B || dst < 0 || dst >= v.capF) return;
-  char* base = which ? v.fpV : v.fpK;
-  *(u32x4*)(base + fp_row(v, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
+  *(u32x4*)(fp_ptr(v, which, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
+}
+// streamed T1: unpack rows [r0, r0+nrows) of the pinned store's row order (one layer's copy of them, same piece
+// layout) into the frame; rows whose position is not in T1 any more are skipped
+__global__ void k_scatter_frame(DevView v, int r0, int nrows, const char* __restrict__ bounce) {
+  const int row_bytes = v.D * v.es, cpr = row_bytes / 16;
+  const long long total = (long long)nrows * v.Hkv * 2 * cpr;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cpr);
+  long long r = i / cpr;
+  const int which = (int)(r & 1); r >>= 1;
+  const int kvh = (int)(r % v.Hkv);
+  const int row = (int)(r / v.Hkv);
+  const int b = v.h_seq[r0 + row], dst = v.h_dst[r0 + row];
+  if (b < 0 || b >= v.B || dst < v.cap0 || dst >= v.capF) return;
+  *(u32x4*)(fp_ptr(v, which, 0, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
+}
+hipError_t launch_scatter_frame(const DevView& v, int r0, int nrows, const char* bounce, hipStream_t st) {
+  const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);
+  hipLaunchKernelGGL(k_scatter_frame, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, r0, nrows, bounce);
+  return hipGetLastError();
 }
 // Re-homing of the pinned store (it is filled by bump allocation and has run out): the rows T1 holds now get the
 // host rows host_base[b], host_base[b] + 1, ... in position order, every other position loses its host row, and

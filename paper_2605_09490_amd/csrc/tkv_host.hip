@@ -63,6 +63,14 @@ struct tkv_cache {
   int* pin_cnt = nullptr;          // pinned [B][CNT_N]
   int* pin_base = nullptr;         // pinned [B]
   int* d_host_base = nullptr;
+  // streamed T1: two frames, the layer each holds (-1: none), fill / release events
+  bool streamed = false;
+  char* frameK[2] = {nullptr, nullptr}; char* frameV[2] = {nullptr, nullptr};
+  int frame_layer[2] = {-1, -1};
+  bool frame_used[2] = {false, false};   // ev_free[f] has been recorded since the frame was last filled
+  hipEvent_t ev_filled[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+  std::vector<int> nS;             // per sequence: length of the T1 list
+  int64_t fill_piece = 0;
   std::vector<EvPair> copy_events; size_t copy_events_used = 0;
   std::vector<EvPair> prof_events; size_t prof_used = 0;
   tkv_stats st{};
@@ -168,6 +176,13 @@ tkv_status enqueue_job(tkv_cache* c, const XferJob& j) {
   HIPCHK(c, hipEventRecord(ea->a, c->sA));
   HIPCHK(c, hipMemcpyAsync(hp, ba, bytes, hipMemcpyDeviceToHost, c->sA));
   HIPCHK(c, hipEventRecord(ea->b, c->sA));
+  if (c->streamed) {
+    // the rows stay in the pinned store; the next fill of this layer's frame waits for the last piece
+    --c->copy_events_used;
+    c->st.d2h_bytes += (int64_t)bytes; c->st.d2h_copies++;
+    if (j.last_of_layer) { HIPCHK(c, hipEventRecord(c->ev_ready[j.layer], c->sA)); c->layer_enq[j.layer] = 1; }
+    return TKV_OK;
+  }
   HIPCHK(c, hipEventRecord(c->ev_piece[j.piece % RING], c->sA));
   HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_piece[j.piece % RING], 0));
   HIPCHK(c, hipEventRecord(eb->a, c->sB));
@@ -228,6 +243,37 @@ tkv_status harvest_profile(tkv_cache* c) {
     }
   }
   c->prof_used = 0;
+  return TKV_OK;
+}
+
+// Streamed T1: refill frame f with the T1 rows of `layer` from the pinned store (every row handed out so far; rows
+// whose position has left T1 are dropped by the scatter), on the prefetch stream, behind the frame's last reader and
+// the layer's last offload.
+tkv_status issue_fill(tkv_cache* c, int layer, int f) {
+  DevView vv = c->dv;
+  vv.frK = c->frameK[f]; vv.frV = c->frameV[f];
+  if (c->frame_used[f]) HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_free[f], 0));
+  if (c->layer_wait[layer]) { HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_ready[layer], 0)); c->layer_wait[layer] = 0; }
+  const size_t slot_bytes = c->bounce_bytes / RING;
+  const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
+  EvPair* ev = next_pair(c->copy_events, c->copy_events_used);
+  if (!ev) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+  ev->dir = 1; ev->bytes = 0;
+  HIPCHK(c, hipEventRecord(ev->a, c->sB));
+  for (int64_t r0 = 0; r0 < c->host_next; r0 += piece_rows) {
+    const int nrows = (int)std::min<int64_t>(piece_rows, c->host_next - r0);
+    const size_t bytes = (size_t)nrows * c->tok_bytes;
+    char* bb = c->bounceB + (size_t)(c->fill_piece++ % RING) * slot_bytes;   // one stream: refilled after its scatter
+    HIPCHK(c, hipMemcpyAsync(bb, c->hstore + ((size_t)layer * c->host_rows + (size_t)r0) * c->tok_bytes, bytes,
+                             hipMemcpyHostToDevice, c->sB));
+    HIPCHK(c, launch_scatter_frame(vv, (int)r0, nrows, bb, c->sB));
+    c->st.h2d_bytes += (int64_t)bytes; c->st.h2d_copies++;
+  }
+  HIPCHK(c, hipEventRecord(ev->b, c->sB));
+  HIPCHK(c, hipEventRecord(c->ev_filled[f], c->sB));
+  c->frame_layer[f] = layer;
+  c->frame_used[f] = false;
+  c->transfers_in_flight = true;
   return TKV_OK;
 }
 
@@ -294,7 +340,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   if (cfg->n_prompt < 0 || cfg->k_sink < 0 || cfg->k_window < 0) return bad("tkv_create: protected sizes must be >= 0");
   if (cfg->t0_rows < 0 || cfg->staging_rows < 0 || cfg->t2_rows < 0 || cfg->host_rows < 0 || cfg->bounce_bytes < 0)
     return bad("tkv_create: capacities must be >= 0");
-  if (cfg->prefetch_mode != TKV_PREFETCH_WAIT && cfg->prefetch_mode != TKV_PREFETCH_LAZY) return bad("tkv_create: prefetch_mode");
+  if (cfg->prefetch_mode < TKV_PREFETCH_WAIT || cfg->prefetch_mode > TKV_PREFETCH_STREAM) return bad("tkv_create: prefetch_mode");
   if (!(cfg->score_scale >= 0.f) || !(cfg->softmax_scale >= 0.f)) return bad("tkv_create: scales must be >= 0");
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr) || (cfg->pin_alloc == nullptr) != (cfg->pin_free == nullptr))
     return bad("tkv_create: allocator callbacks must come in alloc/free pairs");
@@ -320,6 +366,9 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   v.cap1 = cfg->staging_rows ? cfg->staging_rows : N;
   v.cap2 = cfg->t2_rows ? cfg->t2_rows : N;
   v.capF = v.cap0 + v.cap1;
+  c->streamed = cfg->prefetch_mode == TKV_PREFETCH_STREAM;
+  v.streamed = c->streamed ? 1 : 0;
+  v.capP = c->streamed ? v.cap0 : v.capF;
   v.es = c->es;
   v.t2fmt = cfg->t2_format;
   v.cb = cfg->t2_format == TKV_T2_INT8_ROW ? D : D / 2;
@@ -331,7 +380,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   const size_t rows = (size_t)L * B * Hkv;
   const size_t BN = (size_t)B * N;
   bool ok = true;
-  ok = ok && dalloc(c, v.fpK, rows * v.capF * D * c->es) && dalloc(c, v.fpV, rows * v.capF * D * c->es);
+  ok = ok && dalloc(c, v.fpK, rows * v.capP * D * c->es) && dalloc(c, v.fpV, rows * v.capP * D * c->es);
   ok = ok && dalloc(c, v.c2K, rows * v.cap2 * v.cb) && dalloc(c, v.c2V, rows * v.cap2 * v.cb);
   ok = ok && dalloc(c, v.s2K, rows * v.cap2 * v.sb) && dalloc(c, v.s2V, rows * v.cap2 * v.sb);
   ok = ok && dalloc(c, v.tier, BN) && dalloc(c, v.tier_new, BN) && dalloc(c, v.loc, BN) && dalloc(c, v.hloc, BN);
@@ -350,15 +399,26 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess || cus <= 0) cus = 256;
     c->S_alloc = std::max(1, cus / std::max(1, B * Hkv));
   }
-  c->xs_stride = (N / TOK_PER_BLOCK + 2) * TOK_PER_BLOCK;
+  c->xs_stride = (N / TOK_PER_BLOCK + 3) * TOK_PER_BLOCK;   // every list may end in a partly filled tile
   ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
-  ok = ok && dalloc(c, c->part_ml, (size_t)B * Hkv * c->S_alloc * 2 * G);
-  ok = ok && dalloc(c, c->part_o, (size_t)B * Hkv * c->S_alloc * G * D);
+  const int launches = c->streamed ? 2 : 1;   // streamed T1: a second attention launch serves the frame
+  ok = ok && dalloc(c, c->part_ml, (size_t)B * Hkv * c->S_alloc * launches * 2 * G);
+  ok = ok && dalloc(c, c->part_o, (size_t)B * Hkv * c->S_alloc * launches * G * D);
   c->tok_bytes = (size_t)Hkv * 2 * D * c->es;
   c->bounce_bytes = cfg->bounce_bytes ? (size_t)cfg->bounce_bytes : ((size_t)64 << 20);
   if (c->bounce_bytes < RING * c->tok_bytes) c->bounce_bytes = RING * c->tok_bytes;
   ok = ok && dalloc(c, c->bounceA, c->bounce_bytes) && dalloc(c, c->bounceB, c->bounce_bytes);
   c->host_rows = cfg->host_rows ? cfg->host_rows : (int64_t)B * N;
+  if (c->streamed) {
+    const size_t frame_bytes = (size_t)B * Hkv * v.cap1 * D * c->es;
+    for (int f = 0; f < 2; ++f) ok = ok && dalloc(c, c->frameK[f], frame_bytes) && dalloc(c, c->frameV[f], frame_bytes);
+    ok = ok && dalloc(c, v.s_pos, BN) && dalloc(c, v.s_loc, BN) && dalloc(c, v.h_clr, BN);
+    ok = ok && dalloc(c, v.h_seq, (size_t)c->host_rows) && dalloc(c, v.h_dst, (size_t)c->host_rows);
+    if (ok && (hipMemset(v.h_seq, 0xFF, (size_t)c->host_rows * sizeof(int)) != hipSuccess ||
+               hipMemset(v.h_dst, 0xFF, (size_t)c->host_rows * sizeof(int)) != hipSuccess))
+      return die(TKV_EDEVICE, "tkv_create: state initialisation failed");
+    v.frK = c->frameK[0]; v.frV = c->frameV[0];
+  }
   if (ok) {
     c->hstore = (char*)pin_alloc(c, (size_t)L * c->host_rows * c->tok_bytes);
     c->pin_cnt = (int*)pin_alloc(c, (size_t)B * CNT_N * sizeof(int));
@@ -368,7 +428,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   if (!ok) return die(TKV_ENOMEM, "tkv_create: an allocation failed");
 
   c->len.assign(L, 0);
-  c->nF.assign(B, 0); c->nQ.assign(B, 0);
+  c->nF.assign(B, 0); c->nQ.assign(B, 0); c->nS.assign(B, 0);
   c->free0.assign(B, v.cap0); c->free1.assign(B, v.cap1); c->free2.assign(B, v.cap2); c->pend.assign(B, 0);
   c->ntier.assign(4, 0);
   c->ev_ready.assign(L, nullptr);
@@ -381,6 +441,9 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   bool evok = hipEventCreateWithFlags(&c->ev_plan, hipEventDisableTiming) == hipSuccess;
   for (int i = 0; i < RING && evok; ++i) evok = hipEventCreateWithFlags(&c->ev_piece[i], hipEventDisableTiming) == hipSuccess;
   for (int l = 0; l < L && evok; ++l) evok = hipEventCreateWithFlags(&c->ev_ready[l], hipEventDisableTiming) == hipSuccess;
+  for (int f = 0; f < 2 && evok && c->streamed; ++f)
+    evok = hipEventCreateWithFlags(&c->ev_filled[f], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&c->ev_free[f], hipEventDisableTiming) == hipSuccess;
   if (!evok) return die(TKV_EDEVICE, "tkv_create: hipEventCreate failed");
   if (launch_init_state(v, nullptr) != hipSuccess || hipStreamSynchronize(nullptr) != hipSuccess)
     return die(TKV_EDEVICE, "tkv_create: state initialisation failed");
@@ -396,6 +459,8 @@ void tkv_destroy(tkv_cache* c) {
   if (c->ev_plan) (void)hipEventDestroy(c->ev_plan);
   for (auto e : c->ev_piece) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_ready) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_filled) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_free) if (e) (void)hipEventDestroy(e);
   for (auto& p : c->copy_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (auto& p : c->prof_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (void* p : c->dev_allocs) { if (c->cfg.dev_free) c->cfg.dev_free(p, c->cfg.alloc_ctx); else (void)hipFree(p); }
@@ -440,7 +505,17 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   hipStream_t st = (hipStream_t)hip_stream;
   const DevView& v = c->dv;
   bool use_old = false;
-  if (c->layer_wait[layer]) {
+  const int fr = layer & 1;
+  if (c->streamed) {
+    // the layer's T1 rows must be in its frame (normally the fill was issued two layers ago)
+    bool any = false;
+    for (int b = 0; b < v.B; ++b) any = any || c->nS[b] > 0;
+    if (any) {
+      if (c->frame_layer[fr] != layer) { tkv_status fs = issue_fill(c, layer, fr); if (fs != TKV_OK) return fs; }
+      HIPCHK(c, hipStreamWaitEvent(st, c->ev_filled[fr], 0));
+      c->st.attend_waits++;
+    }
+  } else if (c->layer_wait[layer]) {
     if (c->cfg.prefetch_mode == TKV_PREFETCH_WAIT) {
       while (!c->layer_enq[layer] && c->jobs_next < c->jobs.size()) {
         tkv_status ps = pump_transfers(c, 1);
@@ -457,16 +532,20 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
       else return fail(c, TKV_EDEVICE, "hipEventQuery failed: %s", hipGetErrorString(e));
     }
   }
-  int n_tiles = 1;
-  for (int b = 0; b < v.B; ++b)
-    n_tiles = std::max(n_tiles, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK + (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
+  auto tiles = [](int n) { return (n + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK; };
+  int n_tiles = 1, n_tiles_s = 0;
+  for (int b = 0; b < v.B; ++b) {
+    n_tiles = std::max(n_tiles, tiles(c->nF[b]) + tiles(c->nQ[b]) + tiles(c->nS[b]));
+    n_tiles_s = std::max(n_tiles_s, tiles(c->nS[b]));
+  }
   if (n_tiles * TOK_PER_BLOCK > c->xs_stride) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal tile count %d exceeds the scratch", n_tiles);
   // no more workgroups per pair than there are tiles for their waves
   const int nw = attn_waves_per_group(v.D, c->bf16, c->G);
-  const int S = std::max(1, std::min(c->S_alloc, (n_tiles + nw - 1) / nw));
+  const int S = std::max(1, std::min(c->S_alloc, (n_tiles - n_tiles_s + nw - 1) / nw));
+  const int S2 = n_tiles_s > 0 ? std::max(1, std::min(c->S_alloc, (n_tiles_s + nw - 1) / nw)) : 0;
   AttnArgs a{};
   const size_t lrows = (size_t)layer * v.B * v.Hkv;
-  a.fpK = v.fpK + lrows * v.capF * v.D * v.es; a.fpV = v.fpV + lrows * v.capF * v.D * v.es;
+  a.fpK = v.fpK + lrows * v.capP * v.D * v.es; a.fpV = v.fpV + lrows * v.capP * v.D * v.es;
   a.c2K = v.c2K + lrows * v.cap2 * v.cb; a.c2V = v.c2V + lrows * v.cap2 * v.cb;
   a.s2K = v.s2K + lrows * v.cap2 * v.sb; a.s2V = v.s2V + lrows * v.cap2 * v.sb;
   a.q = q; a.out = out;
@@ -475,11 +554,11 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   a.q_es = c->es;
   if (v.B <= ATTN_ARG_SEQS)
     for (int b = 0; b < v.B; ++b) {
-      a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b];
-      a.nWq[b] = attn_q_waves(S * nw, (c->nF[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK, (c->nQ[b] + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
+      a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b]; a.nS[b] = c->nS[b];
+      a.nWq[b] = attn_q_waves(S * nw, tiles(c->nF[b]), tiles(c->nQ[b]));
     }
-  a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capF; a.cap2 = v.cap2;
-  a.S = S; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
+  a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capP; a.cap2 = v.cap2;
+  a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
   EvPair* pe = nullptr;
   if (c->cfg.profile) {
@@ -487,7 +566,29 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
     if (!pe) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
   }
   HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
+  if (S2 > 0) {
+    // streamed T1: the same kernel over the T1 list, rows in the frame; its splits follow the first launch's
+    AttnArgs a2 = a;
+    a2.fpK = c->frameK[fr]; a2.fpV = c->frameV[fr]; a2.capF = v.cap1;
+    a2.f_loc = v.s_loc; a2.f_pos = v.s_pos;
+    a2.S = S2; a2.s0 = S; a2.second = 1;
+    if (v.B <= ATTN_ARG_SEQS)
+      for (int b = 0; b < v.B; ++b) {
+        a2.xs_base[b] = tiles(c->nF[b]) + tiles(c->nQ[b]);
+        a2.nF[b] = c->nS[b]; a2.nQ[b] = 0; a2.nWq[b] = 0;
+      }
+    HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->bf16, st, nullptr, nullptr));
+  }
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
+  if (c->streamed && S2 > 0) {
+    HIPCHK(c, hipEventRecord(c->ev_free[fr], st));
+    c->frame_used[fr] = true;
+    // refill this frame for the layer that uses it next (two layers on, or the next step's first layers)
+    const int L = v.L;
+    const int nxt = layer + 2 < L ? layer + 2 : fr;
+    if (nxt < L && nxt != layer) { tkv_status fs = issue_fill(c, nxt, fr); if (fs != TKV_OK) return fs; }
+    return TKV_OK;
+  }
   // lazy mode spreads the issue of a re-tiering event's copies over the following attention calls, one layer each,
   // so the compute stream is never left empty while the host queues them
   if (c->jobs_next < c->jobs.size()) return pump_transfers(c, 1);
@@ -579,7 +680,7 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
   if (c->host_next + total_new_t1 <= c->host_rows) break;
   // The store hands out rows in order and has too few left.  Packed, it needs the rows T1 holds now plus every row
   // that enters (none of which keeps a host copy across the rewrite); if that fits, rewrite it and count again.
-  if (pass > 0 || live1 + enter1 > c->host_rows)
+  if (pass > 0 || c->streamed || live1 + enter1 > c->host_rows)
     return fail(c, TKV_ECAPACITY, "tkv_migrate: pinned T1 store: %lld rows in T1, %lld enter, capacity %lld",
                 (long long)live1, (long long)enter1, (long long)c->host_rows);
   tkv_status rs = rehome_store(c, n, st);
@@ -588,12 +689,46 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
   HIPCHK(c, hipMemcpyAsync(c->d_host_base, c->pin_base, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
   v.event_base = (int)c->host_next;
   HIPCHK(c, launch_plan_commit(v, n, st));
-  HIPCHK(c, launch_moves(v, max10, maxq, maxd, st));
+  if (!c->streamed) {
+    HIPCHK(c, launch_moves(v, max10, maxq, maxd, st));
+  } else {
+    // Rows that leave T1 for T0 or T2 are read from a frame, layer by layer, each after a fill from the pinned store
+    // (the table of host rows still names them; they are struck from it afterwards).  Rows that come out of T2 and
+    // rows that only move inside HBM do not need the frames.
+    HIPCHK(c, launch_decode_moves(v, maxd, st));
+    int64_t from_t1 = 0;
+    int max_leaving = 0;
+    for (int b = 0; b < B; ++b) {
+      const int* k = c->pin_cnt + b * CNT_N;
+      from_t1 += k[C_M10] + k[C_M12];
+      max_leaving = std::max(max_leaving, k[C_M10] + k[C_M12] + k[C_M13]);
+    }
+    c->frame_layer[0] = c->frame_layer[1] = -1;
+    if (from_t1 == 0) {
+      HIPCHK(c, launch_moves(v, max10, maxq, 0, st));
+    } else {
+      HIPCHK(c, hipEventRecord(c->ev_plan, st));
+      HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_plan, 0));
+      for (int l = 0; l < L; ++l) {
+        const int f = l & 1;
+        tkv_status fs = issue_fill(c, l, f);
+        if (fs != TKV_OK) return fs;
+        HIPCHK(c, hipStreamWaitEvent(st, c->ev_filled[f], 0));
+        DevView vv = v;
+        vv.frK = c->frameK[f]; vv.frV = c->frameV[f];
+        HIPCHK(c, launch_moves_layer(vv, l, max10, maxq, st));
+        HIPCHK(c, hipEventRecord(c->ev_free[f], st));
+        c->frame_used[f] = true;
+      }
+      c->frame_layer[0] = c->frame_layer[1] = -1;   // the frames hold the rows of the old plan
+    }
+    HIPCHK(c, launch_clear_host_rows(v, max_leaving, st));
+  }
   // host mirrors of what plan_commit leaves on the device
   for (int t = 0; t < 4; ++t) c->ntier[t] = 0;
   for (int b = 0; b < B; ++b) {
     const int* k = c->pin_cnt + b * CNT_N;
-    c->nF[b] = k[C_P0] + k[C_P1]; c->nQ[b] = k[C_P2];
+    c->nF[b] = c->streamed ? k[C_P0] : k[C_P0] + k[C_P1]; c->nQ[b] = k[C_P2]; c->nS[b] = c->streamed ? k[C_P1] : 0;
     for (int t = 0; t < 4; ++t) c->ntier[t] += k[C_P0 + t];
     const int e0 = k[C_M10] + k[C_M20] + k[C_M21], e1 = k[C_M01] + k[C_M21], e2 = k[C_M02] + k[C_M12];
     c->free0[b] = k[C_FREE0] + k[C_PEND] - e0 + k[C_M02] + k[C_M03] + k[C_M01R];
@@ -618,7 +753,7 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
       c->layer_wait[l] = 1;
       c->layer_enq[l] = 0;
     }
-    if (c->cfg.prefetch_mode == TKV_PREFETCH_WAIT) {
+    if (c->cfg.prefetch_mode != TKV_PREFETCH_LAZY) {
       tkv_status ps = pump_transfers(c, L);
       if (ps != TKV_OK) return ps;
     }
@@ -732,7 +867,7 @@ tkv_status tkv_get_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head
   const size_t rb = (size_t)v.D * v.es;
   if (tier == 0) {
     if (loc < 0 || loc >= v.capF) return fail(c, TKV_EDEVICE, "tkv_get_row: corrupt slot %d", loc);
-    const size_t off = ((((size_t)layer * v.B + seq) * v.Hkv + kv_head) * v.capF + loc) * rb;
+    const size_t off = ((((size_t)layer * v.B + seq) * v.Hkv + kv_head) * v.capP + loc) * rb;
     HIPCHK(c, hipMemcpy(host_out, (which ? v.fpV : v.fpK) + off, rb, hipMemcpyDeviceToHost));
     return TKV_OK;
   }

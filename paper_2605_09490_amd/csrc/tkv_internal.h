@@ -20,7 +20,8 @@ enum Cnt : int {
   C_P0, C_P1, C_P2, C_P3,   // planned positions per tier (plan_count)
   C_M01R,        // of the T0->T1 moves, rows whose copy in the pinned store is still valid (no transfer: copied inside HBM)
   C_MCOPY,       // rows copied inside HBM: T1->T0 plus the T0->T1 moves counted in C_M01R
-  CNT_N = 28
+  C_NS,          // streamed T1: entries of the T1 list (list F then holds T0 alone)
+  CNT_N = 29
 };
 
 constexpr int TOK_PER_BLOCK = 64;    // list entries per attention tile (one per lane of a wave)
@@ -64,6 +65,16 @@ struct DevView {
   int* g_seq; int* g_src; int* g_dst;   // [host_rows_per_event]: sequence, HBM slot to read, staging slot to fill
   const int* host_base;     // [B] first host row of the sequence's rows at this migrate
   int event_base;           // first host row of this migrate
+  // Streamed T1: the staging slots cap0 .. capF-1 are not backed per layer; one frame [B][Hkv][cap1][D*es] (K and V)
+  // is refilled from the pinned store for the layer that is attended next.
+  int streamed;             // != 0: streamed T1
+  int capP;                 // rows per (layer, seq, kv head) of the pool fpK / fpV: capF, or cap0 when streamed
+  char* frK; char* frV;     // the frame the row movers read staging slots from (set per launch)
+  int* s_pos; int* s_loc;   // [B][Nmax] streamed: list of the T1 rows (position, frame slot = staging slot - cap0); list F
+                            // then holds T0 alone
+  int* h_seq; int* h_dst;   // [host_rows] streamed: for every row of the pinned store its sequence and the staging slot of
+                            // the T1 position it belongs to (-1: the row's position is not in T1 any more)
+  int* h_clr;               // [B][Nmax] scratch: host rows of the positions that leave T1 in the plan being committed
 };
 
 struct AttnArgs {
@@ -76,12 +87,18 @@ struct AttnArgs {
   float* xs;        // [B][Hkv][G][xs_stride] scaled logits by list index (F tiles, then Q tiles)
   float* part_ml;   // [B][Hkv][S][2][G]  (m, l) of each split (= workgroup)
   float* part_o;    // [B][Hkv][S][G][D]
-  int S;            // workgroups per (sequence, kv head)
-  int n_tiles;      // max over the sequences of F tiles + Q tiles
+  int S;            // workgroups per (sequence, kv head) of this launch
+  int S_total, s0;  // splits the finishing kernel merges, and the first one this launch writes (streamed T1: a second
+                    // launch serves the T1 rows from the staging frame and writes the splits after the first launch's)
+  int second;       // != 0: that second launch; its list lengths are nS, its logits follow the first launch's tiles
+  const int* s_pos; // [B][Nmax] positions of the T1 list (streamed T1), for the finishing kernel
+  int n_tiles;      // max over the sequences of F tiles + Q tiles (+ T1 tiles)
   int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_bf16, q_es;
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
   int nWq[ATTN_ARG_SEQS];                     // waves of each (sequence, kv head) pair that serve the Q list (same condition)
+  int nS[ATTN_ARG_SEQS];                      // streamed T1: length of the T1 list
+  int xs_base[ATTN_ARG_SEQS];                 // second launch: first logits tile of the sequence (= its F tiles + Q tiles)
 };
 
 // launchers (defined in the .hip files)
@@ -96,6 +113,11 @@ hipError_t launch_classify(const DevView& v, int n, const uint32_t* ppm, hipStre
 hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st);
 hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st);
 hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st);
+// streamed T1: the two movers that may read staging slots, for one layer whose rows are in the frame v.frK / v.frV
+hipError_t launch_moves_layer(const DevView& v, int layer, int max10, int maxq, hipStream_t st);
+hipError_t launch_decode_moves(const DevView& v, int maxd, hipStream_t st);
+hipError_t launch_clear_host_rows(const DevView& v, int max_leaving, hipStream_t st);
+hipError_t launch_scatter_frame(const DevView& v, int r0, int nrows, const char* bounce, hipStream_t st);
 hipError_t launch_rehome(const DevView& v, int n, hipStream_t st);
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st);
 hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st);

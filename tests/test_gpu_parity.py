@@ -252,9 +252,24 @@ def test_pinned_store_is_rewritten_when_it_runs_out(mode):
     assert st["n_rehome"] >= 2 and st["host_rows_used"] <= 520
 
 
-def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False, rounds=8):
+@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,t2,layers", [
+    ("bf16", 128, 10, 2, "int8_row", 5),
+    ("f32", 64, 8, 2, "int4_g32", 2),
+    ("bf16", 64, 3, 3, "int8_row", 1),
+])
+def test_streamed_t1_walk(kv_dtype, D, Hq, Hkv, t2, layers):
+    """Streamed T1: no per-layer staging buffer; every attention call reads its layer's T1 rows from one of two
+    frames refilled from the pinned store.  The same random walk of plans (rows leaving T1 for T0 and T2 are read back
+    through the frames, rows returning to T1 with a valid host copy move nothing), every T1 row's bits in the pinned
+    store, outputs and scores against the oracle; with 5, 2 and 1 layers (frames recycled, one layer per frame, one
+    frame)."""
+    st = _plan_walk("stream", kv_dtype, D, Hq, Hkv, t2, all_t1_rows=True, layers=layers)
+    assert st["h2d_bytes"] > st["d2h_bytes"] > 0        # T1 crosses the link again at every step
+
+
+def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False, rounds=8, layers=2):
     from gpu_common import assert_out_close, assert_scores_close
-    cfg = small_config(n_layers=2, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+    cfg = small_config(n_layers=layers, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
                        context=500, decode_steps=rounds, t2_format=t2, sigma=1.0)
     p = _pair(cfg, prefetch_mode=mode, **({"host_rows": host_rows} if host_rows else {}))
     rng = np.random.default_rng(77)
@@ -278,10 +293,10 @@ def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False
             pos_t = np.nonzero(tiers[1] == t)[0]
             for pos in (pos_t if (t == 1 and all_t1_rows) else rng.choice(pos_t, size=min(3, len(pos_t)), replace=False)):
                 for which, store in ((0, p.orc.K), (1, p.orc.V)):
-                    row = p.gpu.get_row(1, 1, 1, int(pos), which)
+                    row = p.gpu.get_row(cfg.n_layers - 1, 1, 1, int(pos), which)
                     if kv_dtype == "bf16":
                         row = (row.astype(np.uint32) << 16).view(np.float32)
-                    assert np.array_equal(row.astype(np.float64), store[1][1, 1, int(pos)]), (rnd, t, pos, which)
+                    assert np.array_equal(row.astype(np.float64), store[cfg.n_layers - 1][1, 1, int(pos)]), (rnd, t, pos, which)
         for l in range(cfg.n_layers):
             k, v = p.wl.step_kv(rnd, l)
             p.append(l, k, v)
