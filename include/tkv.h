@@ -67,8 +67,8 @@ typedef enum { TKV_T2_INT8_ROW = 0, TKV_T2_INT4_G32 = 1 } tkv_t2_format;
  *  STREAM: T1 rows are not kept in HBM at all between uses: the staging buffer is two layer-sized frames shared by
  *        all layers, and every tkv_attend_and_score reads its layer's T1 rows from a frame that was refilled from the
  *        pinned store (hipMemcpyAsync on the prefetch stream, event-ordered) while the previous layers were attended.
- *        HBM then holds T0, T2 and two frames; every decode step moves all of T1 over the host link.  In this mode
- *        the pinned store is not rewritten when it runs out (TKV_ECAPACITY): size host_rows for the run. */
+ *        HBM then holds T0, T2 and two frames; every decode step moves all of T1 over the host link (and the rows of
+ *        the pinned store whose positions have left T1 since the store was last rewritten). */
 typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1, TKV_PREFETCH_STREAM = 2 } tkv_prefetch_mode;
 
 typedef struct {

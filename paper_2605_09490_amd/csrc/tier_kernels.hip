@@ -687,6 +687,23 @@ hipError_t launch_rehome(const DevView& v, int n, hipStream_t st) {
   hipLaunchKernelGGL(k_rehome, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
   return hipGetLastError();
 }
+// streamed T1, after a re-homing: the table of host rows, rebuilt from the positions' new host rows
+__global__ void k_htable_clear(DevView v, int rows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows) { v.h_seq[i] = -1; v.h_dst[i] = -1; }
+}
+__global__ void k_htable_fill(DevView v, int n) {
+  const int b = blockIdx.y, i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const size_t o = (size_t)b * v.Nmax;
+  const int h = v.hloc[o + i];
+  if (v.tier[o + i] == 1 && h >= 0) { v.h_seq[h] = b; v.h_dst[h] = v.loc[o + i]; }
+}
+hipError_t launch_rebuild_htable(const DevView& v, int n, int rows, hipStream_t st) {
+  hipLaunchKernelGGL(k_htable_clear, dim3((rows + 255) / 256), dim3(256), 0, st, v, rows);
+  hipLaunchKernelGGL(k_htable_fill, dim3((n + 255) / 256, v.B), dim3(256), 0, st, v, n);
+  return hipGetLastError();
+}
 
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st) {
   const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);

@@ -281,6 +281,8 @@ tkv_status issue_fill(tkv_cache* c, int layer, int f) {
 // sequence, in position order) and rewrite the store from their staged copies, one D2H per layer and bounce piece.
 // All transfers have been drained, so every T1 row is in its staging slot and nothing reads the store.  T0 rows
 // lose their (reusable) host copy.  pin_cnt holds the counters plan_count has just left.
+// Streamed T1 has no staged copies: each layer's rows are first brought into a frame (by the old table of host rows),
+// packed from there, and the table is rebuilt at the end.
 tkv_status rehome_store(tkv_cache* c, int n, hipStream_t st) {
   DevView& v = c->dv;
   const int B = v.B, L = v.L;
@@ -290,21 +292,36 @@ tkv_status rehome_store(tkv_cache* c, int n, hipStream_t st) {
   HIPCHK(c, launch_rehome(v, n, st));
   HIPCHK(c, hipEventRecord(c->ev_plan, st));
   HIPCHK(c, hipStreamWaitEvent(c->sA, c->ev_plan, 0));
+  if (c->streamed) HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_plan, 0));
   const size_t slot_bytes = c->bounce_bytes / RING;
   const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
   int piece = 0;
   for (int l = 0; l < L; ++l) {
+    DevView vl = v;
+    if (c->streamed) {
+      const int f = l & 1;
+      tkv_status fs = issue_fill(c, l, f);
+      if (fs != TKV_OK) return fs;
+      HIPCHK(c, hipStreamWaitEvent(c->sA, c->ev_filled[f], 0));
+      vl.frK = c->frameK[f]; vl.frV = c->frameV[f];
+    }
     for (int64_t r0 = 0; r0 < total; r0 += piece_rows, ++piece) {
       const int nrows = (int)std::min<int64_t>(piece_rows, total - r0);
       const size_t bytes = (size_t)nrows * c->tok_bytes;
       char* ba = c->bounceA + (size_t)(piece % RING) * slot_bytes;     // one stream: a ring slot is refilled after its copy
-      HIPCHK(c, launch_gather(v, l, (int)r0, nrows, ba, c->sA));
+      HIPCHK(c, launch_gather(vl, l, (int)r0, nrows, ba, c->sA));
       HIPCHK(c, hipMemcpyAsync(c->hstore + ((size_t)l * c->host_rows + (size_t)r0) * c->tok_bytes, ba, bytes,
                                hipMemcpyDeviceToHost, c->sA));
       c->st.d2h_bytes += (int64_t)bytes; c->st.d2h_copies++;
     }
+    if (c->streamed) { HIPCHK(c, hipEventRecord(c->ev_free[l & 1], c->sA)); c->frame_used[l & 1] = true; }
   }
   HIPCHK(c, hipStreamSynchronize(c->sA));
+  if (c->streamed) {
+    HIPCHK(c, hipStreamSynchronize(c->sB));
+    HIPCHK(c, launch_rebuild_htable(v, n, (int)c->host_rows, st));
+    c->frame_layer[0] = c->frame_layer[1] = -1;
+  }
   c->host_next = total;
   c->st.n_rehome++;
   return TKV_OK;
@@ -680,7 +697,7 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
   if (c->host_next + total_new_t1 <= c->host_rows) break;
   // The store hands out rows in order and has too few left.  Packed, it needs the rows T1 holds now plus every row
   // that enters (none of which keeps a host copy across the rewrite); if that fits, rewrite it and count again.
-  if (pass > 0 || c->streamed || live1 + enter1 > c->host_rows)
+  if (pass > 0 || live1 + enter1 > c->host_rows)
     return fail(c, TKV_ECAPACITY, "tkv_migrate: pinned T1 store: %lld rows in T1, %lld enter, capacity %lld",
                 (long long)live1, (long long)enter1, (long long)c->host_rows);
   tkv_status rs = rehome_store(c, n, st);

@@ -119,6 +119,7 @@ hipError_t launch_decode_moves(const DevView& v, int maxd, hipStream_t st);
 hipError_t launch_clear_host_rows(const DevView& v, int max_leaving, hipStream_t st);
 hipError_t launch_scatter_frame(const DevView& v, int r0, int nrows, const char* bounce, hipStream_t st);
 hipError_t launch_rehome(const DevView& v, int n, hipStream_t st);
+hipError_t launch_rebuild_htable(const DevView& v, int n, int rows, hipStream_t st);
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st);
 hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st);
 hipError_t launch_init_state(const DevView& v, hipStream_t st);

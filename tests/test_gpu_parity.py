@@ -242,12 +242,13 @@ def test_random_walk_of_plans(mode, kv_dtype, D, Hq, Hkv, t2):
     assert st["n_rehome"] == 0
 
 
-@pytest.mark.parametrize("mode", ["wait", "lazy"])
-def test_pinned_store_is_rewritten_when_it_runs_out(mode):
+@pytest.mark.parametrize("mode,layers", [("wait", 2), ("lazy", 2), ("stream", 2), ("stream", 5)])
+def test_pinned_store_is_rewritten_when_it_runs_out(mode, layers):
     """A longer walk of the same kind with a pinned store of 520 rows: T1 holds ~300 rows and ~100 enter at every plan, so the store
     (rows are handed out in order) runs out every second or third plan and is rewritten from the staged copies; after every
-    plan EVERY T1 row of one (layer, kv head) is read back from the pinned store and compared bit by bit."""
-    st = _plan_walk(mode, "bf16", 128, 10, 2, "int8_row", host_rows=520, all_t1_rows=True, rounds=16)
+    plan EVERY T1 row of one (layer, kv head) is read back from the pinned store and compared bit by bit.  (Streamed
+    T1 has no staged copies: there the rows pass through the frames on their way to their new place.)"""
+    st = _plan_walk(mode, "bf16", 128, 10, 2, "int8_row", host_rows=520, all_t1_rows=True, rounds=16, layers=layers)
     print(f"[case] store rewritten {st['n_rehome']} times, {st['host_rows_used']} rows in use", flush=True)
     assert st["n_rehome"] >= 2 and st["host_rows_used"] <= 520
 

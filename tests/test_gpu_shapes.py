@@ -149,3 +149,17 @@ def test_14b_full_depth_score_mass():
     st = gpu.get_stats()
     assert st["tier_count"][1] > 0 and st["tier_count"][2] > 0 and st["tier_count"][3] > 0
     gpu.close()
+
+
+def test_14b_shape_streamed_t1():
+    """The 14B per-layer shape with streamed T1 (three layers, so a frame is refilled while the other is read): all
+    outputs and scores against the oracle."""
+    _run_shape(dataclasses.replace(CONFIGS["14b"], n_layers=3, decode_steps=3), "stream")
+
+
+def test_batch_above_the_kernel_argument_limit_streamed_t1():
+    """More than 64 sequences with streamed T1: the second attention launch and the finishing kernel take the T1
+    list's length and its first logits tile from device counters."""
+    cfg = small_config(name="wide", n_layers=2, batch=70, n_q_heads=4, n_kv_heads=2, head_dim=64, kv_dtype="bf16",
+                       context=200, decode_steps=3, policy_ppm=(400_000, 300_000, 250_000, 50_000), k_window=16)
+    _run_shape(cfg, "stream", steps_before=1, steps_after=2)
