@@ -47,9 +47,16 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
     from tkv_synth import Workload
 
     wl = Workload(cfg, device="cuda")
+    sizes = {}
+    if mode == "stream":
+        # the two frames are sized for T1's share of the final length plus 30 % (a migrate takes the slots of the rows
+        # that enter T1 before it releases those of the rows that leave); the HBM pool still takes the whole context,
+        # which is appended before the first tiering
+        n_end = cfg.context + cfg.decode_steps
+        sizes = {"staging_rows": min(cfg.max_tokens, int(1.3 * policy[1] * n_end) // 1_000_000 + 64)}
     gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                        kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt, k_sink=cfg.k_sink,
-                       k_window=cfg.k_window, prefetch_mode=mode)
+                       k_window=cfg.k_window, prefetch_mode=mode, **sizes)
     for l in range(cfg.n_layers):
         k, v = wl.context_kv(l)
         gpu.append(l, k, v)
@@ -126,6 +133,8 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
         # 1/(L*Hq) each sequence's scores (evicted positions keep theirs) sum to the number of decode steps so far
         steps_done = 1 + (warmup - 1) + steps + profile_steps
         res["score_mass_rel_err"] = float(np.abs(sc.sum(1) / steps_done - 1.0).max())
+    res["device_bytes"] = st2["device_bytes"]
+    res["pinned_bytes"] = st2["pinned_bytes"]
     res["gpu"] = gpu
     res["wl"] = wl
     return res
@@ -203,7 +212,9 @@ def main():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="14b")
-    ap.add_argument("--mode", default="lazy", choices=["lazy", "wait"])
+    ap.add_argument("--mode", default="lazy", choices=["lazy", "wait", "stream"],
+                    help="T1 transport: lazy / wait keep all of T1 staged in HBM (differential prefetch); stream keeps two "
+                         "layer-sized frames and moves T1 over the link at every step")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
@@ -232,21 +243,25 @@ def main():
     log(f"[bench] workload {cfg.name}: L={cfg.n_layers} B={cfg.batch} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} D={cfg.head_dim} "
         f"{cfg.kv_dtype} ctx={cfg.context} policy={pol} t2={cfg.t2_format} mode={args.mode}")
     other_mode = "wait" if args.mode == "lazy" else "lazy"
+    stream = args.mode == "stream"
     # Job order: the all-HBM twin (same tier counts, T1 share kept in T0) and the other prefetch mode run first, then
     # the job `value` is taken from, then all three once more.  The overhead is a difference of two wall times and the
     # clock of a GPU that has just left idle drifts, so kinds are compared on the faster of their two runs; `value`
     # itself is always the one designated run (the first of the measured mode).
-    kinds = [args.mode] if args.no_twin else ["twin", other_mode, args.mode, "twin", other_mode, args.mode]
+    kinds = [args.mode] if args.no_twin else (["twin", args.mode] if stream else
+                                              ["twin", other_mode, args.mode, "twin", other_mode, args.mode])
     runs = {k: [] for k in kinds}
     runs_all_in = {k: [] for k in kinds}     # timed loop + the initial tiering with its cold fill
     main_res, cpu = None, None
+    mem = {}
     for kind in kinds:
         is_main = kind == args.mode and main_res is None
-        r = run_job(cfg, twin_pol if kind == "twin" else pol, args.mode if kind == "twin" else kind,
+        r = run_job(cfg, twin_pol if kind == "twin" else pol, ("lazy" if stream else args.mode) if kind == "twin" else kind,
                     args.steps, warmup, args.profile_steps if is_main else 0, kind, rule)
         runs[kind].append(r["wall_s"])
         runs_all_in[kind].append(r["wall_s"] + r["cold_fill_ms"] * 1e-3)
         log(f"[bench] {kind}: {r['ms_per_step']:.3f} ms/step" + (f", cold fill {r['cold_fill_ms']:.1f} ms" if is_main else ""))
+        mem[kind] = r.pop("device_bytes")
         if is_main:
             main_res = r
             if not args.no_cpu:
@@ -260,7 +275,7 @@ def main():
         extra = {
             "prefetch_overhead_all_in_pct": round(100.0 * (best_all[args.mode] - best_all["twin"]) / best_all["twin"], 2),
             "prefetch_overhead_pct": round(100.0 * (best[args.mode] - best["twin"]) / best["twin"], 2),
-            f"prefetch_overhead_pct_{other_mode}": round(100.0 * (best[other_mode] - best["twin"]) / best["twin"], 2),
+            **({} if stream else {f"prefetch_overhead_pct_{other_mode}": round(100.0 * (best[other_mode] - best["twin"]) / best["twin"], 2)}),
             "ms_per_step_runs": {k: [round(w * 1e3 / args.steps, 4) for w in v] for k, v in runs.items()},
         }
     value = main_res["bytes"] / main_res["wall_s"] / 1e9
@@ -292,7 +307,9 @@ def main():
                "cold_fill_ms": round(main_res["cold_fill_ms"], 1), "cold_fill_bytes": main_res["cold_fill_bytes"],
                "classify_ms_per_event": round(main_res["classify_ms"] / max(main_res["events"], 1), 3),
                "migrate_ms_per_event": round(main_res["migrate_ms"] / max(main_res["events"], 1), 3),
-               "attend_waits": main_res["attend_waits"], "lazy_old_reads": main_res["lazy_old_reads"], **extra},
+               "attend_waits": main_res["attend_waits"], "lazy_old_reads": main_res["lazy_old_reads"],
+               "device_bytes": mem.get(args.mode), "device_bytes_all_in_hbm_twin": mem.get("twin"),
+               "pinned_bytes": main_res["pinned_bytes"], **extra},
         "tier_count": main_res["tier_count"],
         "score_top20_share": round(main_res.get("top20_share", 0), 3), "score_bottom50_share": round(main_res.get("bottom50_share", 0), 3),
         "score_mass_rel_err": main_res.get("score_mass_rel_err"),

@@ -124,6 +124,8 @@ typedef struct {
   int64_t n_classify, n_migrate;
   int64_t n_rehome;           /* times the pinned T1 store ran full and was rewritten, packed, from the staged copies */
   int64_t host_rows_used;     /* rows of the pinned T1 store handed out since the last rewrite (all sequences) */
+  int64_t device_bytes;       /* device memory the cache holds (pools, frames, lists, scratch) */
+  int64_t pinned_bytes;       /* pinned host memory the cache holds */
 } tkv_stats;
 
 /* ---- life cycle ------------------------------------------------------------------------------ */

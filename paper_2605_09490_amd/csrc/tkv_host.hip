@@ -102,7 +102,7 @@ void* dev_alloc(tkv_cache* c, size_t bytes) {
   if (bytes == 0) bytes = 256;
   if (c->cfg.dev_alloc) p = c->cfg.dev_alloc(bytes, c->cfg.alloc_ctx);
   else if (hipMalloc(&p, bytes) != hipSuccess) p = nullptr;
-  if (p) c->dev_allocs.push_back(p);
+  if (p) { c->dev_allocs.push_back(p); c->st.device_bytes += (int64_t)bytes; }
   return p;
 }
 void* pin_alloc(tkv_cache* c, size_t bytes) {
@@ -110,7 +110,7 @@ void* pin_alloc(tkv_cache* c, size_t bytes) {
   if (bytes == 0) bytes = 256;
   if (c->cfg.pin_alloc) p = c->cfg.pin_alloc(bytes, c->cfg.alloc_ctx);
   else if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) p = nullptr;
-  if (p) c->pin_allocs.push_back(p);
+  if (p) { c->pin_allocs.push_back(p); c->st.pinned_bytes += (int64_t)bytes; }
   return p;
 }
 
@@ -239,7 +239,7 @@ tkv_status harvest_profile(tkv_cache* c) {
     HIPCHK(c, hipEventSynchronize(c->prof_events[i].b));
     if (hipEventElapsedTime(&ms, c->prof_events[i].a, c->prof_events[i].b) == hipSuccess) {
       c->st.attn_kernel_ms += ms;
-      c->st.attn_kernel_launches += 1;
+      if (c->prof_events[i].dir != 2) c->st.attn_kernel_launches += 1;   // 2: second launch of the same layer call
     }
   }
   c->prof_used = 0;
@@ -578,9 +578,18 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
   EvPair* pe = nullptr;
+  EvPair* pe2 = nullptr;
   if (c->cfg.profile) {
     pe = next_pair(c->prof_events, c->prof_used);
     if (!pe) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+    pe->dir = 0;
+    if (S2 > 0) {
+      const size_t i0 = c->prof_used - 1;
+      pe2 = next_pair(c->prof_events, c->prof_used);
+      if (!pe2) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+      pe2->dir = 2;
+      pe = &c->prof_events[i0];        // the pool may have grown
+    }
   }
   HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
   if (S2 > 0) {
@@ -594,7 +603,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
         a2.xs_base[b] = tiles(c->nF[b]) + tiles(c->nQ[b]);
         a2.nF[b] = c->nS[b]; a2.nQ[b] = 0; a2.nWq[b] = 0;
       }
-    HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->bf16, st, nullptr, nullptr));
+    HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->bf16, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
   if (c->streamed && S2 > 0) {
