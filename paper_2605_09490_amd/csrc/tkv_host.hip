@@ -69,6 +69,9 @@ struct tkv_cache {
   int frame_layer[2] = {-1, -1};
   bool frame_used[2] = {false, false};   // ev_free[f] has been recorded since the frame was last filled
   hipEvent_t ev_filled[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+  hipStream_t sC = nullptr;        // scatters of the frame fills, so the copies on sB run back to back
+  hipEvent_t ev_h2d[RING] = {}, ev_scat[RING] = {};
+  bool scat_used[RING] = {};
   std::vector<int> nS;             // per sequence: length of the T1 list
   int64_t fill_piece = 0;
   std::vector<EvPair> copy_events; size_t copy_events_used = 0;
@@ -218,6 +221,7 @@ tkv_status drain_transfers(tkv_cache* c) {
   if (c->transfers_in_flight) {
     HIPCHK(c, hipStreamSynchronize(c->sA));
     HIPCHK(c, hipStreamSynchronize(c->sB));
+    if (c->sC) HIPCHK(c, hipStreamSynchronize(c->sC));
     c->transfers_in_flight = false;
   }
   for (size_t i = 0; i < c->copy_events_used; ++i) {
@@ -252,7 +256,9 @@ tkv_status harvest_profile(tkv_cache* c) {
 tkv_status issue_fill(tkv_cache* c, int layer, int f) {
   DevView vv = c->dv;
   vv.frK = c->frameK[f]; vv.frV = c->frameV[f];
-  if (c->frame_used[f]) HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_free[f], 0));
+  // the copies (prefetch stream) wait for the layer's last offload, the scatters (their own stream) for the frame's
+  // last reader: the next layer's rows cross the link while the frame is still being read
+  if (c->frame_used[f]) HIPCHK(c, hipStreamWaitEvent(c->sC, c->ev_free[f], 0));
   if (c->layer_wait[layer]) { HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_ready[layer], 0)); c->layer_wait[layer] = 0; }
   const size_t slot_bytes = c->bounce_bytes / RING;
   const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
@@ -263,14 +269,20 @@ tkv_status issue_fill(tkv_cache* c, int layer, int f) {
   for (int64_t r0 = 0; r0 < c->host_next; r0 += piece_rows) {
     const int nrows = (int)std::min<int64_t>(piece_rows, c->host_next - r0);
     const size_t bytes = (size_t)nrows * c->tok_bytes;
-    char* bb = c->bounceB + (size_t)(c->fill_piece++ % RING) * slot_bytes;   // one stream: refilled after its scatter
+    const int slot = (int)(c->fill_piece++ % RING);
+    char* bb = c->bounceB + (size_t)slot * slot_bytes;
+    if (c->scat_used[slot]) HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_scat[slot], 0));   // the scatter that read this slot last
     HIPCHK(c, hipMemcpyAsync(bb, c->hstore + ((size_t)layer * c->host_rows + (size_t)r0) * c->tok_bytes, bytes,
                              hipMemcpyHostToDevice, c->sB));
-    HIPCHK(c, launch_scatter_frame(vv, (int)r0, nrows, bb, c->sB));
+    HIPCHK(c, hipEventRecord(c->ev_h2d[slot], c->sB));
+    HIPCHK(c, hipStreamWaitEvent(c->sC, c->ev_h2d[slot], 0));
+    HIPCHK(c, launch_scatter_frame(vv, (int)r0, nrows, bb, c->sC));
+    HIPCHK(c, hipEventRecord(c->ev_scat[slot], c->sC));
+    c->scat_used[slot] = true;
     c->st.h2d_bytes += (int64_t)bytes; c->st.h2d_copies++;
   }
   HIPCHK(c, hipEventRecord(ev->b, c->sB));
-  HIPCHK(c, hipEventRecord(c->ev_filled[f], c->sB));
+  HIPCHK(c, hipEventRecord(c->ev_filled[f], c->sC));
   c->frame_layer[f] = layer;
   c->frame_used[f] = false;
   c->transfers_in_flight = true;
@@ -319,6 +331,7 @@ tkv_status rehome_store(tkv_cache* c, int n, hipStream_t st) {
   HIPCHK(c, hipStreamSynchronize(c->sA));
   if (c->streamed) {
     HIPCHK(c, hipStreamSynchronize(c->sB));
+    HIPCHK(c, hipStreamSynchronize(c->sC));
     HIPCHK(c, launch_rebuild_htable(v, n, (int)c->host_rows, st));
     c->frame_layer[0] = c->frame_layer[1] = -1;
   }
@@ -461,6 +474,11 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   for (int f = 0; f < 2 && evok && c->streamed; ++f)
     evok = hipEventCreateWithFlags(&c->ev_filled[f], hipEventDisableTiming) == hipSuccess &&
            hipEventCreateWithFlags(&c->ev_free[f], hipEventDisableTiming) == hipSuccess;
+  for (int i = 0; i < RING && evok && c->streamed; ++i)
+    evok = hipEventCreateWithFlags(&c->ev_h2d[i], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&c->ev_scat[i], hipEventDisableTiming) == hipSuccess;
+  if (c->streamed && hipStreamCreateWithFlags(&c->sC, hipStreamNonBlocking) != hipSuccess)
+    return die(TKV_EDEVICE, "tkv_create: hipStreamCreate failed");
   if (!evok) return die(TKV_EDEVICE, "tkv_create: hipEventCreate failed");
   if (launch_init_state(v, nullptr) != hipSuccess || hipStreamSynchronize(nullptr) != hipSuccess)
     return die(TKV_EDEVICE, "tkv_create: state initialisation failed");
@@ -473,6 +491,9 @@ void tkv_destroy(tkv_cache* c) {
   (void)hipDeviceSynchronize();
   if (c->sA) (void)hipStreamDestroy(c->sA);
   if (c->sB) (void)hipStreamDestroy(c->sB);
+  if (c->sC) (void)hipStreamDestroy(c->sC);
+  for (auto e : c->ev_h2d) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_scat) if (e) (void)hipEventDestroy(e);
   if (c->ev_plan) (void)hipEventDestroy(c->ev_plan);
   for (auto e : c->ev_piece) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_ready) if (e) (void)hipEventDestroy(e);
