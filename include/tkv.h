@@ -84,7 +84,10 @@ typedef struct {
   float score_scale;                   /* factor on the per-layer sum over query heads; 0 -> 1/(n_layers*n_q_heads) (Eq. 1) */
   float softmax_scale;                 /* 0 -> 1/sqrt(head_dim) (Eq. 3) */
   int32_t t0_rows, staging_rows, t2_rows; /* per-sequence capacity (in positions) of the HBM pool, the T1 staging
-                                          buffer and the compressed pool; 0 -> max_tokens */
+                                          buffer and the compressed pool; 0 -> max_tokens.  The staging buffer exists
+                                          once per layer, or (TKV_PREFETCH_STREAM) as two frames for all layers.  A migrate
+                                          takes the slots of the rows that enter a pool before it releases those of the
+                                          rows that leave it, so a pool needs room for one plan's set plus its entrants */
   int64_t host_rows;                   /* capacity of the pinned T1 store in positions, all sequences; 0 -> batch*max_tokens.
                                           Rows are handed out in order; when they run out tkv_migrate rewrites the store with
                                           the rows T1 holds at that moment (one full D2H of T1), so it must hold the T1 set
@@ -166,7 +169,9 @@ tkv_status tkv_classify(tkv_cache* c, const tkv_policy* policy, void* hip_stream
  * are copied back inside HBM, rows entering T2 are encoded from their current stored value, rows leaving T2
  * are stored as binary32(code*scale) rounded to kv_dtype, T2->T2 keeps its codes, rows entering T3 are
  * dropped everywhere.  ESTATE without a pending plan or if a position would leave T3; ECAPACITY if a pool
- * cannot take the rows entering it (nothing is changed then). */
+ * cannot take the rows entering it (nothing is changed then).
+ * TKV_PREFETCH_STREAM: T0->T1 rows only make the trip to the pinned store; rows leaving T1 for T0 or T2 are read
+ * back from it through the frames, layer by layer, inside this call. */
 tkv_status tkv_migrate(tkv_cache* c, void* hip_stream);
 
 /* ---- inspection and test hooks (host pointers; these synchronise) -------------------------- */
@@ -186,7 +191,8 @@ tkv_status tkv_get_t2_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_h
  * currently lives (HBM pool, or the pinned host store for T1).  ESTATE for T2/T3 positions. */
 tkv_status tkv_get_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head, int32_t pos, int32_t which,
                        void* host_out);
-/* Blocks until every T1 transfer started by tkv_migrate has landed in the staging buffer. */
+/* Blocks until every T1 transfer started by tkv_migrate (and, TKV_PREFETCH_STREAM, every frame refill in flight) has
+ * landed. */
 tkv_status tkv_wait_prefetch(tkv_cache* c);
 tkv_status tkv_get_stats(tkv_cache* c, tkv_stats* out);
 /* Switches the per-kernel HIP-event timing of the attention kernels on or off (see tkv_config.profile). */
