@@ -50,5 +50,34 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+HOST_CHECK = os.path.join(HERE, "_build", "host_sanitize_check")
+
+
+def build_host_check(verbose: bool = False) -> str:
+    """A second build of the host code (tkv_host.hip) with AddressSanitizer and UndefinedBehaviorSanitizer on the host
+    side only, linked with the ordinary kernel objects and the scenario driver tests/native/host_sanitize_check.cpp.
+    build() must have run (it leaves the kernel objects in _build/)."""
+    objdir = os.path.join(HERE, "_build")
+    hipcc = _hipcc()
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    host_obj = os.path.join(objdir, "tkv_host_san.o")
+    drv_obj = os.path.join(objdir, "host_sanitize_check.o")
+    drv_src = os.path.join(os.path.dirname(HERE), "tests", "native", "host_sanitize_check.cpp")
+    for cmd in ([hipcc, *FLAGS, "-g", *san, "-c", os.path.join(CSRC, "tkv_host.hip"), "-o", host_obj],
+                [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", *san, "-x", "hip", "-c", drv_src, "-o", drv_obj]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + r.stderr)
+    objs = [os.path.join(objdir, n) for _, _, n in UNITS if n != "tkv_host.o"]
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+                        drv_obj, host_obj, *objs, "-o", HOST_CHECK], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    if verbose:
+        print(HOST_CHECK, file=sys.stderr)
+    return HOST_CHECK
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_host_check(verbose=True))

@@ -87,3 +87,18 @@ def test_tier_counts_agree_with_oracle_and_reject_bad_policy():
         assert tkv.tier_counts(pol, m, ev, count_rule=1) == O.tier_counts_alg1(m, pol, ev)
     with pytest.raises(tkv.TkvError):
         tkv.tier_counts((1, 2, 3, 4), 10)
+
+
+def test_host_code_under_sanitizers_host_only_part():
+    """The library's host code built with AddressSanitizer and UndefinedBehaviorSanitizer (host side only) and driven by
+    tests/native/host_sanitize_check.cpp: here the part that needs no GPU (configuration validation, band sizes, NULL
+    handles).  The full scenario runs in the GPU suite."""
+    import subprocess
+    from paper_2605_09490_amd import build
+    exe = build.HOST_CHECK
+    if not os.path.exists(exe):
+        build.build_host_check()
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:protect_shadow_gap=0", UBSAN_OPTIONS="halt_on_error=1")
+    r = subprocess.run([exe, "--host-only"], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "host sanitizer check passed" in r.stdout

@@ -163,3 +163,19 @@ def test_batch_above_the_kernel_argument_limit_streamed_t1():
     cfg = small_config(name="wide", n_layers=2, batch=70, n_q_heads=4, n_kv_heads=2, head_dim=64, kv_dtype="bf16",
                        context=200, decode_steps=3, policy_ppm=(400_000, 300_000, 250_000, 50_000), k_window=16)
     _run_shape(cfg, "stream", steps_before=1, steps_after=2)
+
+
+def test_host_code_under_sanitizers():
+    """A randomised sequence of plans, decode steps, store rewrites and inspections in all three prefetch modes, run by a
+    build of the host code with AddressSanitizer and UndefinedBehaviorSanitizer (host side only; the kernels are the
+    ordinary ones): any host-memory error or undefined arithmetic in the bookkeeping aborts it."""
+    import os
+    import subprocess
+    from paper_2605_09490_amd import build
+    assert os.path.exists(build.HOST_CHECK), "build the sanitized host check first: python paper_2605_09490_amd/build.py"
+    print(f"[case] {build.HOST_CHECK}", flush=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:protect_shadow_gap=0", UBSAN_OPTIONS="halt_on_error=1")
+    r = subprocess.run([build.HOST_CHECK], capture_output=True, text=True, timeout=200, env=env)
+    print(r.stdout[-600:], flush=True)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    assert "host sanitizer check passed" in r.stdout
