@@ -49,7 +49,7 @@ typedef enum {
   TKV_EDEVICE = -5    /* a HIP call failed */
 } tkv_status;
 
-typedef enum { TKV_F32 = 0, TKV_BF16 = 1 } tkv_dtype;
+typedef enum { TKV_F32 = 0, TKV_BF16 = 1, TKV_F16 = 2 } tkv_dtype;   /* binary32, bfloat16, binary16 */
 
 /* T2 encodings (Sec. 3.2 only says "reduced precision, e.g. 8-bit"); both are symmetric, defined in
  * IEEE binary32 with round-to-nearest-even and true division, K row and V row encoded separately:
@@ -77,7 +77,8 @@ typedef struct {
   int32_t max_tokens;                  /* per-sequence capacity in positions (< 2^24) */
   int32_t kv_dtype;                    /* tkv_dtype: type of K, V and q */
   int32_t out_dtype;                   /* tkv_dtype of the attention output.  binary32 keeps the accumulator's value;
-                                          bf16 adds one round-to-nearest-even (up to 2^-8 relative per element) */
+                                          bf16 / binary16 add one round-to-nearest-even (up to 2^-8 / 2^-11 relative
+                                          per element) */
   int32_t t2_format;                   /* tkv_t2_format */
   int32_t n_prompt, k_sink, k_window;  /* protected regions (Sec. 3.2): prompt, first k_sink reasoning tokens,
                                           last k_window tokens; never offloaded, compressed or evicted */

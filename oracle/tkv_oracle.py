@@ -57,6 +57,8 @@ def round_to_storage(x32: np.ndarray, kv_dtype: str) -> np.ndarray:
         return np.asarray(x32, dtype=np.float32)
     if kv_dtype == "bf16":
         return round_to_bf16(x32)
+    if kv_dtype == "f16":
+        return round_to_fp16(x32)
     raise ValueError(kv_dtype)
 
 

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtkv.so")
 
 TKV_OK, TKV_EINVAL, TKV_ENOMEM, TKV_ECAPACITY, TKV_ESTATE, TKV_EDEVICE = 0, -1, -2, -3, -4, -5
-TKV_F32, TKV_BF16 = 0, 1
+TKV_F32, TKV_BF16, TKV_F16 = 0, 1, 2
 TKV_T2_INT8_ROW, TKV_T2_INT4_G32 = 0, 1
 TKV_PREFETCH_WAIT, TKV_PREFETCH_LAZY, TKV_PREFETCH_STREAM = 0, 1, 2
 TKV_COUNT_TOTAL, TKV_COUNT_ALG1 = 0, 1
@@ -128,14 +128,16 @@ class TieredKV:
         self.max_tokens = max_tokens
         self.kv_dtype = kv_dtype
         self.t2_format = t2_format
-        self.torch_dtype = torch.float32 if kv_dtype == "f32" else torch.bfloat16
-        self.out_torch_dtype = torch.float32 if out_dtype == "f32" else torch.bfloat16
+        torch_types = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+        codes = {"f32": TKV_F32, "bf16": TKV_BF16, "f16": TKV_F16}
+        self.torch_dtype = torch_types[kv_dtype]
+        self.out_torch_dtype = torch_types[out_dtype]
         self._held = {}
         cfg = tkv_config()
         cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_layers, batch, n_q_heads, n_kv_heads, head_dim
         cfg.max_tokens = max_tokens
-        cfg.kv_dtype = TKV_F32 if kv_dtype == "f32" else TKV_BF16
-        cfg.out_dtype = TKV_F32 if out_dtype == "f32" else TKV_BF16
+        cfg.kv_dtype = codes[kv_dtype]
+        cfg.out_dtype = codes[out_dtype]
         cfg.t2_format = TKV_T2_INT8_ROW if t2_format == "int8_row" else TKV_T2_INT4_G32
         cfg.n_prompt, cfg.k_sink, cfg.k_window = n_prompt, k_sink, k_window
         cfg.score_scale, cfg.softmax_scale = float(score_scale or 0.0), float(softmax_scale or 0.0)

@@ -9,8 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtkv.so")
-# (source, extra flags, object name); the attention kernels are one source compiled in five parts that build in parallel
-UNITS = [("attn_kernels.hip", [f"-DTKV_ATTN_PART={p}"], f"attn_kernels_{p}.o") for p in range(5)]
+# (source, extra flags, object name); the attention kernels are one source compiled in seven parts that build in parallel
+UNITS = [("attn_kernels.hip", [f"-DTKV_ATTN_PART={p}"], f"attn_kernels_{p}.o") for p in range(7)]
 UNITS += [("tkv_host.hip", [], "tkv_host.o"), ("tier_kernels.hip", [], "tier_kernels.o")]
 # packed-fp32 VALU forms are switched off on purpose (the compiler would otherwise emit them from plain float code)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -35,6 +35,7 @@ namespace tkv {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(3))) char lds_char;
 
@@ -42,7 +43,9 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr int TB = TOK_PER_BLOCK;
 static_assert(TB == 64, "a tile is one list entry per lane");
 
-enum Mode : int { F_BF16 = 0, F_F32 = 1, Q_INT8 = 2, Q_INT4 = 3 };
+enum Mode : int { F_BF16 = 0, F_F32 = 1, Q_INT8 = 2, Q_INT4 = 3, F_F16 = 4 };
+// type of K, V and q as a template argument: binary32, bfloat16, binary16
+constexpr int KT_F32 = 0, KT_BF16 = 1, KT_F16 = 2;
 
 template <class F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
@@ -185,6 +188,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+// two code values (exact in binary16) packed as a binary16 pair
+__device__ __forceinline__ uint32_t pack_f16_pair(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+__device__ __forceinline__ float f16_lo(uint32_t u) { return (float)__builtin_bit_cast(f16x2, u).x; }
+__device__ __forceinline__ float f16_hi(uint32_t u) { return (float)__builtin_bit_cast(f16x2, u).y; }
 // two code values (exact in bf16: at most 8 significant bits) packed as a bf16 pair
 __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
   return (__builtin_bit_cast(uint32_t, hi) & 0xffff0000u) | (__builtin_bit_cast(uint32_t, lo) >> 16);
@@ -204,7 +213,7 @@ struct GPad { static constexpr int v = (G <= 4) ? 4 : 8; };
 template <int D, Mode M>
 struct Geo {
   static constexpr bool IS_Q = (M == Q_INT8 || M == Q_INT4);
-  static constexpr int RB = (M == F_BF16) ? 2 * D : (M == F_F32) ? 4 * D : (M == Q_INT8) ? D : D / 2;   // bytes per row
+  static constexpr int RB = (M == F_BF16 || M == F_F16) ? 2 * D : (M == F_F32) ? 4 * D : (M == Q_INT8) ? D : D / 2;   // bytes per row
   static constexpr int KLB = RB / 8;                        // bytes of a K row per lane
   static constexpr int KS = (KLB % 16 == 0) ? 16 : 4;       // bytes per unit
   static constexpr int KU = KLB / KS;                       // units per lane and row
@@ -260,9 +269,10 @@ __device__ __forceinline__ void unpack_unit(const typename UnitT<S>::type& u, fl
 
 // The lane's units of the G query vectors.  bf16 queries stay packed (fed to the bf16 dot instruction); binary32
 // queries are kept as floats.  qs is the sum over a unit (Q modes only).
-template <int D, int G, Mode M, bool QBF>
+template <int D, int G, Mode M, int KT>
 struct QRegs {
   using GE = Geo<D, M>;
+  static constexpr bool QBF = KT != KT_F32;   // 16-bit queries stay packed in pairs
   uint32_t qp[QBF ? G : 1][GE::KU][GE::EUK / 2];
   float qf[QBF ? 1 : G][GE::KU][GE::EUK];
   float qs[G][GE::KU];
@@ -278,12 +288,26 @@ struct VStep {
 
 // G logits of one K row, reduced over the row's 8 lanes (every lane of the group gets them).
 // sc: INT8 the row's scale; INT4 the scale of the 32-code group of each of the lane's units.
-template <int D, int G, Mode M, bool QBF>
-__device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D, G, M, QBF>& q,
+template <int D, int G, Mode M, int KT>
+__device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D, G, M, KT>& q,
                                            const float (&sc)[Geo<D, M>::KU], float (&x)[G]) {
   using GE = Geo<D, M>;
   constexpr int KU = GE::KU, KS = GE::KS, EUK = GE::EUK;
-  if constexpr (M == F_BF16) {
+  constexpr bool QBF = KT != KT_F32, H = KT == KT_F16;
+  if constexpr (M == F_F16) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < KU; ++j)
+#pragma unroll
+        for (int c = 0; c < EUK / 2; ++c)
+          acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, unit_word<KS>(kr.u[j], c)),
+                                       __builtin_bit_cast(f16x2, q.qp[h][j][c]), acc, false);
+      x[h] = acc;
+    }
+    group_sum8_all<G>(x);
+  } else if constexpr (M == F_BF16) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float acc = 0.f;
@@ -318,15 +342,17 @@ __device__ __forceinline__ void row_logits(const KBatch<D, M>& kr, const QRegs<D
       uint32_t kp[EUK / 2];
       if constexpr (QBF) {
 #pragma unroll
-        for (int c = 0; c < EUK / 2; ++c) kp[c] = pack_bf16_pair(kf[2 * c], kf[2 * c + 1]);
+        for (int c = 0; c < EUK / 2; ++c) kp[c] = H ? pack_f16_pair(kf[2 * c], kf[2 * c + 1]) : pack_bf16_pair(kf[2 * c], kf[2 * c + 1]);
       }
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         float acc = -GE::OFF * q.qs[h][j];
         if constexpr (QBF) {
 #pragma unroll
-          for (int c = 0; c < EUK / 2; ++c)
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[c]), __builtin_bit_cast(bf16x2, q.qp[h][j][c]), acc, false);
+          for (int c = 0; c < EUK / 2; ++c) {
+            if constexpr (H) acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, kp[c]), __builtin_bit_cast(f16x2, q.qp[h][j][c]), acc, false);
+            else acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[c]), __builtin_bit_cast(bf16x2, q.qp[h][j][c]), acc, false);
+          }
         } else {
 #pragma unroll
           for (int c = 0; c < EUK; ++c) acc = fmaf(q.qf[h][j][c], kf[c], acc);
@@ -356,6 +382,9 @@ __device__ __forceinline__ void row_accumulate(const VStep<D, G, M>& vr, float s
   if constexpr (M == F_BF16) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) { const uint32_t wv = elem(vr.u[0], c); vf[2 * c] = bf_lo(wv); vf[2 * c + 1] = bf_hi(wv); }
+  } else if constexpr (M == F_F16) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { const uint32_t wv = elem(vr.u[0], c); vf[2 * c] = f16_lo(wv); vf[2 * c + 1] = f16_hi(wv); }
   } else if constexpr (M == F_F32) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) vf[c] = elem_f(vr.u[0], c);
@@ -403,7 +432,7 @@ __device__ __forceinline__ void dma(const __amdgpu_buffer_rsrc_t& rs, char* lds,
 //   V scales of t+1 | per V step of t: the K pieces of t+1 on its bytes
 // Accumulates into o (offset-corrected for code rows), m_run, l_lane (per-lane partial sums of the softmax
 // denominator, relative to m_run); leaves the scaled logits in xs.
-template <int D, int G, Mode M, bool QBF>
+template <int D, int G, Mode M, int KT>
 __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, int b, int kvh, int lane,
                                           int tile0, int tstride, int n_list, const int* loc_list, int xs_tile0,
                                           float (&o)[G][Geo<D, M>::EV], float (&m_run)[G], float (&l_lane)[G]) {
@@ -411,6 +440,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   constexpr int EV = GE::EV, LPRV = GE::LPRV, NITV = GE::NITV, KU = GE::KU, KS = GE::KS, VU = GE::VU, VS = GE::VS;
   constexpr int EUK = GE::EUK, SCD = GE::SCD, RB = GE::RB, N_K = GE::N_K, N_V = GE::N_V;
   constexpr int GP = GPad<G>::v;
+  constexpr bool QBF = KT != KT_F32, H = KT == KT_F16;
   constexpr int KIB = 64 * KS, VIB = 64 * VS;        // bytes of the tile buffer one K / V piece covers
   constexpr int KBB = KU * KIB, VSB = VU * VIB;      // ... one K batch / one V step
   static_assert(KBB % VIB == 0 && 8 * KBB == NITV * VSB, "K batches and V steps tile the same buffer");
@@ -433,7 +463,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   if (tile0 * 64 >= n_list) return;
 
   // the lane's units of the G query vectors
-  QRegs<D, G, M, QBF> q;
+  QRegs<D, G, M, KT> q;
   {
     constexpr int qes = QBF ? 2 : 4;
     const char* qb = (const char*)a.q + (size_t)(b * a.Hq + kvh * G) * D * qes;
@@ -447,7 +477,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
 #pragma unroll
           for (int c = 0; c < EUK / 2; ++c) {
             q.qp[h][j][c] = ((const uint32_t*)src)[c];
-            if constexpr (GE::IS_Q) sacc += bf_lo(q.qp[h][j][c]) + bf_hi(q.qp[h][j][c]);
+            if constexpr (GE::IS_Q) sacc += H ? f16_lo(q.qp[h][j][c]) + f16_hi(q.qp[h][j][c]) : bf_lo(q.qp[h][j][c]) + bf_hi(q.qp[h][j][c]);
           }
         } else {
 #pragma unroll
@@ -579,7 +609,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
       for (int v = i * VPB; v < (i + 1) * VPB; ++v) issue_v_piece(v);
       if constexpr (i + 1 < 8) read_k(std::integral_constant<int, (i + 1 < 8 ? i + 1 : 7)>{}, kb[(i + 1) & 1]);
       float x[G];
-      row_logits<D, G, M, QBF>(kb[i & 1], q, ksc[i], x);
+      row_logits<D, G, M, KT>(kb[i & 1], q, ksc[i], x);
 #pragma unroll
       for (int h = 0; h < G; ++h) xt[h] = (r8 == i) ? x[h] : xt[h];   // lane 8*g8 + i keeps entry 8*g8 + i
     });
@@ -697,9 +727,9 @@ constexpr int waves_per_group(int row_bytes, int G) {
   return (row_bytes > 256 && waves_per_simd(G) * 4 > 4) ? 4 : waves_per_simd(G) * 4;
 }
 
-template <int D, int G, bool BF16>
+template <int D, int G, int KT>
 struct KernelGeo {
-  static constexpr Mode MF = BF16 ? F_BF16 : F_F32;
+  static constexpr Mode MF = KT == KT_BF16 ? F_BF16 : KT == KT_F16 ? F_F16 : F_F32;
   static constexpr int RB = Geo<D, MF>::RB;
   static constexpr int NW = waves_per_group(RB, G);
   static constexpr int EV = Geo<D, MF>::EV;
@@ -722,9 +752,9 @@ __host__ __device__ inline int q_waves(int nwv, int nft, int nqt) {
   return best;
 }
 
-template <int D, int G, bool BF16>
-__global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, BF16>::NW / 4)) void k_attn_tiered(const AttnArgs a) {
-  using KG = KernelGeo<D, G, BF16>;
+template <int D, int G, int KT>
+__global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT>::NW / 4)) void k_attn_tiered(const AttnArgs a) {
+  using KG = KernelGeo<D, G, KT>;
   constexpr int NW = KG::NW, EV = KG::EV, LPRV = KG::LPRV, GP = GPad<G>::v;
   constexpr int TILE_BYTES = 64 * KG::RB;
   static_assert(G * D * 4 <= TILE_BYTES, "a wave's output partial is parked in its tile buffer");
@@ -763,11 +793,11 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
   }
   bool o_written = false;
   if (u < nwf) {
-    attn_wave<D, G, KG::MF, BF16>(a, w, b, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
+    attn_wave<D, G, KG::MF, KT>(a, w, b, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
   } else {
     if constexpr (EV == 8) {
-      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
-      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
     } else {
       // binary32 rows use 4 elements per lane, code rows 8: separate accumulators, parked directly
       float o8[G][8];
@@ -775,8 +805,8 @@ __global__ __launch_bounds__((KernelGeo<D, G, BF16>::NW * 64), (KernelGeo<D, G, 
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o8[h][e] = 0.f;
-      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
-      else attn_wave<D, G, Q_INT4, BF16>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
       constexpr int L8 = D / 8;
 #pragma unroll
       for (int st = L8; st < 64; st <<= 1)
@@ -937,14 +967,15 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
       for (int g2 = 1; g2 < NSG; ++g2) tot += sm_pm[g2 * D + d];
       tot *= IL[hq];
       const size_t oi = ((size_t)b * a.Hq + hq) * D + d;
-      if (a.out_bf16) ((uint16_t*)a.out)[oi] = f32_to_bf16(tot);
+      if (a.out_kind == KT_BF16) ((uint16_t*)a.out)[oi] = f32_to_bf16(tot);
+      else if (a.out_kind == KT_F16) ((_Float16*)a.out)[oi] = (_Float16)tot;    // round to nearest even
       else ((float*)a.out)[oi] = tot;
     }
   }
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------------
-// The file is compiled once per part (TKV_ATTN_PART = 0..3: one (head_dim, KV dtype) pair of attn_tiered each,
+// The file is compiled once per part (TKV_ATTN_PART = 0..3, 5, 6: one (head_dim, KV dtype) pair of attn_tiered each,
 // 4: attn_finish and the launchers), so the parts build in parallel; without the macro it is one translation unit.
 // TKV_ATTN_ONLY_BF16_128 (kernel experiments) builds one unit with the bf16, head_dim 128 kernels alone.
 #if defined(TKV_ATTN_ONLY_BF16_128)
@@ -969,15 +1000,15 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   }
 
 // With a pair of events the launch is timed by the dispatch's own begin / end timestamps (no bracket overhead).
-template <int D, int G, bool BF16>
+template <int D, int G, int KT>
 static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   dim3 grid(a.S, a.Hkv, a.B);
-  constexpr int threads = KernelGeo<D, G, BF16>::NW * 64;
-  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
-  else hipLaunchKernelGGL((k_attn_tiered<D, G, BF16>), grid, dim3(threads), 0, st, a);
+  constexpr int threads = KernelGeo<D, G, KT>::NW * 64;
+  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
+  else hipLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, a);
   return hipGetLastError();
 }
-template <int D, bool BF16>
+template <int D, int KT>
 hipError_t tiered_by_group(const AttnArgs& a, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 #define TKV_DEFINE_PART(D_, BF_)                                                                                   \
   template <>                                                                                                      \
@@ -985,49 +1016,59 @@ hipError_t tiered_by_group(const AttnArgs& a, int G, hipStream_t st, hipEvent_t 
     TKV_DISPATCH_G(run_tiered, D_, BF_, a, st, ev0, ev1)                                                           \
   }
 #if TKV_HAS_PART(0)
-TKV_DEFINE_PART(128, true)
+TKV_DEFINE_PART(128, KT_BF16)
 #endif
 #if TKV_HAS_PART(1)
-TKV_DEFINE_PART(128, false)
+TKV_DEFINE_PART(128, KT_F32)
 #endif
 #if TKV_HAS_PART(2)
-TKV_DEFINE_PART(64, true)
+TKV_DEFINE_PART(64, KT_BF16)
 #endif
 #if TKV_HAS_PART(3)
-TKV_DEFINE_PART(64, false)
+TKV_DEFINE_PART(64, KT_F32)
+#endif
+#if TKV_HAS_PART(5)
+TKV_DEFINE_PART(128, KT_F16)
+#endif
+#if TKV_HAS_PART(6)
+TKV_DEFINE_PART(64, KT_F16)
 #endif
 
 #if TKV_HAS_PART(4)
 #if defined(TKV_ATTN_ONLY_BF16_128)
-template <int D, bool BF16>
+template <int D, int KT>
 hipError_t tiered_by_group(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipErrorInvalidValue; }
 #else
-template <> hipError_t tiered_by_group<128, true>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
-template <> hipError_t tiered_by_group<128, false>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
-template <> hipError_t tiered_by_group<64, true>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
-template <> hipError_t tiered_by_group<64, false>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<128, KT_BF16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<128, KT_F32>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<128, KT_F16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<64, KT_BF16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<64, KT_F32>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
+template <> hipError_t tiered_by_group<64, KT_F16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
 #endif
 
-template <int D, int G, bool BF16>
+template <int D, int G, int KT>
 static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
   const int tiles = a.n_tiles;
   hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, a, tiles);
   return hipGetLastError();
 }
 
-hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  if (D == 128 && bf16) return tiered_by_group<128, true>(a, G, st, ev0, ev1);
-  if (D == 128 && !bf16) return tiered_by_group<128, false>(a, G, st, ev0, ev1);
-  if (D == 64 && bf16) return tiered_by_group<64, true>(a, G, st, ev0, ev1);
-  if (D == 64 && !bf16) return tiered_by_group<64, false>(a, G, st, ev0, ev1);
+hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (D == 128 && kt == KT_BF16) return tiered_by_group<128, KT_BF16>(a, G, st, ev0, ev1);
+  if (D == 128 && kt == KT_F32) return tiered_by_group<128, KT_F32>(a, G, st, ev0, ev1);
+  if (D == 128 && kt == KT_F16) return tiered_by_group<128, KT_F16>(a, G, st, ev0, ev1);
+  if (D == 64 && kt == KT_BF16) return tiered_by_group<64, KT_BF16>(a, G, st, ev0, ev1);
+  if (D == 64 && kt == KT_F32) return tiered_by_group<64, KT_F32>(a, G, st, ev0, ev1);
+  if (D == 64 && kt == KT_F16) return tiered_by_group<64, KT_F16>(a, G, st, ev0, ev1);
   return hipErrorInvalidValue;
 }
-int attn_waves_per_group(int D, bool bf16, int G) { return waves_per_group(D * (bf16 ? 2 : 4), G); }
+int attn_waves_per_group(int D, int elem_bytes, int G) { return waves_per_group(D * elem_bytes, G); }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
 
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {
-  if (D == 128) { TKV_DISPATCH_G(run_finish, 128, true, a, st) }
-  if (D == 64) { TKV_DISPATCH_G(run_finish, 64, true, a, st) }
+  if (D == 128) { TKV_DISPATCH_G(run_finish, 128, KT_BF16, a, st) }
+  if (D == 64) { TKV_DISPATCH_G(run_finish, 64, KT_BF16, a, st) }
   return hipErrorInvalidValue;
 }
 #endif

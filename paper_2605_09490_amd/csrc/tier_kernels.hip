@@ -7,6 +7,7 @@
 namespace tkv {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
 struct Ppm { uint32_t f[4]; uint32_t rule; };
 
@@ -445,8 +446,17 @@ __global__ void k_move_copy(DevView v, int layer0) {
 }
 
 // 8 consecutive elements of a stored row as binary32
-__device__ __forceinline__ void load8(const char* row, int e0, int es, float (&x)[8]) {
-  if (es == 4) {
+__device__ __forceinline__ void load8(const char* row, int e0, int kt, float (&x)[8]) {
+  if (kt == 2) {
+    const u32x4 w = *(const u32x4*)(row + (size_t)e0 * 2);
+    const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const f16x2 h = __builtin_bit_cast(f16x2, u[c]);
+      x[2 * c] = (float)h.x;
+      x[2 * c + 1] = (float)h.y;
+    }
+  } else if (kt == 0) {
     const float4 a = *(const float4*)(row + (size_t)e0 * 4), b = *(const float4*)(row + (size_t)e0 * 4 + 16);
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
   } else {
@@ -464,8 +474,20 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
 }
-__device__ __forceinline__ void store8(char* row, int e0, int es, const float (&x)[8]) {
-  if (es == 4) {
+__device__ __forceinline__ void store8(char* row, int e0, int kt, const float (&x)[8]) {
+  if (kt == 2) {
+    u32x4 w;
+    uint32_t u[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      f16x2 h;
+      h.x = (_Float16)x[2 * c];          // round to nearest even
+      h.y = (_Float16)x[2 * c + 1];
+      u[c] = __builtin_bit_cast(uint32_t, h);
+    }
+    w.x = u[0]; w.y = u[1]; w.z = u[2]; w.w = u[3];
+    *(u32x4*)(row + (size_t)e0 * 2) = w;
+  } else if (kt == 0) {
     *(float4*)(row + (size_t)e0 * 4) = make_float4(x[0], x[1], x[2], x[3]);
     *(float4*)(row + (size_t)e0 * 4 + 16) = make_float4(x[4], x[5], x[6], x[7]);
   } else {
@@ -490,7 +512,7 @@ __global__ __launch_bounds__(256) void k_move_quant(DevView v, int layer0) {
   if (act) { src = v.mvq_src[(size_t)b * v.Nmax + j]; dst = v.mvq_dst[(size_t)b * v.Nmax + j]; }
   const bool ok = act && src >= 0 && src < v.capF && dst >= 0 && dst < v.cap2;
   float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (ok) load8(fp_ptr(v, which, layer, b, kvh, src), r * 8, v.es, x);
+  if (ok) load8(fp_ptr(v, which, layer, b, kvh, src), r * 8, v.kt, x);
   float a = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(x[e]));
@@ -557,7 +579,7 @@ __global__ __launch_bounds__(256) void k_move_dequant(DevView v) {
       x[e] = (float)c * sc;
     }
   }
-  store8(fp_ptr(v, which, layer, b, kvh, dst), r * 8, v.es, x);
+  store8(fp_ptr(v, which, layer, b, kvh, dst), r * 8, v.kt, x);
 }
 
 hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st) {

@@ -35,7 +35,7 @@ struct tkv_cache {
   std::string err;
   std::vector<void*> dev_allocs, pin_allocs;
   int G = 0, es = 0;
-  bool bf16 = false;
+  int kt = 0;                      // kv_dtype: 0 binary32, 1 bfloat16, 2 binary16
   float score_scale = 0.f, softmax_scale = 0.f;
   // host mirrors
   std::vector<int> len;            // tokens appended per layer
@@ -364,8 +364,8 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   if (cfg->n_q_heads > 128) return bad("tkv_create: n_q_heads must be <= 128");
   if (cfg->head_dim != 64 && cfg->head_dim != 128) return bad("tkv_create: head_dim must be 64 or 128");
   if (cfg->max_tokens < 1 || cfg->max_tokens >= (1 << 24)) return bad("tkv_create: max_tokens must be in [1, 2^24)");
-  if (cfg->kv_dtype != TKV_F32 && cfg->kv_dtype != TKV_BF16) return bad("tkv_create: kv_dtype");
-  if (cfg->out_dtype != TKV_F32 && cfg->out_dtype != TKV_BF16) return bad("tkv_create: out_dtype");
+  if (cfg->kv_dtype < TKV_F32 || cfg->kv_dtype > TKV_F16) return bad("tkv_create: kv_dtype");
+  if (cfg->out_dtype < TKV_F32 || cfg->out_dtype > TKV_F16) return bad("tkv_create: out_dtype");
   if (cfg->t2_format != TKV_T2_INT8_ROW && cfg->t2_format != TKV_T2_INT4_G32) return bad("tkv_create: t2_format");
   if (cfg->n_prompt < 0 || cfg->k_sink < 0 || cfg->k_window < 0) return bad("tkv_create: protected sizes must be >= 0");
   if (cfg->t0_rows < 0 || cfg->staging_rows < 0 || cfg->t2_rows < 0 || cfg->host_rows < 0 || cfg->bounce_bytes < 0)
@@ -378,8 +378,8 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   tkv_cache* c = new tkv_cache();
   c->cfg = *cfg;
   c->G = G;
-  c->bf16 = cfg->kv_dtype == TKV_BF16;
-  c->es = c->bf16 ? 2 : 4;
+  c->kt = cfg->kv_dtype;
+  c->es = c->kt == TKV_F32 ? 4 : 2;
   c->score_scale = cfg->score_scale > 0.f ? cfg->score_scale : 1.0f / ((float)cfg->n_layers * (float)cfg->n_q_heads);
   c->softmax_scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
   auto die = [&](tkv_status s, const char* m) {
@@ -400,6 +400,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   v.streamed = c->streamed ? 1 : 0;
   v.capP = c->streamed ? v.cap0 : v.capF;
   v.es = c->es;
+  v.kt = c->kt;
   v.t2fmt = cfg->t2_format;
   v.cb = cfg->t2_format == TKV_T2_INT8_ROW ? D : D / 2;
   v.sb = cfg->t2_format == TKV_T2_INT8_ROW ? 4 : (D / 32) * 2;
@@ -578,7 +579,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   }
   if (n_tiles * TOK_PER_BLOCK > c->xs_stride) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal tile count %d exceeds the scratch", n_tiles);
   // no more workgroups per pair than there are tiles for their waves
-  const int nw = attn_waves_per_group(v.D, c->bf16, c->G);
+  const int nw = attn_waves_per_group(v.D, c->es, c->G);
   const int S = std::max(1, std::min(c->S_alloc, (n_tiles - n_tiles_s + nw - 1) / nw));
   const int S2 = n_tiles_s > 0 ? std::max(1, std::min(c->S_alloc, (n_tiles_s + nw - 1) / nw)) : 0;
   AttnArgs a{};
@@ -596,7 +597,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
       a.nWq[b] = attn_q_waves(S * nw, tiles(c->nF[b]), tiles(c->nQ[b]));
     }
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capP; a.cap2 = v.cap2;
-  a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_bf16 = c->cfg.out_dtype == TKV_BF16;
+  a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_kind = c->cfg.out_dtype;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
@@ -612,7 +613,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
       pe = &c->prof_events[i0];        // the pool may have grown
     }
   }
-  HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->bf16, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
+  HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->kt, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
   if (S2 > 0) {
     // streamed T1: the same kernel over the T1 list, rows in the frame; its splits follow the first launch's
     AttnArgs a2 = a;
@@ -624,7 +625,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
         a2.xs_base[b] = tiles(c->nF[b]) + tiles(c->nQ[b]);
         a2.nF[b] = c->nS[b]; a2.nQ[b] = 0; a2.nWq[b] = 0;
       }
-    HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->bf16, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
+    HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->kt, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
   if (c->streamed && S2 > 0) {
@@ -649,7 +650,7 @@ tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, c
   const DevView& v = c->dv;
   const size_t kv_stride = (size_t)v.B * v.Hkv * v.D * v.es;
   const size_t q_stride = (size_t)v.B * v.Hq * v.D * v.es;
-  const size_t o_stride = (size_t)v.B * v.Hq * v.D * (c->cfg.out_dtype == TKV_BF16 ? 2 : 4);
+  const size_t o_stride = (size_t)v.B * v.Hq * v.D * (c->cfg.out_dtype == TKV_F32 ? 4 : 2);
   // all layers are at the same length here, so the new token's rows of every layer go in with one launch
   const int n = common_length(c);
   if (n >= 0 && n == c->n_assigned && !c->plan_pending) {

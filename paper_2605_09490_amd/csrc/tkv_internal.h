@@ -36,6 +36,7 @@ struct DevView {
   int cap0, cap1, cap2;     // slots per (layer, seq, kv head): HBM pool, staging buffer, compressed pool
   int capF;                 // cap0 + cap1: one slot space, staging slots are cap0 .. capF-1
   int es;                   // bytes per K/V element
+  int kt;                   // 0 binary32, 1 bfloat16, 2 binary16
   int t2fmt;                // 0 int8 row, 1 int4 g32
   int cb, sb;               // bytes of codes / of scales per T2 row
   int n_prompt, k_sink, k_window;
@@ -93,7 +94,7 @@ struct AttnArgs {
   int second;       // != 0: that second launch; its list lengths are nS, its logits follow the first launch's tiles
   const int* s_pos; // [B][Nmax] positions of the T1 list (streamed T1), for the finishing kernel
   int n_tiles;      // max over the sequences of F tiles + Q tiles (+ T1 tiles)
-  int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_bf16, q_es;
+  int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_kind, q_es;   // out_kind: 0 binary32, 1 bfloat16, 2 binary16
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
   int nWq[ATTN_ARG_SEQS];                     // waves of each (sequence, kv head) pair that serve the Q list (same condition)
@@ -102,9 +103,10 @@ struct AttnArgs {
 };
 
 // launchers (defined in the .hip files)
-hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, bool bf16, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+// kt: type of K, V and q (0 binary32, 1 bfloat16, 2 binary16)
+hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
-int attn_waves_per_group(int D, bool bf16, int G);   // waves per attention workgroup (one workgroup per compute unit)
+int attn_waves_per_group(int D, int elem_bytes, int G);   // waves per attention workgroup (one workgroup per compute unit)
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles);   // how many of a pair's waves serve the Q list
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);

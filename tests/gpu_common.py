@@ -7,7 +7,7 @@ import paper_2605_09490_amd as tkv
 from oracle import tkv_oracle as O
 from tkv_synth import Workload
 
-TOL_OUT = {"bf16": 2e-3, "f32": 1e-5}
+TOL_OUT = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-5}
 TOL_SCORE_REL = 1e-4
 
 

@@ -27,6 +27,8 @@ def _mass(cfg, calls):
     ("f32", 64, 8, 2, 512),      # group 4, the tiny config's shape
     ("f32", 128, 4, 4, 130),     # group 1, ragged
     ("bf16", 128, 10, 2, 700),   # group 5 (14B/32B shape), several splits + tail
+    ("f16", 128, 10, 2, 700),    # binary16 rows and queries (the paper's own KV type)
+    ("f16", 64, 8, 2, 333),
     ("bf16", 128, 14, 2, 257),   # group 7 (7B shape), one entry past a split boundary
     ("bf16", 64, 16, 2, 256),    # group 8, exactly one split
     ("bf16", 128, 6, 2, 1),      # single token
@@ -66,6 +68,16 @@ def test_bf16_output_rounding():
     assert o16.dtype == torch.bfloat16
     assert torch.equal(o32.to(torch.bfloat16), o16)
     a.close(); b.close()
+    # the same for binary16 rows with a binary16 output
+    cfg = small_config(n_layers=1, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="f16", context=333,
+                       decode_steps=0)
+    a, b = Pair(cfg), Pair(cfg, out_dtype="f16")
+    q = a.wl.step_q(0, 0)
+    o32 = a.gpu.attend_and_score(0, q)
+    o16 = b.gpu.attend_and_score(0, q)
+    assert o16.dtype == torch.float16
+    assert torch.equal(o32.to(torch.float16), o16)
+    a.close(); b.close()
 
 
 def _random_tiers(rng, B, n, frac=(0.4, 0.3, 0.2, 0.1), protect=(4, 16)):
@@ -78,6 +90,8 @@ def _random_tiers(rng, B, n, frac=(0.4, 0.3, 0.2, 0.1), protect=(4, 16)):
 @pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,t2", [
     ("f32", 64, 8, 2, "int8_row"),
     ("bf16", 128, 10, 2, "int8_row"),
+    ("f16", 128, 10, 2, "int8_row"),
+    ("f16", 64, 6, 2, "int4_g32"),
     ("bf16", 128, 14, 2, "int4_g32"),
     ("bf16", 64, 8, 2, "int4_g32"),
     ("f32", 128, 8, 2, "int4_g32"),
@@ -152,7 +166,7 @@ def test_forced_tiers_attention_codes_and_lists(kv_dtype, D, Hq, Hkv, t2, mode):
 
 
 @pytest.mark.parametrize("mode", ["wait", "lazy"])
-@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv", [("bf16", 128, 10, 2), ("f32", 64, 8, 2)])
+@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv", [("bf16", 128, 10, 2), ("f32", 64, 8, 2), ("f16", 128, 10, 2)])
 def test_prop1_t1_placement_is_bit_invisible(mode, kv_dtype, D, Hq, Hkv):
     """Zero-error offloading: the run with rows in T1 (round trip through pinned host memory and the
     staging buffer) gives the same bits as the run with those rows left in T0 -- outputs and scores."""
@@ -230,6 +244,7 @@ def test_rows_returning_to_t1_reuse_their_host_copy(mode):
 
 @pytest.mark.parametrize("mode,kv_dtype,D,Hq,Hkv,t2", [
     ("lazy", "bf16", 128, 10, 2, "int8_row"),
+    ("lazy", "f16", 128, 10, 2, "int4_g32"),
     ("wait", "bf16", 128, 10, 2, "int4_g32"),
     ("lazy", "f32", 64, 8, 2, "int8_row"),
 ])
@@ -255,6 +270,7 @@ def test_pinned_store_is_rewritten_when_it_runs_out(mode, layers):
 
 @pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,t2,layers", [
     ("bf16", 128, 10, 2, "int8_row", 5),
+    ("f16", 128, 10, 2, "int8_row", 3),
     ("f32", 64, 8, 2, "int4_g32", 2),
     ("bf16", 64, 3, 3, "int8_row", 1),
 ])
@@ -297,6 +313,8 @@ def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False
                     row = p.gpu.get_row(cfg.n_layers - 1, 1, 1, int(pos), which)
                     if kv_dtype == "bf16":
                         row = (row.astype(np.uint32) << 16).view(np.float32)
+                    elif kv_dtype == "f16":
+                        row = row.view(np.float16)
                     assert np.array_equal(row.astype(np.float64), store[cfg.n_layers - 1][1, 1, int(pos)]), (rnd, t, pos, which)
         for l in range(cfg.n_layers):
             k, v = p.wl.step_kv(rnd, l)

@@ -242,6 +242,13 @@ def test_promotion_value_is_binary32_product_rounded_to_storage():
     assert np.array_equal(got, want)
     got32 = O.t2_decode_to_storage(codes, scale, "int8_row", "f32")
     assert np.array_equal(got32, codes.astype(np.float32) * scale)
+    got16 = O.t2_decode_to_storage(codes, scale, "int8_row", "f16")
+    want16 = torch.from_numpy(codes.astype(np.float32) * scale).to(torch.float16).to(torch.float32).numpy()
+    assert np.array_equal(got16, want16)
+    # binary16 rounding: ties to even, by hand (1 + 2^-11 is halfway between 1 and 1 + 2^-10; 1 + 3*2^-11 between
+    # 1 + 2^-10 and 1 + 2^-9), and the largest finite value
+    x = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 65504.0, 2.0 ** -25], np.float32)
+    assert np.array_equal(O.round_to_storage(x, "f16"), np.array([1.0, 1.0 + 2.0 ** -9, 65504.0, 0.0], np.float32))
 
 
 # ---------------------------------------------------------------- tier sizes and ranking

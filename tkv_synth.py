@@ -13,7 +13,7 @@ available offline):
   c = exp(sigma * z), z ~ N(0, 1), shared by all layers and kv heads, and
   K <- c * K; optionally a random `boost_frac` of positions gets K <- boost * K
   (late-referenced intermediate results).  Queries ~ N(0, 1) fresh per
-  (step, layer).  All values are rounded to the KV dtype (bf16 or fp32).
+  (step, layer).  All values are rounded to the KV dtype (bf16, fp16 or fp32).
 """
 from __future__ import annotations
 
@@ -30,7 +30,7 @@ class WorkloadConfig:
     n_q_heads: int
     n_kv_heads: int
     head_dim: int
-    kv_dtype: str            # "f32" | "bf16"
+    kv_dtype: str            # "f32" | "bf16" | "f16"
     context: int             # tokens preloaded before the first decode step
     decode_steps: int
     reclassify_every: int    # Delta
@@ -51,7 +51,7 @@ class WorkloadConfig:
 
     @property
     def torch_dtype(self):
-        return torch.float32 if self.kv_dtype == "f32" else torch.bfloat16
+        return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.kv_dtype]
 
 
 CONFIGS = {
