@@ -34,7 +34,7 @@ def log(*a):
 def call_bytes(cfg, n_full, n_t2, out_es=4):
     """Algorithmic bytes of one layer call: every live row once (K and V), q and out, score read-modify-write.
     n_full, n_t2 are position counts summed over the batch."""
-    es = 2 if cfg.kv_dtype == "bf16" else 4
+    es = 4 if cfg.kv_dtype == "f32" else 2
     D, Hkv, Hq, B = cfg.head_dim, cfg.n_kv_heads, cfg.n_q_heads, cfg.batch
     t2_row = (D + 4) if cfg.t2_format == "int8_row" else (D // 2 + (D // 32) * 2)
     kv = Hkv * (n_full * 2 * D * es + n_t2 * 2 * t2_row)
@@ -218,6 +218,7 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
+    ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "f16", "f32"], help="K, V and query type (default: the workload's own)")
     ap.add_argument("--delta", type=int, default=0, help="re-tier every DELTA steps (default: the workload's own)")
     ap.add_argument("--k-window", type=int, default=-1, help="protected recent window (default: the workload's own)")
     ap.add_argument("--count-rule", default="total", choices=["total", "alg1"],
@@ -236,6 +237,7 @@ def main():
     warmup = max(args.warmup, 1)
     cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps,
                               reclassify_every=args.delta or base.reclassify_every,
+                              kv_dtype=args.kv_dtype or base.kv_dtype,
                               k_window=base.k_window if args.k_window < 0 else args.k_window)
     rule = 1 if args.count_rule == "alg1" else 0
     pol = cfg.policy_ppm
@@ -286,7 +288,7 @@ def main():
         "metric": "tiered decode-attn KV GB/s & % of HBM peak; T1 prefetch overhead % of step",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": warmup,
         "ms_per_step": round(main_res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16" if cfg.kv_dtype == "bf16" else "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": cfg.kv_dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}-shaped: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d {cfg.head_dim}, "
                                f"{cfg.kv_dtype} KV, batch {cfg.batch}, {cfg.context}-token context, tiers ppm {list(pol)}, "
                                f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"
