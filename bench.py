@@ -215,7 +215,10 @@ def main():
     ap.add_argument("--mode", default="lazy", choices=["lazy", "wait", "stream"],
                     help="T1 transport: lazy / wait keep all of T1 staged in HBM (differential prefetch); stream keeps two "
                          "layer-sized frames and moves T1 over the link at every step")
-    ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--profile-steps", type=int, default=-1,
+                    help="extra decode steps, after the timed ones, in which every attention launch is timed by HIP events "
+                         "(default: one re-tiering period, so the window holds the same mix of steps right after an event "
+                         "and steady ones as the timed region)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
     ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "f16", "f32"], help="K, V and query type (default: the workload's own)")
@@ -235,6 +238,8 @@ def main():
     probe = link_probe()     # before the caches exist: the largest workload leaves little pinned memory to spare
     base = CONFIGS[args.workload]
     warmup = max(args.warmup, 1)
+    if args.profile_steps < 0:
+        args.profile_steps = args.delta or base.reclassify_every
     cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps,
                               reclassify_every=args.delta or base.reclassify_every,
                               kv_dtype=args.kv_dtype or base.kv_dtype,

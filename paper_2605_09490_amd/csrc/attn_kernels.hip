@@ -766,15 +766,16 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
   const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
   int nF, nQ, xsb = 0;
-  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; if (a.second) xsb = a.xs_base[b]; }
-  else if (!a.second) { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
-  else {
+  if (!a.second) {
+    if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+    else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  } else {
     nF = a.cnt[b * CNT_N + C_NS]; nQ = 0;
     xsb = ((a.cnt[b * CNT_N + C_NF] + 63) >> 6) + ((a.cnt[b * CNT_N + C_NQ] + 63) >> 6);
   }
   const int nft = (nF + 63) >> 6, nqt = (nQ + 63) >> 6;
   const int nwv = a.S * NW;
-  const int nwq = (a.B <= ATTN_ARG_SEQS) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
+  const int nwq = a.second ? 0 : (a.B <= ATTN_ARG_SEQS) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
   const int u = s * NW + wave;
 
   WaveLds w;
@@ -882,8 +883,9 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   __shared__ float M[128], IL[128];
   const int t = threadIdx.x, b = blockIdx.y;
   int nF, nQ, nS;
-  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; nS = a.nS[b]; }
-  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; nS = a.s_pos ? a.cnt[b * CNT_N + C_NS] : 0; }
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  nS = a.s_pos ? a.cnt[b * CNT_N + C_NS] : 0;
   // logits columns: F tiles, Q tiles, then (streamed T1) the T1 list's tiles
   const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = a.S_total;
   const bool is_tile = (int)blockIdx.x < n_tiles;
@@ -895,10 +897,11 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   int pos = -1;
   float x0[G], score_old = 0.f;
   if (is_tile) {
-    if (j < nF) pos = a.f_pos[(size_t)b * a.Nmax + j];
-    else if (j >= cf * TB && j - cf * TB < nQ) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
-    else if (j >= (cf + cq) * TB && j - (cf + cq) * TB < nS) pos = a.s_pos[(size_t)b * a.Nmax + (j - (cf + cq) * TB)];
-    const bool live = pos >= 0;
+    const bool in_f = j < nF, in_q = j >= cf * TB && j - cf * TB < nQ, in_s = j >= (cf + cq) * TB && j - (cf + cq) * TB < nS;
+    const bool live = in_f || in_q || in_s;      // from the list lengths alone: the logits are fetched beside the position
+    if (in_f) pos = a.f_pos[(size_t)b * a.Nmax + j];
+    else if (in_q) pos = a.q_pos[(size_t)b * a.Nmax + (j - cf * TB)];
+    else if (in_s) pos = a.s_pos[(size_t)b * a.Nmax + (j - (cf + cq) * TB)];
 #pragma unroll
     for (int g = 0; g < G; ++g) x0[g] = (live && hg < a.Hkv) ? a.xs[((size_t)b * a.Hq + hg * G + g) * a.xs_stride + j] : 0.f;
     if (hg == 0 && pos >= 0) score_old = a.score[(size_t)b * a.Nmax + pos];

@@ -420,10 +420,14 @@ hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st) {
 
 // ---- row movers ------------------------------------------------------------------------------------------------
 // a row of the unified F slot space: HBM pool, or (streamed T1, staging slots) the frame that holds the layer's T1 rows
+// (STREAMED is a template argument so that the resident modes keep one wave-uniform base pointer per access)
+template <bool STREAMED>
 __device__ __forceinline__ char* fp_ptr(const DevView& v, int which, int layer, int b, int kvh, int slot) {
   const size_t rb = (size_t)(v.D * v.es);
-  if (v.streamed && slot >= v.cap0)
-    return (which ? v.frV : v.frK) + (((size_t)b * v.Hkv + kvh) * v.cap1 + (slot - v.cap0)) * rb;
+  if constexpr (STREAMED) {
+    if (slot >= v.cap0)
+      return (which ? v.frV : v.frK) + (((size_t)b * v.Hkv + kvh) * v.cap1 + (slot - v.cap0)) * rb;
+  }
   return (which ? v.fpV : v.fpK) + ((((size_t)layer * v.B + b) * v.Hkv + kvh) * v.capP + slot) * rb;
 }
 __device__ __forceinline__ size_t t2_row(const DevView& v, int layer, int b, int kvh, int slot) {
@@ -432,6 +436,7 @@ __device__ __forceinline__ size_t t2_row(const DevView& v, int layer, int b, int
 
 // Copies inside the F slot space, bits preserved: T1 -> T0 (staging slot -> HBM slot) and T0 -> T1 of rows whose host
 // copy is still valid (HBM slot -> staging slot).  grid (pieces, Hkv*2, L*B)
+template <bool STREAMED>
 __global__ void k_move_copy(DevView v, int layer0) {
   const int lb = blockIdx.z, layer = layer0 + lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
@@ -442,7 +447,7 @@ __global__ void k_move_copy(DevView v, int layer0) {
   if (j >= n) return;
   const int src = v.mv10_src[(size_t)b * v.Nmax + j], dst = v.mv10_dst[(size_t)b * v.Nmax + j];
   if (src < 0 || src >= v.capF || dst < 0 || dst >= v.capF) return;
-  *(u32x4*)(fp_ptr(v, which, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(fp_ptr(v, which, layer, b, kvh, src) + c * 16);
+  *(u32x4*)(fp_ptr<STREAMED>(v, which, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(fp_ptr<STREAMED>(v, which, layer, b, kvh, src) + c * 16);
 }
 
 // 8 consecutive elements of a stored row as binary32
@@ -500,6 +505,7 @@ __device__ __forceinline__ void store8(char* row, int e0, int kt, const float (&
 
 // -> T2: encode the current stored row.  D/8 lanes per row (8 elements each), 64/(D/8) rows per wave.
 // grid (pieces, Hkv*2, L*B).  All arithmetic in binary32, round-to-nearest-even, true division.
+template <bool STREAMED>
 __global__ __launch_bounds__(256) void k_move_quant(DevView v, int layer0) {
   const int lb = blockIdx.z, layer = layer0 + lb / v.B, b = lb % v.B;
   const int kvh = blockIdx.y >> 1, which = blockIdx.y & 1;
@@ -512,7 +518,7 @@ __global__ __launch_bounds__(256) void k_move_quant(DevView v, int layer0) {
   if (act) { src = v.mvq_src[(size_t)b * v.Nmax + j]; dst = v.mvq_dst[(size_t)b * v.Nmax + j]; }
   const bool ok = act && src >= 0 && src < v.capF && dst >= 0 && dst < v.cap2;
   float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (ok) load8(fp_ptr(v, which, layer, b, kvh, src), r * 8, v.kt, x);
+  if (ok) load8(fp_ptr<STREAMED>(v, which, layer, b, kvh, src), r * 8, v.kt, x);
   float a = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(x[e]));
@@ -579,7 +585,7 @@ __global__ __launch_bounds__(256) void k_move_dequant(DevView v) {
       x[e] = (float)c * sc;
     }
   }
-  store8(fp_ptr(v, which, layer, b, kvh, dst), r * 8, v.kt, x);
+  store8(fp_ptr<false>(v, which, layer, b, kvh, dst), r * 8, v.kt, x);     // decoded rows always land in the HBM pool
 }
 
 hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStream_t st) {
@@ -588,9 +594,9 @@ hipError_t launch_moves(const DevView& v, int max10, int maxq, int maxd, hipStre
   if (maxd > 0)
     hipLaunchKernelGGL(k_move_dequant, dim3((maxd + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v);
   if (max10 > 0)
-    hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v, 0);
+    hipLaunchKernelGGL(k_move_copy<false>, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v, 0);
   if (maxq > 0)
-    hipLaunchKernelGGL(k_move_quant, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v, 0);
+    hipLaunchKernelGGL(k_move_quant<false>, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.L * v.B), dim3(256), 0, st, v, 0);
   return hipGetLastError();
 }
 hipError_t launch_decode_moves(const DevView& v, int maxd, hipStream_t st) {
@@ -603,9 +609,9 @@ hipError_t launch_moves_layer(const DevView& v, int layer, int max10, int maxq, 
   const int cpr = v.D * v.es / 16;
   const int rpb = 4 * (64 / (v.D / 8));
   if (max10 > 0)
-    hipLaunchKernelGGL(k_move_copy, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.B), dim3(256), 0, st, v, layer);
+    hipLaunchKernelGGL(k_move_copy<true>, dim3((max10 * cpr + 255) / 256, v.Hkv * 2, v.B), dim3(256), 0, st, v, layer);
   if (maxq > 0)
-    hipLaunchKernelGGL(k_move_quant, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.B), dim3(256), 0, st, v, layer);
+    hipLaunchKernelGGL(k_move_quant<true>, dim3((maxq + rpb - 1) / rpb, v.Hkv * 2, v.B), dim3(256), 0, st, v, layer);
   return hipGetLastError();
 }
 // streamed T1: the positions that left T1 in the plan just committed give up their entry in the host-row table
@@ -626,6 +632,7 @@ hipError_t launch_clear_host_rows(const DevView& v, int max_leaving, hipStream_t
 
 // T0 -> T1, device side of the offload: pack rows [r0, r0+nrows) of this migrate's host-row order into a
 // contiguous bounce piece laid out [row][kv head][K|V][D]; the D2H copy then lands them in the pinned store.
+template <bool STREAMED>
 __global__ void k_gather(DevView v, int layer, int r0, int nrows, char* __restrict__ bounce) {
   const int row_bytes = v.D * v.es, cpr = row_bytes / 16;
   const long long total = (long long)nrows * v.Hkv * 2 * cpr;
@@ -638,7 +645,7 @@ __global__ void k_gather(DevView v, int layer, int r0, int nrows, char* __restri
   const int row = (int)(r / v.Hkv);
   const int b = v.g_seq[r0 + row], src = v.g_src[r0 + row];
   if (b < 0 || b >= v.B || src < 0 || src >= v.capF) return;
-  *(u32x4*)(bounce + (size_t)i * 16) = *(const u32x4*)(fp_ptr(v, which, layer, b, kvh, src) + c * 16);
+  *(u32x4*)(bounce + (size_t)i * 16) = *(const u32x4*)(fp_ptr<STREAMED>(v, which, layer, b, kvh, src) + c * 16);
 }
 // staging side of the prefetch: unpack a bounce piece (same layout) into the rows' staging slots
 __global__ void k_scatter(DevView v, int layer, int r0, int nrows, const char* __restrict__ bounce) {
@@ -653,7 +660,7 @@ __global__ void k_scatter(DevView v, int layer, int r0, int nrows, const char* _
   const int row = (int)(r / v.Hkv);
   const int b = v.g_seq[r0 + row], dst = v.g_dst[r0 + row];
   if (b < 0 || b >= v.B || dst < 0 || dst >= v.capF) return;
-  *(u32x4*)(fp_ptr(v, which, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
+  *(u32x4*)(fp_ptr<false>(v, which, layer, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
 }
 // streamed T1: unpack rows [r0, r0+nrows) of the pinned store's row order (one layer's copy of them, same piece
 // layout) into the frame; rows whose position is not in T1 any more are skipped
@@ -669,7 +676,7 @@ __global__ void k_scatter_frame(DevView v, int r0, int nrows, const char* __rest
   const int row = (int)(r / v.Hkv);
   const int b = v.h_seq[r0 + row], dst = v.h_dst[r0 + row];
   if (b < 0 || b >= v.B || dst < v.cap0 || dst >= v.capF) return;
-  *(u32x4*)(fp_ptr(v, which, 0, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
+  *(u32x4*)(fp_ptr<true>(v, which, 0, b, kvh, dst) + c * 16) = *(const u32x4*)(bounce + (size_t)i * 16);
 }
 hipError_t launch_scatter_frame(const DevView& v, int r0, int nrows, const char* bounce, hipStream_t st) {
   const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);
@@ -729,7 +736,8 @@ hipError_t launch_rebuild_htable(const DevView& v, int n, int rows, hipStream_t 
 
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st) {
   const long long total = (long long)nrows * v.Hkv * 2 * (v.D * v.es / 16);
-  hipLaunchKernelGGL(k_gather, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, layer, r0, nrows, bounce);
+  if (v.streamed) hipLaunchKernelGGL(k_gather<true>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, layer, r0, nrows, bounce);
+  else hipLaunchKernelGGL(k_gather<false>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, layer, r0, nrows, bounce);
   return hipGetLastError();
 }
 hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st) {

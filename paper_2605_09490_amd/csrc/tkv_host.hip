@@ -430,7 +430,9 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess || cus <= 0) cus = 256;
     c->S_alloc = std::max(1, cus / std::max(1, B * Hkv));
   }
-  c->xs_stride = (N / TOK_PER_BLOCK + 3) * TOK_PER_BLOCK;   // every list may end in a partly filled tile
+  // every list may end in a partly filled tile; an odd number of 256-byte tiles per row keeps the rows of the heads
+  // of one tile from falling on the same memory channels
+  c->xs_stride = ((N / TOK_PER_BLOCK + (cfg->prefetch_mode == TKV_PREFETCH_STREAM ? 3 : 2)) | 1) * TOK_PER_BLOCK;
   ok = ok && dalloc(c, c->xs, (size_t)B * v.Hq * c->xs_stride);
   const int launches = c->streamed ? 2 : 1;   // streamed T1: a second attention launch serves the frame
   ok = ok && dalloc(c, c->part_ml, (size_t)B * Hkv * c->S_alloc * launches * 2 * G);
@@ -593,7 +595,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   a.q_es = c->es;
   if (v.B <= ATTN_ARG_SEQS)
     for (int b = 0; b < v.B; ++b) {
-      a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b]; a.nS[b] = c->nS[b];
+      a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b];
       a.nWq[b] = attn_q_waves(S * nw, tiles(c->nF[b]), tiles(c->nQ[b]));
     }
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capP; a.cap2 = v.cap2;
@@ -620,11 +622,6 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
     a2.fpK = c->frameK[fr]; a2.fpV = c->frameV[fr]; a2.capF = v.cap1;
     a2.f_loc = v.s_loc; a2.f_pos = v.s_pos;
     a2.S = S2; a2.s0 = S; a2.second = 1;
-    if (v.B <= ATTN_ARG_SEQS)
-      for (int b = 0; b < v.B; ++b) {
-        a2.xs_base[b] = tiles(c->nF[b]) + tiles(c->nQ[b]);
-        a2.nF[b] = c->nS[b]; a2.nQ[b] = 0; a2.nWq[b] = 0;
-      }
     HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->kt, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));

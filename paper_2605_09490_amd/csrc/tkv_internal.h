@@ -98,8 +98,8 @@ struct AttnArgs {
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
   int nWq[ATTN_ARG_SEQS];                     // waves of each (sequence, kv head) pair that serve the Q list (same condition)
-  int nS[ATTN_ARG_SEQS];                      // streamed T1: length of the T1 list
-  int xs_base[ATTN_ARG_SEQS];                 // second launch: first logits tile of the sequence (= its F tiles + Q tiles)
+  // (streamed T1: the second launch and the finishing kernel take the T1 list's length and the first launch's tile
+  // counts from the device counters; the argument block stays small, it is read over the host link in some set-ups)
 };
 
 // launchers (defined in the .hip files)
