@@ -527,3 +527,36 @@ def test_pool_capacities_are_checked_before_anything_moves():
         p.gpu.append(0, *p.wl.step_kv(1, 0))
     assert e.value.status == tkv.TKV_ECAPACITY
     p.close()
+
+
+def test_streamed_t1_with_a_sequence_that_has_no_t1_rows():
+    """Streamed T1 where one sequence keeps nothing in T1 (its share of the second attention launch has no tiles and
+    must contribute neutral partials) and the other keeps nothing in T2."""
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=400,
+                       decode_steps=3, sigma=1.0)
+    p = _pair(cfg, prefetch_mode="stream")
+    rng = np.random.default_rng(11)
+    n = cfg.context
+    tiers = np.zeros((cfg.batch, n), np.uint8)
+    tiers[0] = _random_tiers(rng, 1, n, frac=(0.3, 0.7, 0.0, 0.0))[0]
+    tiers[1] = _random_tiers(rng, 1, n, frac=(0.4, 0.0, 0.5, 0.1))[0]
+    p.force_tiers(tiers)
+    calls = 0
+    for step in range(cfg.decode_steps):
+        for l in range(cfg.n_layers):
+            p.append(l, *p.wl.step_kv(step, l))
+            got, ref = p.attend(l, p.wl.step_q(step, l))
+            calls += 1
+            assert_out_close(got, ref, "bf16", f"step {step} layer {l}")
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n + cfg.decode_steps, _mass(cfg, calls))
+    # now the first sequence gives up all of T1 as well: the second launch disappears
+    t2 = np.zeros((cfg.batch, n + cfg.decode_steps), np.uint8)
+    t2[:, :n] = np.where(tiers == 1, 0, tiers)
+    p.force_tiers(t2)
+    for l in range(cfg.n_layers):
+        got, ref = p.attend(l, p.wl.step_q(0, l))
+        calls += 1
+        assert_out_close(got, ref, "bf16", f"no T1 left, layer {l}")
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n + cfg.decode_steps, _mass(cfg, calls))
+    p.close()
