@@ -259,6 +259,7 @@ hipError_t launch_plan_count(const DevView& v, int n, hipStream_t st) {
 // Exclusive scan of four packed 4x16-bit counters over the workgroup (chunk counts never exceed 1024).
 struct Pack4 { unsigned long long p[4]; };
 
+template <int THREADS>
 __device__ __forceinline__ Pack4 block_excl_scan(const Pack4& in, Pack4& total, unsigned long long (*wsum)[4]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   Pack4 inc = in;
@@ -279,7 +280,7 @@ __device__ __forceinline__ Pack4 block_excl_scan(const Pack4& in, Pack4& total, 
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     unsigned long long pre = 0, tot = 0;
-    for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
       const unsigned long long s = wsum[w][k];
       if (w < wave) pre += s;
       tot += s;
@@ -293,8 +294,11 @@ __device__ __forceinline__ Pack4 block_excl_scan(const Pack4& in, Pack4& total, 
 
 __device__ __forceinline__ int fld(unsigned long long p, int k) { return (int)((p >> (16 * k)) & 0xFFFFull); }
 
-__global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) {
-  __shared__ unsigned long long wsum[PLAN_THREADS / 64][4];
+// 512 threads: the 13 running ranks, the packed scan and the move-list bookkeeping need more than the 128 registers a
+// thread of a 1024-thread workgroup can have (the wider version spilled 170 of them)
+constexpr int COMMIT_THREADS = 512;
+__global__ __launch_bounds__(COMMIT_THREADS) void k_plan_commit(DevView v, int n) {
+  __shared__ unsigned long long wsum[COMMIT_THREADS / 64][4];
   const int b = blockIdx.x, t = threadIdx.x;
   int* cnt = v.cnt + b * CNT_N;
   const size_t o = (size_t)b * v.Nmax;
@@ -305,7 +309,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
   int* free2 = v.free2 + (size_t)b * v.cap2;
   __syncthreads();
   // HBM slots whose rows were offloaded at the previous migrate are free now (their staged copies have landed)
-  for (int j = t; j < npend; j += PLAN_THREADS) {
+  for (int j = t; j < npend; j += COMMIT_THREADS) {
     if (nfree0 + j < v.cap0) free0[nfree0 + j] = v.pend[o + j];
   }
   nfree0 += npend;
@@ -317,7 +321,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
   int run[13];
   for (int k = 0; k < 13; ++k) run[k] = 0;
   const int hbase = v.host_base[b];
-  for (int base = 0; base < n; base += PLAN_THREADS) {
+  for (int base = 0; base < n; base += COMMIT_THREADS) {
     const int i = base + t;
     const bool in = i < n;
     const int a = in ? v.tier[o + i] : 0, c = in ? v.tier_new[o + i] : 0;
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
               ((unsigned long long)m10 << 48);
     pk.p[3] = (unsigned long long)md;
     Pack4 tot;
-    const Pack4 ex = block_excl_scan(pk, tot, wsum);
+    const Pack4 ex = block_excl_scan<COMMIT_THREADS>(pk, tot, wsum);
     int rk[13], tt[13];
     for (int k = 0; k < 13; ++k) { rk[k] = run[k] + fld(ex.p[k >> 2], k & 3); tt[k] = fld(tot.p[k >> 2], k & 3); }
     // a chunk total of exactly 1024 does not fit a 16-bit field only if > 65535: fine
@@ -403,9 +407,9 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
   __syncthreads();
   // push the released slots above what is left of each stack
   const int h0 = nfree0 - run[4], h1 = nfree1 - run[5], h2 = nfree2 - run[6];
-  for (int j = t; j < run[7]; j += PLAN_THREADS) if (h0 + j >= 0 && h0 + j < v.cap0) free0[h0 + j] = v.rel0[o + j];
-  for (int j = t; j < run[9]; j += PLAN_THREADS) if (h1 + j >= 0 && h1 + j < v.cap1) free1[h1 + j] = v.rel1[o + j];
-  for (int j = t; j < run[10]; j += PLAN_THREADS) if (h2 + j >= 0 && h2 + j < v.cap2) free2[h2 + j] = v.rel2[o + j];
+  for (int j = t; j < run[7]; j += COMMIT_THREADS) if (h0 + j >= 0 && h0 + j < v.cap0) free0[h0 + j] = v.rel0[o + j];
+  for (int j = t; j < run[9]; j += COMMIT_THREADS) if (h1 + j >= 0 && h1 + j < v.cap1) free1[h1 + j] = v.rel1[o + j];
+  for (int j = t; j < run[10]; j += COMMIT_THREADS) if (h2 + j >= 0 && h2 + j < v.cap2) free2[h2 + j] = v.rel2[o + j];
   if (t == 0) {
     cnt[C_NF] = v.streamed ? run[0] : run[0] + run[1]; cnt[C_NQ] = run[2]; cnt[C_NS] = v.streamed ? run[1] : 0;
     cnt[C_N0] = run[0]; cnt[C_N1] = run[1]; cnt[C_N2] = run[2]; cnt[C_N3] = run[3];
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_plan_commit(DevView v, int n) 
   }
 }
 hipError_t launch_plan_commit(const DevView& v, int n, hipStream_t st) {
-  hipLaunchKernelGGL(k_plan_commit, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
+  hipLaunchKernelGGL(k_plan_commit, dim3(v.B), dim3(COMMIT_THREADS), 0, st, v, n);
   return hipGetLastError();
 }
 
@@ -699,7 +703,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_rehome(DevView v, int n) {
     Pack4 pk;
     pk.p[0] = (unsigned long long)f; pk.p[1] = 0; pk.p[2] = 0; pk.p[3] = 0;
     Pack4 tot;
-    const Pack4 ex = block_excl_scan(pk, tot, wsum);
+    const Pack4 ex = block_excl_scan<PLAN_THREADS>(pk, tot, wsum);
     if (in) {
       if (f) {
         const int hl = hbase + run + fld(ex.p[0], 0);
