@@ -372,7 +372,7 @@ def test_classify_bit_exact_given_scores(seed, rule):
 
 
 def test_tiny_config_teacher_forced():
-    """BASELINE config 0: 1 layer, 8/2 heads, d 64, fp32, 512-token context, 32 steps, re-tiering every 8 steps
+    """The tiny benchmark configuration: 1 layer, 8/2 heads, d 64, fp32, 512-token context, 32 steps, re-tiering every 8 steps
     (plus once before the first step).  At each event the oracle's ranking of the GPU's score array must equal
     the GPU's plan bit for bit; the oracle then adopts that plan (teacher forcing)."""
     from gpu_common import assert_out_close, assert_scores_close

@@ -1,5 +1,5 @@
 """GPU parity at the benchmark's shapes: the per-layer launch configuration depends on (batch, heads, head_dim,
-context, tier mix), not on the layer count, so these cases keep the full per-layer shape of the BASELINE configs and
+context, tier mix), not on the layer count, so these cases keep the full per-layer shape of the benchmark configurations and
 cut the number of layers (and, for the production-batch config, the number of sequences) to what the CPU oracle
 finishes in seconds.  Every output element and every score is compared, not a sample."""
 import dataclasses
