@@ -56,8 +56,10 @@ HOST_CHECK = os.path.join(HERE, "_build", "host_sanitize_check")
 def build_host_check(verbose: bool = False) -> str:
     """A second build of the host code (tkv_host.hip) with AddressSanitizer and UndefinedBehaviorSanitizer on the host
     side only, linked with the ordinary kernel objects and the scenario driver tests/native/host_sanitize_check.cpp.
-    build() must have run (it leaves the kernel objects in _build/)."""
+    Uses the kernel objects build() leaves in _build/ (and runs it first if they are not there)."""
     objdir = os.path.join(HERE, "_build")
+    if not all(os.path.exists(os.path.join(objdir, n)) for _, _, n in UNITS):
+        build()
     hipcc = _hipcc()
     san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
     host_obj = os.path.join(objdir, "tkv_host_san.o")
