@@ -87,6 +87,8 @@ def test_tier_counts_agree_with_oracle_and_reject_bad_policy():
         assert tkv.tier_counts(pol, m, ev, count_rule=1) == O.tier_counts_alg1(m, pol, ev)
     with pytest.raises(tkv.TkvError):
         tkv.tier_counts((1, 2, 3, 4), 10)
+    with pytest.raises(tkv.TkvError):
+        tkv.tier_counts((250000, 250000, 250000, 250000), 10, 0, count_rule=5)
 
 
 def test_host_code_under_sanitizers_host_only_part():

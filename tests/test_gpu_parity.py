@@ -420,6 +420,9 @@ def test_error_paths_leave_the_gpu_alone():
     with pytest.raises(tkv.TkvError) as e:
         p.gpu.classify((1, 2, 3, 4))
     assert e.value.status == tkv.TKV_EINVAL
+    with pytest.raises(tkv.TkvError) as e:      # unknown count rule
+        p.gpu.classify(cfg.policy_ppm, count_rule=2)
+    assert e.value.status == tkv.TKV_EINVAL
     k, v = p.wl.step_kv(0, 0)
     p.gpu.append(0, k, v)
     with pytest.raises(tkv.TkvError) as e:      # layer 1 is one token short
@@ -510,6 +513,23 @@ def test_pool_capacities_are_checked_before_anything_moves():
     with pytest.raises(tkv.TkvError) as e:
         p.gpu.migrate()
     assert e.value.status == tkv.TKV_ECAPACITY
+    p.close()
+    # streamed T1: the frames are too small for the plan; afterwards a plan that fits works
+    p = Pair(cfg, staging_rows=10, prefetch_mode="stream")
+    t = np.zeros((cfg.batch, 200), np.uint8)
+    t[:, 50:90] = 1
+    p.gpu.set_tiers(t)
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.migrate()
+    assert e.value.status == tkv.TKV_ECAPACITY
+    assert np.all(p.gpu.get_tiers() == 0)
+    t[:, 58:90] = 0                                   # 8 rows to T1
+    p.gpu.set_tiers(t); p.gpu.migrate()
+    p.orc.set_tiers(t); p.orc.migrate()
+    for l in range(2):
+        p.append(l, *p.wl.step_kv(0, l))
+        got, ref = p.attend(l, p.wl.step_q(0, l))
+        assert_out_close(got, ref, "bf16")
     p.close()
     # pinned host store too small
     p = Pair(cfg, host_rows=16)
