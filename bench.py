@@ -41,19 +41,22 @@ def call_bytes(cfg, n_full, n_t2, out_es=4):
     return kv + B * Hq * D * (es + out_es) + (n_full + n_t2) * 4 * 2
 
 
+BOUNCE_MIB = 0   # --bounce-mib: size of each bounce ring of the T1 transport (0: the library's default)
+
+
 def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
     import torch
     import paper_2605_09490_amd as tkv
     from tkv_synth import Workload
 
     wl = Workload(cfg, device="cuda")
-    sizes = {}
+    sizes = {"bounce_bytes": BOUNCE_MIB << 20}
     if mode == "stream":
         # the two frames are sized for T1's share of the final length plus 30 % (a migrate takes the slots of the rows
         # that enter T1 before it releases those of the rows that leave); the HBM pool still takes the whole context,
         # which is appended before the first tiering
         n_end = cfg.context + cfg.decode_steps
-        sizes = {"staging_rows": min(cfg.max_tokens, int(1.3 * policy[1] * n_end) // 1_000_000 + 64)}
+        sizes["staging_rows"] = min(cfg.max_tokens, int(1.3 * policy[1] * n_end) // 1_000_000 + 64)
     gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                        kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt, k_sink=cfg.k_sink,
                        k_window=cfg.k_window, prefetch_mode=mode, **sizes)
@@ -224,9 +227,12 @@ def main():
     ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "f16", "f32"], help="K, V and query type (default: the workload's own)")
     ap.add_argument("--delta", type=int, default=0, help="re-tier every DELTA steps (default: the workload's own)")
     ap.add_argument("--k-window", type=int, default=-1, help="protected recent window (default: the workload's own)")
+    ap.add_argument("--bounce-mib", type=int, default=0, help="size of each T1 bounce ring in MiB (default: the library's own)")
     ap.add_argument("--count-rule", default="total", choices=["total", "alg1"],
                     help="band sizes as fixed fractions of all candidates, or Algorithm 1's floors (evicts again at every event)")
     args = ap.parse_args()
+    global BOUNCE_MIB
+    BOUNCE_MIB = args.bounce_mib
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)

@@ -27,7 +27,8 @@ struct EvPair { hipEvent_t a, b; int64_t bytes; int dir; };  // dir 0 = D2H, 1 =
 }  // namespace
 
 // one bounce-buffer piece of a layer's demoted rows: gather -> D2H -> H2D -> scatter
-struct XferJob { int layer; int r0; int nrows; int piece; int64_t host_row; bool last_of_layer; };
+// (nlayers > 1: the same rows of that many consecutive layers, moved by one strided copy each way)
+struct XferJob { int layer; int r0; int nrows; int piece; int64_t host_row; bool last_of_layer; int nlayers; };
 
 struct tkv_cache {
   tkv_config cfg{};
@@ -174,30 +175,33 @@ tkv_status enqueue_job(tkv_cache* c, const XferJob& j) {
     return fail(c, TKV_EDEVICE, "hipEventCreate failed");
   EvPair* ea = &c->copy_events[c->copy_events_used - 2];
   EvPair* eb = &c->copy_events[c->copy_events_used - 1];
-  ea->dir = 0; eb->dir = 1; ea->bytes = eb->bytes = (int64_t)bytes;
-  HIPCHK(c, launch_gather(v, j.layer, j.r0, j.nrows, ba, c->sA));
+  const int nl = j.nlayers;
+  const size_t layer_pitch = (size_t)c->host_rows * c->tok_bytes;     // distance of the same host row in the next layer
+  ea->dir = 0; eb->dir = 1; ea->bytes = eb->bytes = (int64_t)bytes * nl;
+  for (int li = 0; li < nl; ++li) HIPCHK(c, launch_gather(v, j.layer + li, j.r0, j.nrows, ba + (size_t)li * bytes, c->sA));
   HIPCHK(c, hipEventRecord(ea->a, c->sA));
-  HIPCHK(c, hipMemcpyAsync(hp, ba, bytes, hipMemcpyDeviceToHost, c->sA));
+  if (nl == 1) HIPCHK(c, hipMemcpyAsync(hp, ba, bytes, hipMemcpyDeviceToHost, c->sA));
+  else HIPCHK(c, hipMemcpy2DAsync(hp, layer_pitch, ba, bytes, bytes, (size_t)nl, hipMemcpyDeviceToHost, c->sA));
   HIPCHK(c, hipEventRecord(ea->b, c->sA));
   if (c->streamed) {
-    // the rows stay in the pinned store; the next fill of this layer's frame waits for the last piece
+    // the rows stay in the pinned store; the next fill of a layer's frame waits for the layer's last piece
     --c->copy_events_used;
-    c->st.d2h_bytes += (int64_t)bytes; c->st.d2h_copies++;
-    if (j.last_of_layer) { HIPCHK(c, hipEventRecord(c->ev_ready[j.layer], c->sA)); c->layer_enq[j.layer] = 1; }
+    c->st.d2h_bytes += (int64_t)bytes * nl; c->st.d2h_copies++;
+    if (j.last_of_layer)
+      for (int li = 0; li < nl; ++li) { HIPCHK(c, hipEventRecord(c->ev_ready[j.layer + li], c->sA)); c->layer_enq[j.layer + li] = 1; }
     return TKV_OK;
   }
   HIPCHK(c, hipEventRecord(c->ev_piece[j.piece % RING], c->sA));
   HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_piece[j.piece % RING], 0));
   HIPCHK(c, hipEventRecord(eb->a, c->sB));
-  HIPCHK(c, hipMemcpyAsync(bb, hp, bytes, hipMemcpyHostToDevice, c->sB));
+  if (nl == 1) HIPCHK(c, hipMemcpyAsync(bb, hp, bytes, hipMemcpyHostToDevice, c->sB));
+  else HIPCHK(c, hipMemcpy2DAsync(bb, bytes, hp, layer_pitch, bytes, (size_t)nl, hipMemcpyHostToDevice, c->sB));
   HIPCHK(c, hipEventRecord(eb->b, c->sB));
-  HIPCHK(c, launch_scatter(v, j.layer, j.r0, j.nrows, bb, c->sB));
-  c->st.d2h_bytes += (int64_t)bytes; c->st.h2d_bytes += (int64_t)bytes;
+  for (int li = 0; li < nl; ++li) HIPCHK(c, launch_scatter(v, j.layer + li, j.r0, j.nrows, bb + (size_t)li * bytes, c->sB));
+  c->st.d2h_bytes += (int64_t)bytes * nl; c->st.h2d_bytes += (int64_t)bytes * nl;
   c->st.d2h_copies++; c->st.h2d_copies++;
-  if (j.last_of_layer) {
-    HIPCHK(c, hipEventRecord(c->ev_ready[j.layer], c->sB));
-    c->layer_enq[j.layer] = 1;
-  }
+  if (j.last_of_layer)
+    for (int li = 0; li < nl; ++li) { HIPCHK(c, hipEventRecord(c->ev_ready[j.layer + li], c->sB)); c->layer_enq[j.layer + li] = 1; }
   return TKV_OK;
 }
 
@@ -207,7 +211,7 @@ tkv_status pump_transfers(tkv_cache* c, int n_layers) {
     const XferJob& j = c->jobs[c->jobs_next++];
     tkv_status s = enqueue_job(c, j);
     if (s != TKV_OK) return s;
-    if (j.last_of_layer) --n_layers;
+    if (j.last_of_layer) n_layers -= j.nlayers;
   }
   return TKV_OK;
 }
@@ -790,13 +794,16 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
     int piece = 0;
     c->jobs.clear(); c->jobs_next = 0;
-    for (int l = 0; l < L; ++l) {
+    // when a layer's rows fill only part of a bounce piece, several layers share one (one strided copy each way
+    // instead of one per layer: the copies disturb the attention kernels per copy, not per byte)
+    const int group = total_new_t1 <= piece_rows ? (int)std::min<int64_t>(L, piece_rows / total_new_t1) : 1;
+    for (int l = 0; l < L; l += group) {
+      const int nl = std::min(group, L - l);
       for (int64_t r0 = 0; r0 < total_new_t1; r0 += piece_rows, ++piece) {
         const int nrows = (int)std::min<int64_t>(piece_rows, total_new_t1 - r0);
-        c->jobs.push_back(XferJob{l, (int)r0, nrows, piece, c->host_next + r0, r0 + piece_rows >= total_new_t1});
+        c->jobs.push_back(XferJob{l, (int)r0, nrows, piece, c->host_next + r0, r0 + piece_rows >= total_new_t1, nl});
       }
-      c->layer_wait[l] = 1;
-      c->layer_enq[l] = 0;
+      for (int li = 0; li < nl; ++li) { c->layer_wait[l + li] = 1; c->layer_enq[l + li] = 0; }
     }
     if (c->cfg.prefetch_mode != TKV_PREFETCH_LAZY) {
       tkv_status ps = pump_transfers(c, L);
