@@ -257,6 +257,24 @@ def test_random_walk_of_plans(mode, kv_dtype, D, Hq, Hkv, t2):
     assert st["n_rehome"] == 0
 
 
+@pytest.mark.parametrize("mode", ["wait", "lazy", "stream"])
+@pytest.mark.parametrize("piece_rows", [100, 600])
+def test_walk_with_small_bounce_rings(mode, piece_rows):
+    """The same walk over 5 layers with bounce rings whose pieces hold 100 or 600 positions of one layer, against the
+    ~200-350 positions that enter T1 at a plan: with 100 every layer's rows take several copies, with 600 the rows
+    of two layers share a piece and one strided copy (a last group of one layer, and a first plan whose rows fill a
+    piece alone).  Every T1 row of the last layer is read back from the pinned store after every plan."""
+    tok_bytes = 2 * 2 * 64 * 2
+    st = _plan_walk(mode, "bf16", 64, 8, 2, "int8_row", all_t1_rows=True, rounds=5, layers=5,
+                    bounce_bytes=4 * piece_rows * tok_bytes)
+    assert st["n_rehome"] == 0
+    copies_one_per_layer = 5 * 5
+    if piece_rows == 100:
+        assert st["d2h_copies"] > copies_one_per_layer
+    else:
+        assert 0 < st["d2h_copies"] < copies_one_per_layer
+
+
 @pytest.mark.parametrize("mode,layers", [("wait", 2), ("lazy", 2), ("stream", 2), ("stream", 5)])
 def test_pinned_store_is_rewritten_when_it_runs_out(mode, layers):
     """A longer walk of the same kind with a pinned store of 520 rows: T1 holds ~300 rows and ~100 enter at every plan, so the store
@@ -284,11 +302,11 @@ def test_streamed_t1_walk(kv_dtype, D, Hq, Hkv, t2, layers):
     assert st["h2d_bytes"] > st["d2h_bytes"] > 0        # T1 crosses the link again at every step
 
 
-def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False, rounds=8, layers=2):
+def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False, rounds=8, layers=2, **create_kw):
     from gpu_common import assert_out_close, assert_scores_close
     cfg = small_config(n_layers=layers, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
                        context=500, decode_steps=rounds, t2_format=t2, sigma=1.0)
-    p = _pair(cfg, prefetch_mode=mode, **({"host_rows": host_rows} if host_rows else {}))
+    p = _pair(cfg, prefetch_mode=mode, **({"host_rows": host_rows} if host_rows else {}), **create_kw)
     rng = np.random.default_rng(77)
     n = cfg.context
     tiers = np.zeros((cfg.batch, n), np.uint8)
