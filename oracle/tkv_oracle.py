@@ -17,7 +17,8 @@ fixes a precision:
 Parity pins (see tests/test_oracle_pins.py): softmax mass, Prop. 1, Eq. 3,
 Eq. 4, closed forms for tiny hand-made caches, float64
 scaled_dot_product_attention for the full-cache case, brute-force sorting for
-ranks, codec round-trip bounds.  No function here is "parity unpinned".
+ranks, codec round-trip bounds, hand-worked and brute-force cases for the
+value-aware scorer.  No function here is "parity unpinned".
 
 Notation follows the paper: L layers, H query heads (Hq), Hkv key/value heads,
 G = Hq/Hkv, d head dim, s_i cumulative score of position i, tiers T0..T3,
@@ -122,6 +123,34 @@ def score_increment(alpha: np.ndarray, score_scale: float) -> np.ndarray:
     double average; evicted positions have alpha = 0 and so keep their score.
     """
     return float(score_scale) * alpha.sum(axis=1)
+
+
+def value_norms(V: np.ndarray) -> np.ndarray:
+    """Euclidean norm of every value row: V [..., d] -> [...]."""
+    V = np.asarray(V, dtype=np.float64)
+    return np.sqrt((V * V).sum(axis=-1))
+
+
+def score_increment_vatp(alpha: np.ndarray, vnorm: np.ndarray, score_scale: float) -> np.ndarray:
+    """One layer's contribution under the value-aware scorer of the scoring ablation
+    (Sec. "Ablation: Importance Scoring Methods"): every head's attention weight on a
+    position is multiplied by the norm of the value row that head reads there.
+
+    alpha [B, Hq, n], vnorm [B, Hkv, n] -> [B, n]:
+    score_scale * sum_h alpha[b, h, i] * vnorm[b, h // G, i].
+    The paper names "value vector norms" without saying which norm or which copy of
+    the row; this build's reading: Euclidean, of the row as appended (a position's
+    norm does not change when its row is later compressed).
+    """
+    alpha = np.asarray(alpha, dtype=np.float64)
+    vnorm = np.asarray(vnorm, dtype=np.float64)
+    B, Hq, n = alpha.shape
+    G = Hq // vnorm.shape[1]
+    inc = np.zeros((B, n), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            inc[b] += alpha[b, h] * vnorm[b, h // G]
+    return float(score_scale) * inc
 
 
 def eviction_error_bound(alpha_full: np.ndarray, V: np.ndarray, evicted: np.ndarray) -> float:
@@ -329,7 +358,7 @@ class OracleCache:
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens,
                  kv_dtype="bf16", t2_format="int8_row", n_prompt=0, k_sink=4, k_window=128,
-                 score_scale=None, softmax_scale=None, layers=None):
+                 score_scale=None, softmax_scale=None, layers=None, scorer="attention"):
         self.L, self.B, self.Hq, self.Hkv, self.d = n_layers, batch, n_q_heads, n_kv_heads, head_dim
         self.G = n_q_heads // n_kv_heads
         assert self.G * n_kv_heads == n_q_heads
@@ -348,6 +377,10 @@ class OracleCache:
         self.tier = np.zeros((batch, max_tokens), dtype=np.uint8)
         self.tier_pending = None
         self.score = np.zeros((batch, max_tokens), dtype=np.float64)
+        # "attention": Eq. 1.  "vatp": the value-aware variant of the scoring ablation.
+        assert scorer in ("attention", "vatp")
+        self.scorer = scorer
+        self.vnorm = {l: np.zeros(shape[:3], dtype=np.float64) for l in self.layers} if scorer == "vatp" else None
 
     # -- Algorithm 1: the cache grows by the generated token --------------------
     def append(self, layer, k, v):
@@ -360,6 +393,8 @@ class OracleCache:
             raise OverflowError("append beyond max_tokens")
         self.K[layer][:, :, n0:n0 + n_new] = k.transpose(0, 2, 1, 3)
         self.V[layer][:, :, n0:n0 + n_new] = v.transpose(0, 2, 1, 3)
+        if self.vnorm is not None:
+            self.vnorm[layer][:, :, n0:n0 + n_new] = value_norms(v.transpose(0, 2, 1, 3))
         self.length[layer] = n0 + n_new
         self.tier[:, n0:n0 + n_new] = T0
 
@@ -368,7 +403,10 @@ class OracleCache:
         n = self.length[layer]
         live = self.tier[:, :n] != T3
         out, alpha = attend_gqa(q, self.K[layer][:, :, :n], self.V[layer][:, :, :n], live, self.softmax_scale)
-        self.score[:, :n] += score_increment(alpha, self.score_scale)
+        if self.scorer == "vatp":
+            self.score[:, :n] += score_increment_vatp(alpha, self.vnorm[layer][:, :, :n], self.score_scale)
+        else:
+            self.score[:, :n] += score_increment(alpha, self.score_scale)
         return out
 
     # -- tier management ----------------------------------------------------------

@@ -452,3 +452,81 @@ def test_cache_classify_then_attend_skips_evicted():
     assert ev.sum() == (40 - 6) // 10
     assert np.array_equal(c.score[0, :40][ev], s_before[0, :40][ev])
     assert np.all(c.score[0, :40][~ev] > s_before[0, :40][~ev])
+
+
+# ---------------------------------------------------------------- value-aware scorer (scoring ablation)
+def test_vatp_hand_worked_case():
+    # one head, two positions with the same key: weights 1/2 and 1/2; value rows (3, 4) and (0, 2) have
+    # norms 5 and 2, so the increments are 2.5 and 1 (score_scale 1)
+    c = O.OracleCache(1, 1, 1, 1, 2, max_tokens=4, kv_dtype="f32", score_scale=1.0, scorer="vatp", k_sink=0, k_window=0)
+    k = np.array([[[[1.0, 0.0]], [[1.0, 0.0]]]], np.float32)          # [B=1, n=2, Hkv=1, d=2]
+    v = np.array([[[[3.0, 4.0]], [[0.0, 2.0]]]], np.float32)
+    c.append(0, k, v)
+    c.attend_and_score(0, np.array([[[0.7, -0.2]]]))
+    assert np.allclose(c.score[0, :2], [2.5, 1.0], atol=1e-15)
+
+
+def test_vatp_with_unit_value_rows_is_the_attention_score():
+    ca = O.OracleCache(2, 2, 4, 2, 16, max_tokens=40, kv_dtype="f32", score_scale=1.0)
+    cv = O.OracleCache(2, 2, 4, 2, 16, max_tokens=40, kv_dtype="f32", score_scale=1.0, scorer="vatp")
+    for l in range(2):
+        k = rng.normal(size=(2, 30, 2, 16))
+        v = rng.normal(size=(2, 30, 2, 16))
+        v /= np.linalg.norm(v, axis=-1, keepdims=True)
+        ca.append(l, k, v); cv.append(l, k, v)
+    for l in range(2):
+        q = rng.normal(size=(2, 4, 16))
+        assert np.array_equal(ca.attend_and_score(l, q), cv.attend_and_score(l, q))   # outputs do not depend on the scorer
+    assert np.allclose(ca.score, cv.score, rtol=1e-13, atol=0)
+
+
+def test_vatp_scaling_one_value_row_scales_that_positions_increment_only():
+    def run(scale_pos7):
+        c = O.OracleCache(1, 1, 4, 2, 8, max_tokens=16, kv_dtype="f32", score_scale=0.25, scorer="vatp")
+        r = np.random.default_rng(5)
+        k = r.normal(size=(1, 12, 2, 8)); v = r.normal(size=(1, 12, 2, 8))
+        v[0, 7] *= scale_pos7
+        c.append(0, k, v)
+        c.attend_and_score(0, r.normal(size=(1, 4, 8)))
+        return c.score[0, :12].copy()
+    s1, s3 = run(1.0), run(-3.0)
+    assert np.allclose(s3[7], 3.0 * s1[7], rtol=1e-13)
+    others = np.arange(12) != 7
+    assert np.allclose(s3[others], s1[others], rtol=1e-13)          # the weights do not depend on V
+
+
+def test_vatp_matches_brute_force_loops_with_gqa_and_eviction():
+    B, Hq, Hkv, d, n = 2, 6, 2, 4, 9
+    G = Hq // Hkv
+    r = np.random.default_rng(11)
+    c = O.OracleCache(1, B, Hq, Hkv, d, max_tokens=n, kv_dtype="f32", score_scale=0.5, scorer="vatp", k_sink=0, k_window=0)
+    k = r.normal(size=(B, n, Hkv, d)); v = r.normal(size=(B, n, Hkv, d))
+    c.append(0, k, v)
+    tiers = np.zeros((B, n), np.uint8); tiers[:, 2] = O.T3; tiers[1, 5] = O.T3
+    c.set_tiers(tiers); c.migrate()
+    q = r.normal(size=(B, Hq, d))
+    c.attend_and_score(0, q)
+    for b in range(B):
+        want = [0.0] * n
+        for h in range(Hq):
+            kvh = h // G
+            live = [i for i in range(n) if tiers[b, i] != O.T3]
+            x = {i: sum(q[b, h, e] * k[b, i, kvh, e] for e in range(d)) / math.sqrt(d) for i in live}
+            z = sum(math.exp(x[i]) for i in live)
+            for i in live:
+                want[i] += 0.5 * (math.exp(x[i]) / z) * math.sqrt(sum(v[b, i, kvh, e] ** 2 for e in range(d)))
+        assert np.allclose(c.score[b], want, rtol=1e-12, atol=1e-15)
+    assert c.score[0, 2] == 0.0 and c.score[1, 5] == 0.0
+
+
+def test_vatp_norm_is_the_appended_rows_and_survives_compression():
+    # a row that goes to T2 keeps the norm it was appended with (this build's reading)
+    c = O.OracleCache(1, 1, 2, 1, 8, max_tokens=8, kv_dtype="bf16", score_scale=1.0, scorer="vatp", k_sink=0, k_window=0)
+    r = np.random.default_rng(3)
+    k = O.round_to_bf16(r.normal(size=(1, 6, 1, 8)).astype(np.float32)); v = O.round_to_bf16(r.normal(size=(1, 6, 1, 8)).astype(np.float32))
+    c.append(0, k, v)
+    before = c.vnorm[0].copy()
+    tiers = np.zeros((1, 6), np.uint8); tiers[0, 1] = O.T2
+    c.set_tiers(tiers); c.migrate()
+    assert np.array_equal(c.vnorm[0], before)
+    assert np.allclose(before[0, 0, :6], np.linalg.norm(v[0, :, 0].astype(np.float64), axis=-1), rtol=1e-15)
