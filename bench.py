@@ -42,6 +42,7 @@ def call_bytes(cfg, n_full, n_t2, out_es=4):
 
 
 BOUNCE_MIB = 0   # --bounce-mib: size of each bounce ring of the T1 transport (0: the library's default)
+SCORER = "attention"   # --scorer
 
 
 def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
@@ -50,7 +51,7 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
     from tkv_synth import Workload
 
     wl = Workload(cfg, device="cuda")
-    sizes = {"bounce_bytes": BOUNCE_MIB << 20}
+    sizes = {"bounce_bytes": BOUNCE_MIB << 20, "scorer": SCORER}
     if mode == "stream":
         # the two frames are sized for T1's share of the final length plus 30 % (a migrate takes the slots of the rows
         # that enter T1 before it releases those of the rows that leave); the HBM pool still takes the whole context,
@@ -135,7 +136,8 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
         # Eq. 1 at full size: every attention call adds one unit of probability per query head, so with the scale
         # 1/(L*Hq) each sequence's scores (evicted positions keep theirs) sum to the number of decode steps so far
         steps_done = 1 + (warmup - 1) + steps + profile_steps
-        res["score_mass_rel_err"] = float(np.abs(sc.sum(1) / steps_done - 1.0).max())
+        if SCORER == "attention":
+            res["score_mass_rel_err"] = float(np.abs(sc.sum(1) / steps_done - 1.0).max())
     res["device_bytes"] = st2["device_bytes"]
     res["pinned_bytes"] = st2["pinned_bytes"]
     res["gpu"] = gpu
@@ -228,11 +230,14 @@ def main():
     ap.add_argument("--delta", type=int, default=0, help="re-tier every DELTA steps (default: the workload's own)")
     ap.add_argument("--k-window", type=int, default=-1, help="protected recent window (default: the workload's own)")
     ap.add_argument("--bounce-mib", type=int, default=0, help="size of each T1 bounce ring in MiB (default: the library's own)")
+    ap.add_argument("--scorer", default="attention", choices=["attention", "vatp"],
+                    help="cumulative attention (Eq. 1, the paper's method) or the value-aware variant of its scoring ablation")
     ap.add_argument("--count-rule", default="total", choices=["total", "alg1"],
                     help="band sizes as fixed fractions of all candidates, or Algorithm 1's floors (evicts again at every event)")
     args = ap.parse_args()
-    global BOUNCE_MIB
+    global BOUNCE_MIB, SCORER
     BOUNCE_MIB = args.bounce_mib
+    SCORER = args.scorer
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -304,7 +309,8 @@ def main():
                                f"{cfg.kv_dtype} KV, batch {cfg.batch}, {cfg.context}-token context, tiers ppm {list(pol)}, "
                                f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"
                                + (f", k_window {cfg.k_window}" if args.k_window >= 0 else "")
-                               + (", Algorithm-1 count rule" if rule else "")},
+                               + (", Algorithm-1 count rule" if rule else "")
+                               + (", value-aware scorer" if SCORER != "attention" else "")},
         "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),
         "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
         "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,

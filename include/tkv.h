@@ -71,6 +71,14 @@ typedef enum { TKV_T2_INT8_ROW = 0, TKV_T2_INT4_G32 = 1 } tkv_t2_format;
  *        the pinned store whose positions have left T1 since the store was last rewritten). */
 typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1, TKV_PREFETCH_STREAM = 2 } tkv_prefetch_mode;
 
+/* What a layer call adds to the cumulative score of a position:
+ *  ATTENTION: score_scale * sum over query heads of the attention weight (Eq. 1; the paper's method);
+ *  VATP: the value-aware variant of the paper's scoring ablation (Sec. "Ablation: Importance Scoring Methods"): each
+ *        head's weight is multiplied by the Euclidean norm of the value row that head reads at the position.  The norm
+ *        is taken once, from the row as appended (binary32, fixed summation order); it does not follow the row
+ *        through later compression.  Costs 4 bytes per (layer, sequence, kv head, position) of device memory. */
+typedef enum { TKV_SCORE_ATTENTION = 0, TKV_SCORE_VATP = 1 } tkv_scorer;
+
 typedef struct {
   int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64, 128}; n_q_heads % n_kv_heads == 0,
                                                                group size n_q_heads / n_kv_heads <= 8 */
@@ -96,6 +104,7 @@ typedef struct {
   int64_t bounce_bytes;                /* size of each of the two device bounce rings used for T1 traffic; 0 -> 64 MiB */
   int32_t prefetch_mode;               /* tkv_prefetch_mode */
   int32_t profile;                     /* != 0: time every attention kernel with HIP events (tkv_get_stats) */
+  int32_t scorer;                      /* tkv_scorer */
   int32_t device;                      /* HIP device ordinal */
   void* (*dev_alloc)(size_t bytes, void* ctx); /* device memory, 256-byte aligned; NULL -> hipMalloc */
   void (*dev_free)(void* p, void* ctx);

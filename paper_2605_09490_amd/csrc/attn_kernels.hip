@@ -937,8 +937,16 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
         float x[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) x[g] = (kvh == hg) ? x0[g] : a.xs[((size_t)b * a.Hq + kvh * G + g) * a.xs_stride + j];
+        if (a.vnorm) {
+          // value-aware scorer: the group's weights times the norm of the value row its heads read
+          float w = 0.f;
 #pragma unroll
-        for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[kvh * G + g]) * LOG2E) * IL[kvh * G + g];
+          for (int g = 0; g < G; ++g) w += __builtin_amdgcn_exp2f((x[g] - M[kvh * G + g]) * LOG2E) * IL[kvh * G + g];
+          acc = fmaf(w, a.vnorm[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
+        } else {
+#pragma unroll
+          for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[kvh * G + g]) * LOG2E) * IL[kvh * G + g];
+        }
       }
     }
     __syncthreads();          // sm_pm is free now: reuse it for the partial sums

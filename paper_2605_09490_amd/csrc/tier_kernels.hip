@@ -92,10 +92,13 @@ __global__ void k_append_step(DevView v, const char* __restrict__ k, const char*
   *(u32x4*)(v.fpK + dst) = *(const u32x4*)(k + (size_t)i * 16);
   *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + (size_t)i * 16);
 }
+static void launch_vnorm(const DevView& v, const void* rows, long long n_rows, int n_new, int lb0, int pos0, hipStream_t st);
+
 hipError_t launch_append_step(const DevView& v, const void* k, const void* v_, int pos, hipStream_t st) {
   hipLaunchKernelGGL(k_append_assign, dim3(v.B), dim3(256), 0, st, v, pos, 1);
   const long long total = (long long)v.L * v.B * v.Hkv * (v.D * v.es / 16);
   hipLaunchKernelGGL(k_append_step, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, (const char*)k, (const char*)v_, pos);
+  if (v.vnorm) launch_vnorm(v, v_, (long long)v.L * v.B * v.Hkv, 1, 0, pos, st);
   return hipGetLastError();
 }
 
@@ -105,6 +108,7 @@ hipError_t launch_append(const DevView& v, int layer, const void* k, const void*
   const long long total = (long long)v.B * n_new * v.Hkv * (v.D * v.es / 16);
   const int blocks = (int)((total + 255) / 256);
   hipLaunchKernelGGL(k_append_rows, dim3(blocks), dim3(256), 0, st, v, layer, (const char*)k, (const char*)v_, pos0, n_new);
+  if (v.vnorm) launch_vnorm(v, v_, (long long)v.B * n_new * v.Hkv, n_new, layer * v.B, pos0, st);
   return hipGetLastError();
 }
 
@@ -505,6 +509,33 @@ __device__ __forceinline__ void store8(char* row, int e0, int kt, const float (&
     w.z = bf16_rne_bits(x[4]) | (bf16_rne_bits(x[5]) << 16); w.w = bf16_rne_bits(x[6]) | (bf16_rne_bits(x[7]) << 16);
     *(u32x4*)(row + (size_t)e0 * 2) = w;
   }
+}
+
+// Value-aware scorer: Euclidean norm of appended value rows.  rows: dense [n_rows][D] in the KV type, row r being
+// (layer * B + sequence, new token j, kv head) = (lb0 + r / (n_new * Hkv), (r / Hkv) % n_new, r % Hkv); D / 8 lanes
+// per row, each sums the squares of its 8 elements in order, then the lanes' sums are added pairwise (1, 2, 4, 8 apart).
+__global__ void k_vnorm(DevView v, const char* __restrict__ rows, long long n_rows, int n_new, int lb0, int pos0) {
+  const int lpr = v.D / 8;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long r = i / lpr;
+  const int c = (int)(i % lpr);
+  float ss = 0.f;
+  if (r < n_rows) {
+    float x[8];
+    load8(rows + (size_t)r * v.D * v.es, c * 8, v.kt, x);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+  }
+  for (int o = 1; o < lpr; o <<= 1) ss += __shfl_xor(ss, o);
+  if (r < n_rows && c == 0) {
+    const int kvh = (int)(r % v.Hkv), j = (int)((r / v.Hkv) % n_new);
+    const long long lb = lb0 + r / ((long long)n_new * v.Hkv);
+    if (pos0 + j < v.Nmax) v.vnorm[((size_t)lb * v.Hkv + kvh) * v.Nmax + pos0 + j] = sqrtf(ss);
+  }
+}
+static void launch_vnorm(const DevView& v, const void* rows, long long n_rows, int n_new, int lb0, int pos0, hipStream_t st) {
+  const long long total = n_rows * (v.D / 8);
+  hipLaunchKernelGGL(k_vnorm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, (const char*)rows, n_rows, n_new, lb0, pos0);
 }
 
 // -> T2: encode the current stored row.  D/8 lanes per row (8 elements each), 64/(D/8) rows per wave.

@@ -76,6 +76,8 @@ struct DevView {
   int* h_seq; int* h_dst;   // [host_rows] streamed: for every row of the pinned store its sequence and the staging slot of
                             // the T1 position it belongs to (-1: the row's position is not in T1 any more)
   int* h_clr;               // [B][Nmax] scratch: host rows of the positions that leave T1 in the plan being committed
+  float* vnorm;             // [L][B][Hkv][Nmax] value-aware scorer: Euclidean norm of every appended value row, by position
+                            // (NULL with the attention-only scorer)
 };
 
 struct AttnArgs {
@@ -93,6 +95,7 @@ struct AttnArgs {
                     // launch serves the T1 rows from the staging frame and writes the splits after the first launch's)
   int second;       // != 0: that second launch; its list lengths are nS, its logits follow the first launch's tiles
   const int* s_pos; // [B][Nmax] positions of the T1 list (streamed T1), for the finishing kernel
+  const float* vnorm; // [B][Hkv][Nmax] this layer's value-row norms (value-aware scorer), else NULL
   int n_tiles;      // max over the sequences of F tiles + Q tiles (+ T1 tiles)
   int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_kind, q_es;   // out_kind: 0 binary32, 1 bfloat16, 2 binary16
   float softmax_scale, score_scale;

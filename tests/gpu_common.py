@@ -18,17 +18,17 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 class Pair:
     """One GPU cache and one oracle cache fed with identical stored values."""
 
-    def __init__(self, cfg, prefetch_mode="wait", preload=True, **gpu_kw):
+    def __init__(self, cfg, prefetch_mode="wait", preload=True, scorer="attention", **gpu_kw):
         self.cfg = cfg
         self.wl = Workload(cfg, device="cuda")
         self.score_scale = cfg.score_scale if cfg.score_scale is not None else 1.0 / (cfg.n_layers * cfg.n_q_heads)
         self.gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                                 kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt,
                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale,
-                                prefetch_mode=prefetch_mode, **gpu_kw)
+                                prefetch_mode=prefetch_mode, scorer=scorer, **gpu_kw)
         self.orc = O.OracleCache(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                                  kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt,
-                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale)
+                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale, scorer=scorer)
         self.steps_done = 0
         if preload:
             for l in range(cfg.n_layers):

@@ -567,6 +567,51 @@ def test_pool_capacities_are_checked_before_anything_moves():
     p.close()
 
 
+@pytest.mark.parametrize("mode,kv_dtype,D,Hq,Hkv,t2", [
+    ("lazy", "bf16", 128, 10, 2, "int8_row"),
+    ("stream", "f16", 128, 8, 2, "int4_g32"),
+    ("wait", "f32", 64, 6, 2, "int8_row"),
+])
+def test_value_aware_scorer_walk(mode, kv_dtype, D, Hq, Hkv, t2):
+    """The plan walk with the value-aware scorer of the scoring ablation: every head's weight times the Euclidean norm
+    of the value row it reads (taken when the row is appended, whatever tier the row is in later); scores against
+    the oracle's at the end, outputs as always."""
+    _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, layers=3, scorer="vatp")
+
+
+def test_value_aware_scorer_whole_steps_and_classify():
+    """Whole decode steps (one append launch for all layers, so the norms of the new rows of every layer come from one
+    launch) with re-tiering by the value-aware scores: the plan is the oracle's for the GPU's score array, bit for bit,
+    and the scores agree with the oracle's to the usual tolerance."""
+    from gpu_common import assert_scores_close
+    cfg = small_config(n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=700,
+                       decode_steps=12, sigma=1.0, k_window=16)
+    p = _pair(cfg, prefetch_mode="lazy", scorer="vatp")
+    pol = (300000, 400000, 200000, 100000)
+    calls = 0
+    for step in range(cfg.decode_steps):
+        ks, vs, qs = zip(*[(*p.wl.step_kv(step, l), p.wl.step_q(step, l)) for l in range(cfg.n_layers)])
+        k_all, v_all, q_all = torch.stack(ks), torch.stack(vs), torch.stack(qs)
+        p.gpu.decode_step(k_all, v_all, q_all)
+        for l in range(cfg.n_layers):
+            from gpu_common import to_f64
+            p.orc.append(l, to_f64(ks[l]), to_f64(vs[l]))
+            p.orc.attend_and_score(l, to_f64(qs[l]))
+            calls += 1
+        if step % 4 == 3:
+            n = p.gpu.layer_length(0)
+            s_gpu = p.gpu.get_scores()
+            assert_scores_close(s_gpu, p.orc.score, n, _mass(cfg, calls) * 20.0, f"step {step}")
+            p.gpu.classify(pol)
+            plan = p.gpu.get_pending_tiers()[:, :n]
+            assert np.array_equal(plan, p.orc.classify(pol, score_f32=s_gpu)[:, :n])
+            p.gpu.migrate()
+            p.orc.set_tiers(plan); p.orc.migrate()
+    # the scores really are not the attention-only ones
+    assert p.orc.score.sum() > 2.0 * cfg.batch * _mass(cfg, calls)
+    p.close()
+
+
 def test_streamed_t1_with_a_sequence_that_has_no_t1_rows():
     """Streamed T1 where one sequence keeps nothing in T1 (its share of the second attention launch has no tiles and
     must contribute neutral partials) and the other keeps nothing in T2."""
