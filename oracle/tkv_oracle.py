@@ -409,6 +409,29 @@ class OracleCache:
             self.score[:, :n] += score_increment(alpha, self.score_scale)
         return out
 
+    def attend_and_score_chunk(self, layer, q):
+        """Several query tokens at once: q [B, T, Hq, d] belongs to the last T appended positions,
+        query j to position n - T + j.  Each attends causally, i.e. to the positions up to and
+        including its own (Eq. 2 sums i = 1..t for the token at t), and each adds its weights to
+        the scores (Eq. 1), in the order j = 0..T-1: the same as T single-token steps whose
+        appends had all been done beforehand.  Returns out [B, T, Hq, d]."""
+        q = np.asarray(q, dtype=np.float64)
+        n = self.length[layer]
+        T = q.shape[1]
+        if T < 1 or T > n:
+            raise ValueError("chunk length")
+        out = np.zeros(q.shape, dtype=np.float64)
+        for j in range(T):
+            m = n - T + j + 1
+            live = self.tier[:, :m] != T3
+            o, alpha = attend_gqa(q[:, j], self.K[layer][:, :, :m], self.V[layer][:, :, :m], live, self.softmax_scale)
+            if self.scorer == "vatp":
+                self.score[:, :m] += score_increment_vatp(alpha, self.vnorm[layer][:, :, :m], self.score_scale)
+            else:
+                self.score[:, :m] += score_increment(alpha, self.score_scale)
+            out[:, j] = o
+        return out
+
     # -- tier management ----------------------------------------------------------
     def classify(self, policy_ppm, score_f32=None, count_rule=0):
         """Plan new tiers.  `score_f32` (e.g. the GPU's array) replaces the oracle's own

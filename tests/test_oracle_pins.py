@@ -530,3 +530,62 @@ def test_vatp_norm_is_the_appended_rows_and_survives_compression():
     c.set_tiers(tiers); c.migrate()
     assert np.array_equal(c.vnorm[0], before)
     assert np.allclose(before[0, 0, :6], np.linalg.norm(v[0, :, 0].astype(np.float64), axis=-1), rtol=1e-15)
+
+
+# ---------------------------------------------------------------- multi-token queries (causal chunk)
+def test_chunk_of_one_is_the_single_token_call():
+    c1, data = _mk_cache()
+    c2 = O.OracleCache(2, 2, 4, 2, 16, max_tokens=56, kv_dtype="f32", k_sink=2, k_window=4)
+    for l, (k, v) in data.items():
+        c2.append(l, k, v)
+    q = rng.normal(size=(2, 4, 16))
+    assert np.array_equal(c1.attend_and_score(0, q), c2.attend_and_score_chunk(0, q[:, None])[:, 0])
+    assert np.array_equal(c1.score, c2.score)
+
+
+def test_chunk_equals_token_by_token_decode():
+    # T tokens appended one at a time, each attended right after its append, against the same tokens appended
+    # first and attended as one causal chunk: outputs and scores must be the same numbers
+    B, Hq, Hkv, d, n0, T = 2, 4, 2, 8, 20, 5
+    r = np.random.default_rng(21)
+    k0, v0 = r.normal(size=(B, n0, Hkv, d)), r.normal(size=(B, n0, Hkv, d))
+    kn, vn = r.normal(size=(B, T, Hkv, d)), r.normal(size=(B, T, Hkv, d))
+    q = r.normal(size=(B, T, Hq, d))
+    tiers = np.zeros((B, n0), np.uint8); tiers[:, 3] = O.T3; tiers[0, 7] = O.T2; tiers[1, 9] = O.T1
+    def fresh():
+        c = O.OracleCache(1, B, Hq, Hkv, d, max_tokens=n0 + T, kv_dtype="f32", score_scale=1.0, k_sink=0, k_window=0)
+        c.append(0, k0, v0)
+        c.set_tiers(tiers); c.migrate()
+        return c
+    a = fresh()
+    outs = []
+    for j in range(T):
+        a.append(0, kn[:, j:j + 1], vn[:, j:j + 1])
+        outs.append(a.attend_and_score(0, q[:, j]))
+    b = fresh()
+    b.append(0, kn, vn)
+    got = b.attend_and_score_chunk(0, q)
+    assert np.array_equal(got, np.stack(outs, axis=1))
+    assert np.array_equal(a.score, b.score)
+
+
+def test_chunk_matches_float64_sdpa_with_a_causal_mask():
+    B, Hq, Hkv, d, n, T = 2, 6, 2, 16, 33, 7
+    r = np.random.default_rng(22)
+    c = O.OracleCache(1, B, Hq, Hkv, d, max_tokens=n, kv_dtype="f32", score_scale=1.0)
+    k, v = r.normal(size=(B, n, Hkv, d)), r.normal(size=(B, n, Hkv, d))
+    c.append(0, k, v)
+    q = r.normal(size=(B, T, Hq, d))
+    got = c.attend_and_score_chunk(0, q)
+    G = Hq // Hkv
+    tq = torch.from_numpy(q).permute(0, 2, 1, 3)                                   # [B, Hq, T, d]
+    tk = torch.from_numpy(k).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)       # [B, Hq, n, d]
+    tv = torch.from_numpy(v).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    mask = torch.zeros((T, n), dtype=torch.bool)
+    for j in range(T):
+        mask[j, : n - T + j + 1] = True
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask).permute(0, 2, 1, 3).numpy()
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
+    # every query adds one unit of weight per head; the last position is seen by the last query alone
+    assert np.allclose(c.score.sum(axis=1), T * Hq, rtol=1e-12)
+    assert np.all(c.score[:, n - 1] < Hq)
