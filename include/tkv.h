@@ -161,6 +161,14 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
  * ESTATE on an empty layer. */
 tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream);
 
+/* The same for n_q query tokens per sequence at once (a chunk of drafted or prompt tokens whose rows have been
+ * appended): q device [batch, n_q, n_q_heads, head_dim], out the same shape.  Query j belongs to position
+ * n - n_q + j of the layer's n positions and attends to the positions up to and including its own (Eq. 2 sums
+ * i = 1..t for the token at t); each query adds its weights to the scores (Eq. 1), in the order j = 0 .. n_q-1, which
+ * is what n_q single-token steps would have done.  One launch of the decode kernels per query token: the cache is
+ * read n_q times.  ESTATE unless all n_q positions were appended after the last tkv_migrate (they are then in T0). */
+tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q, void* out, int32_t n_q, void* hip_stream);
+
 /* One decode step of Algorithm 1's loop body for all layers, in layer order: for every layer l,
  * tkv_append(l, k_all[l], v_all[l], 1) then tkv_attend_and_score(l, q_all[l], out_all[l]).  Device pointers:
  * k_all, v_all [n_layers, batch, 1, n_kv_heads, head_dim] kv_dtype; q_all [n_layers, batch, n_q_heads, head_dim]

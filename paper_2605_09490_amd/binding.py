@@ -64,6 +64,7 @@ SYMBOLS = {
     "tkv_destroy": (None, [_VP]),
     "tkv_append": (C.c_int, [_VP, _I32, _VP, _VP, _I32, _VP]),
     "tkv_attend_and_score": (C.c_int, [_VP, _I32, _VP, _VP, _VP]),
+    "tkv_attend_and_score_chunk": (C.c_int, [_VP, _I32, _VP, _VP, _I32, _VP]),
     "tkv_decode_step": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _VP]),
     "tkv_set_profile": (C.c_int, [_VP, _I32]),
     "tkv_classify": (C.c_int, [_VP, C.POINTER(tkv_policy), _VP]),
@@ -220,6 +221,16 @@ class TieredKV:
         self._check(self.lib.tkv_attend_and_score(self._h, layer, self._dev_tensor(q, (B, Hq, D)),
                                                   self._dev_tensor(out, (B, Hq, D), self.out_torch_dtype),
                                                   self._stream(stream)))
+        return out
+
+    def attend_and_score_chunk(self, layer, q, out=None, stream=None):
+        L, B, Hq, Hkv, D = self.shape
+        n_q = int(q.shape[1])
+        if out is None:
+            out = torch.empty((B, n_q, Hq, D), dtype=self.out_torch_dtype, device=self.device)
+        self._check(self.lib.tkv_attend_and_score_chunk(self._h, layer, self._dev_tensor(q, (B, n_q, Hq, D)),
+                                                        self._dev_tensor(out, (B, n_q, Hq, D), self.out_torch_dtype),
+                                                        n_q, self._stream(stream)))
         return out
 
     def decode_step(self, k_all, v_all, q_all, out_all=None, stream=None):

@@ -466,7 +466,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   QRegs<D, G, M, KT> q;
   {
     constexpr int qes = QBF ? 2 : 4;
-    const char* qb = (const char*)a.q + (size_t)(b * a.Hq + kvh * G) * D * qes;
+    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + kvh * G) * D * qes;
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -768,10 +768,10 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
   int nF, nQ, xsb = 0;
   if (!a.second) {
     if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
-    else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+    else { nF = a.cnt[b * CNT_N + C_NF] - a.trim; nQ = a.cnt[b * CNT_N + C_NQ]; }
   } else {
     nF = a.cnt[b * CNT_N + C_NS]; nQ = 0;
-    xsb = ((a.cnt[b * CNT_N + C_NF] + 63) >> 6) + ((a.cnt[b * CNT_N + C_NQ] + 63) >> 6);
+    xsb = ((a.cnt[b * CNT_N + C_NF] - a.trim + 63) >> 6) + ((a.cnt[b * CNT_N + C_NQ] + 63) >> 6);
   }
   const int nft = (nF + 63) >> 6, nqt = (nQ + 63) >> 6;
   const int nwv = a.S * NW;
@@ -884,7 +884,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   const int t = threadIdx.x, b = blockIdx.y;
   int nF, nQ, nS;
   if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
-  else { nF = a.cnt[b * CNT_N + C_NF]; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  else { nF = a.cnt[b * CNT_N + C_NF] - a.trim; nQ = a.cnt[b * CNT_N + C_NQ]; }
   nS = a.s_pos ? a.cnt[b * CNT_N + C_NS] : 0;
   // logits columns: F tiles, Q tiles, then (streamed T1) the T1 list's tiles
   const int cf = (nF + TB - 1) / TB, cq = (nQ + TB - 1) / TB, ns = a.S_total;
@@ -977,7 +977,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 #pragma unroll
       for (int g2 = 1; g2 < NSG; ++g2) tot += sm_pm[g2 * D + d];
       tot *= IL[hq];
-      const size_t oi = ((size_t)b * a.Hq + hq) * D + d;
+      const size_t oi = ((size_t)b * a.o_bs + hq) * D + d;
       if (a.out_kind == KT_BF16) ((uint16_t*)a.out)[oi] = f32_to_bf16(tot);
       else if (a.out_kind == KT_F16) ((_Float16*)a.out)[oi] = (_Float16)tot;    // round to nearest even
       else ((float*)a.out)[oi] = tot;

@@ -41,6 +41,7 @@ struct tkv_cache {
   // host mirrors
   std::vector<int> len;            // tokens appended per layer
   int n_assigned = 0;              // positions that own a slot
+  int n_at_plan = 0;               // n_assigned when the last plan was applied (later positions are T0, the tail of list F)
   std::vector<int> nF, nQ, free0, free1, free2, pend;  // per sequence
   std::vector<int64_t> ntier;      // [4] summed over sequences
   bool plan_pending = false;
@@ -544,12 +545,11 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
   return TKV_OK;
 }
 
-tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream) {
-  if (!c) return TKV_EINVAL;
-  if (layer < 0 || layer >= c->cfg.n_layers || !q || !out) return fail(c, TKV_EINVAL, "tkv_attend_and_score: bad argument");
-  if (c->len[layer] == 0) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d is empty", layer);
-  if (c->len[layer] != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d has %d tokens, %d are assigned; append first", layer, c->len[layer], c->n_assigned);
-  hipStream_t st = (hipStream_t)hip_stream;
+// One query token per sequence against one layer.  trim: entries at the end of list F to leave out (later tokens of a
+// chunk); q_bs / o_bs: query heads between consecutive sequences in q / out; last: the layer's last call of this step
+// (the streamed frame is released and refilled, queued transfers are pumped).
+static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* out, int trim, int q_bs, int o_bs, bool last,
+                             hipStream_t st) {
   const DevView& v = c->dv;
   bool use_old = false;
   const int fr = layer & 1;
@@ -582,7 +582,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   auto tiles = [](int n) { return (n + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK; };
   int n_tiles = 1, n_tiles_s = 0;
   for (int b = 0; b < v.B; ++b) {
-    n_tiles = std::max(n_tiles, tiles(c->nF[b]) + tiles(c->nQ[b]) + tiles(c->nS[b]));
+    n_tiles = std::max(n_tiles, tiles(c->nF[b] - trim) + tiles(c->nQ[b]) + tiles(c->nS[b]));
     n_tiles_s = std::max(n_tiles_s, tiles(c->nS[b]));
   }
   if (n_tiles * TOK_PER_BLOCK > c->xs_stride) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal tile count %d exceeds the scratch", n_tiles);
@@ -602,12 +602,13 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   a.q_es = c->es;
   if (v.B <= ATTN_ARG_SEQS)
     for (int b = 0; b < v.B; ++b) {
-      a.nF[b] = c->nF[b]; a.nQ[b] = c->nQ[b];
-      a.nWq[b] = attn_q_waves(S * nw, tiles(c->nF[b]), tiles(c->nQ[b]));
+      a.nF[b] = c->nF[b] - trim; a.nQ[b] = c->nQ[b];
+      a.nWq[b] = attn_q_waves(S * nw, tiles(c->nF[b] - trim), tiles(c->nQ[b]));
     }
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capP; a.cap2 = v.cap2;
   a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_kind = c->cfg.out_dtype;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
+  a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim;
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
   if (c->cfg.profile) {
@@ -632,6 +633,7 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
     HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->kt, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
+  if (!last) return TKV_OK;
   if (c->streamed && S2 > 0) {
     HIPCHK(c, hipEventRecord(c->ev_free[fr], st));
     c->frame_used[fr] = true;
@@ -644,6 +646,32 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   // lazy mode spreads the issue of a re-tiering event's copies over the following attention calls, one layer each,
   // so the compute stream is never left empty while the host queues them
   if (c->jobs_next < c->jobs.size()) return pump_transfers(c, 1);
+  return TKV_OK;
+}
+
+tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers || !q || !out) return fail(c, TKV_EINVAL, "tkv_attend_and_score: bad argument");
+  if (c->len[layer] == 0) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d is empty", layer);
+  if (c->len[layer] != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d has %d tokens, %d are assigned; append first", layer, c->len[layer], c->n_assigned);
+  return attend_one(c, layer, q, out, 0, c->dv.Hq, c->dv.Hq, true, (hipStream_t)hip_stream);
+}
+
+tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q, void* out, int32_t n_q, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers || !q || !out || n_q < 1) return fail(c, TKV_EINVAL, "tkv_attend_and_score_chunk: bad argument");
+  if (c->len[layer] == 0) return fail(c, TKV_ESTATE, "tkv_attend_and_score_chunk: layer %d is empty", layer);
+  if (c->len[layer] != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_attend_and_score_chunk: layer %d has %d tokens, %d are assigned; append first", layer, c->len[layer], c->n_assigned);
+  // the chunk's positions must be the tail of list F: appended since the last plan was applied, so still in T0
+  if (n_q > c->n_assigned - c->n_at_plan)
+    return fail(c, TKV_ESTATE, "tkv_attend_and_score_chunk: %d query tokens, but only %d positions were appended since the last tkv_migrate", n_q, c->n_assigned - c->n_at_plan);
+  const DevView& v = c->dv;
+  const size_t q_tok = (size_t)v.Hq * v.D * c->es, o_tok = (size_t)v.Hq * v.D * (c->cfg.out_dtype == TKV_F32 ? 4 : 2);
+  for (int j = 0; j < n_q; ++j) {
+    tkv_status s = attend_one(c, layer, (const char*)q + j * q_tok, (char*)out + j * o_tok, n_q - 1 - j, n_q * v.Hq, n_q * v.Hq,
+                              j == n_q - 1, (hipStream_t)hip_stream);
+    if (s != TKV_OK) return s;
+  }
   return TKV_OK;
 }
 
@@ -816,6 +844,7 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     c->host_next += total_new_t1;
   }
   c->plan_pending = false;
+  c->n_at_plan = n;
   c->st.n_migrate++;
   c->st.migrate_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
   return TKV_OK;

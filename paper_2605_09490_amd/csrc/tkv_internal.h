@@ -97,6 +97,9 @@ struct AttnArgs {
   const int* s_pos; // [B][Nmax] positions of the T1 list (streamed T1), for the finishing kernel
   const float* vnorm; // [B][Hkv][Nmax] this layer's value-row norms (value-aware scorer), else NULL
   int n_tiles;      // max over the sequences of F tiles + Q tiles (+ T1 tiles)
+  int q_bs, o_bs;   // query heads between consecutive sequences in q and in out: Hq, or n_q * Hq for one token of a chunk
+  int trim;         // entries at the end of list F this call leaves out (the chunk's later tokens); nF[] has them
+                    // taken off already, the device counter has not
   int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_kind, q_es;   // out_kind: 0 binary32, 1 bfloat16, 2 binary16
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS

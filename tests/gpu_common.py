@@ -44,6 +44,11 @@ class Pair:
         ref = self.orc.attend_and_score(layer, to_f64(q))
         return to_f64(out), ref
 
+    def attend_chunk(self, layer, q):
+        out = self.gpu.attend_and_score_chunk(layer, q)
+        ref = self.orc.attend_and_score_chunk(layer, to_f64(q))
+        return to_f64(out), ref
+
     def force_tiers(self, tiers):
         self.gpu.set_tiers(tiers)
         self.gpu.migrate()

@@ -612,6 +612,51 @@ def test_value_aware_scorer_whole_steps_and_classify():
     p.close()
 
 
+@pytest.mark.parametrize("mode,kv_dtype,D,Hq,Hkv,t2,scorer,batch", [
+    ("lazy", "bf16", 128, 10, 2, "int8_row", "attention", 2),
+    ("stream", "bf16", 128, 10, 2, "int4_g32", "attention", 2),
+    ("wait", "f32", 64, 8, 2, "int8_row", "vatp", 2),
+    ("lazy", "f16", 128, 7, 1, "int8_row", "attention", 3),
+    ("lazy", "bf16", 64, 2, 1, "int8_row", "attention", 66),      # list lengths from the device counters
+])
+def test_chunks_of_query_tokens(mode, kv_dtype, D, Hq, Hkv, t2, scorer, batch):
+    """Several query tokens per sequence at once: chunks of 6, 1 and 9 tokens appended to every layer and attended
+    causally (query j sees the positions up to its own), over a cache with all four tiers; every query's output and
+    the scores at the end against the oracle.  With 9 tokens the chunk crosses a 64-entry tile boundary of list F
+    for at least one query.  A chunk that reaches behind the last migrate is refused."""
+    import paper_2605_09490_amd as tkv
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=2, batch=batch, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+                       context=200 if batch > 8 else 450, decode_steps=16, t2_format=t2, sigma=1.0)
+    p = _pair(cfg, prefetch_mode=mode, scorer=scorer)
+    rng = np.random.default_rng(31)
+    n = cfg.context
+    tiers = _random_tiers(rng, cfg.batch, n, frac=(0.35, 0.3, 0.25, 0.1), protect=(4, 8))
+    p.force_tiers(tiers)
+    calls, step = 0, 0
+    for T in (6, 1, 9):
+        for l in range(cfg.n_layers):
+            ks, vs = zip(*[p.wl.step_kv(step + j, l) for j in range(T)])
+            p.append(l, torch.cat(ks, dim=1), torch.cat(vs, dim=1))
+        for l in range(cfg.n_layers):
+            q = torch.stack([p.wl.step_q(step + j, l) for j in range(T)], dim=1).contiguous()
+            print(f"[case] chunk T={T} layer {l} n={n + T}", flush=True)
+            got, ref = p.attend_chunk(l, q)
+            calls += T
+            for j in range(T):
+                assert_out_close(got[:, j], ref[:, j], kv_dtype, f"chunk {T} layer {l} query {j}")
+        step += T
+        n += T
+    mass = _mass(cfg, calls) * (20.0 if scorer == "vatp" else 1.0)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, mass)
+    # 16 positions were appended since the plan: a chunk of 17 would reach into re-tiered positions
+    q17 = torch.zeros((cfg.batch, 17, Hq, D), dtype=q.dtype, device=q.device)
+    with pytest.raises(tkv.TkvError) as e:
+        p.gpu.attend_and_score_chunk(0, q17)
+    assert e.value.status == tkv.TKV_ESTATE
+    p.close()
+
+
 def test_streamed_t1_with_a_sequence_that_has_no_t1_rows():
     """Streamed T1 where one sequence keeps nothing in T1 (its share of the second attention launch has no tiles and
     must contribute neutral partials) and the other keeps nothing in T2."""

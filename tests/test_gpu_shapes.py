@@ -151,6 +151,45 @@ def test_14b_full_depth_score_mass():
     gpu.close()
 
 
+def test_14b_shape_chunk_of_four_query_tokens():
+    """Four query tokens per sequence at the 14B per-layer shape (two layers), after one decode step and a
+    re-tiering: every query's output and the scores against the oracle; prints the time of the chunk call."""
+    from gpu_common import Pair, assert_out_close, assert_scores_close, to_f64
+    cfg = dataclasses.replace(CONFIGS["14b"], n_layers=2, decode_steps=5)
+    print(f"[case] 14b-shaped chunk L={cfg.n_layers} B={cfg.batch} ctx={cfg.context}", flush=True)
+    p = Pair(cfg, prefetch_mode="lazy")
+    L, T = cfg.n_layers, 4
+    k_all, v_all, q_all = p.wl.decode_inputs(0, 1 + T)
+    p.gpu.decode_step(k_all[0], v_all[0], q_all[0])
+    for l in range(L):
+        p.orc.append(l, to_f64(k_all[0, l]), to_f64(v_all[0, l]))
+        p.orc.attend_and_score(l, to_f64(q_all[0, l]))
+    n = p.gpu.layer_length(0)
+    p.gpu.classify(cfg.policy_ppm)
+    plan = p.gpu.get_pending_tiers()[:, :n]
+    p.gpu.migrate()
+    p.orc.set_tiers(plan); p.orc.migrate()
+    p.gpu.wait_prefetch()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for l in range(L):
+        k = torch.cat([k_all[1 + j, l] for j in range(T)], dim=1)          # [B, T, Hkv, D]
+        v = torch.cat([v_all[1 + j, l] for j in range(T)], dim=1)
+        p.append(l, k, v)
+    for l in range(L):
+        q = torch.stack([q_all[1 + j, l] for j in range(T)], dim=1).contiguous()
+        ev0.record()
+        out = p.gpu.attend_and_score_chunk(l, q)
+        ev1.record()
+        ref = p.orc.attend_and_score_chunk(l, to_f64(q))
+        torch.cuda.synchronize()
+        print(f"[case] layer {l}: chunk of {T} took {ev0.elapsed_time(ev1) * 1e3:.1f} us", flush=True)
+        for j in range(T):
+            assert_out_close(to_f64(out[:, j]), ref[:, j], cfg.kv_dtype, f"layer {l} query {j}")
+    ss = 1.0 / (cfg.n_layers * cfg.n_q_heads)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n + T, (1 + T) * L * cfg.n_q_heads * ss)
+    p.close()
+
+
 def test_14b_shape_streamed_t1():
     """The 14B per-layer shape with streamed T1 (three layers, so a frame is refilled while the other is read): all
     outputs and scores against the oracle."""
