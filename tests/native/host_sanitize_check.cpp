@@ -112,6 +112,12 @@ static void run_mode(int mode) {
               (long long)st.n_migrate, (long long)st.n_rehome, (long long)st.host_rows_used, (long long)st.h2d_bytes,
               (long long)st.d2h_bytes);
   CHECK(st.n_rehome >= 1);
+  // two query tokens per sequence at once, over two positions appended after the last migrate
+  for (int l = 0; l < L; ++l) OK(tkv_append(c, l, dk, dv, 2, nullptr));
+  for (int l = 0; l < L; ++l) OK(tkv_attend_and_score_chunk(c, l, dq, dout, 2, nullptr));
+  CHECK(tkv_attend_and_score_chunk(c, 0, dq, dout, 3, nullptr) == TKV_ESTATE);
+  CHECK(tkv_attend_and_score_chunk(c, 0, dq, dout, 0, nullptr) == TKV_EINVAL);
+  OK(tkv_get_scores(c, scores.data()));
   // error paths on a live handle
   CHECK(tkv_attend_and_score(c, 99, dq, dout, nullptr) == TKV_EINVAL);
   CHECK(tkv_migrate(c, nullptr) == TKV_ESTATE);
