@@ -657,6 +657,44 @@ def test_chunks_of_query_tokens(mode, kv_dtype, D, Hq, Hkv, t2, scorer, batch):
     p.close()
 
 
+@pytest.mark.parametrize("mix,mode", [("all_t2", "lazy"), ("all_t3", "wait"), ("all_t1", "wait"), ("all_t1", "stream"),
+                                      ("all_t3", "stream"), ("mixed_per_sequence", "lazy")])
+def test_degenerate_tier_mixes(mix, mode):
+    """Plans at the edges: every unprotected position compressed, evicted or offloaded (list F, or list Q, then holds
+    next to nothing: some workgroups have no tile at all), and a batch whose sequences each sit at a different edge.
+    Outputs and scores against the oracle over three decode steps, then everything that can return goes back to T0."""
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=2, batch=3, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=390,
+                       decode_steps=3, sigma=1.0)
+    p = _pair(cfg, prefetch_mode=mode)
+    n = cfg.context
+    tiers = np.zeros((cfg.batch, n), np.uint8)
+    inner = slice(2, n - 3)
+    if mix == "mixed_per_sequence":
+        tiers[0, inner], tiers[1, inner], tiers[2, inner] = 2, 3, 1
+    else:
+        tiers[:, inner] = {"all_t2": 2, "all_t3": 3, "all_t1": 1}[mix]
+    p.force_tiers(tiers)
+    calls = 0
+    for step in range(cfg.decode_steps):
+        for l in range(cfg.n_layers):
+            p.append(l, *p.wl.step_kv(step, l))
+            got, ref = p.attend(l, p.wl.step_q(step, l))
+            calls += 1
+            assert_out_close(got, ref, "bf16", f"{mix} step {step} layer {l}")
+    n += cfg.decode_steps
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _mass(cfg, calls))
+    back = np.zeros((cfg.batch, n), np.uint8)
+    back[:, :cfg.context] = np.where(tiers == 3, 3, 0)
+    p.force_tiers(back)
+    for l in range(cfg.n_layers):
+        got, ref = p.attend(l, p.wl.step_q(0, l))
+        assert_out_close(got, ref, "bf16", f"{mix} back in T0, layer {l}")
+    st = p.gpu.get_stats()
+    assert st["tier_count"][1] == 0 and st["tier_count"][2] == 0
+    p.close()
+
+
 def test_streamed_t1_with_a_sequence_that_has_no_t1_rows():
     """Streamed T1 where one sequence keeps nothing in T1 (its share of the second attention launch has no tiles and
     must contribute neutral partials) and the other keeps nothing in T2."""
