@@ -68,7 +68,9 @@ typedef enum { TKV_T2_INT8_ROW = 0, TKV_T2_INT4_G32 = 1 } tkv_t2_format;
  *        all layers, and every tkv_attend_and_score reads its layer's T1 rows from a frame that was refilled from the
  *        pinned store (hipMemcpyAsync on the prefetch stream, event-ordered) while the previous layers were attended.
  *        HBM then holds T0, T2 and two frames; every decode step moves all of T1 over the host link (and the rows of
- *        the pinned store whose positions have left T1 since the store was last rewritten). */
+ *        the pinned store whose positions have left T1 since the store was last rewritten; tkv_migrate rewrites it
+ *        packed, beside the frame pass it makes anyway, when those rows would cost more link time until the next
+ *        plan than the rewrite). */
 typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1, TKV_PREFETCH_STREAM = 2 } tkv_prefetch_mode;
 
 /* What a layer call adds to the cumulative score of a position:
@@ -137,6 +139,8 @@ typedef struct {
   int64_t n_classify, n_migrate;
   int64_t n_rehome;           /* times the pinned T1 store ran full and was rewritten, packed, from the staged copies */
   int64_t host_rows_used;     /* rows of the pinned T1 store handed out since the last rewrite (all sequences) */
+  int64_t n_repack;           /* streamed T1: plans during which the store was rewritten packed because its stale rows
+                                 (positions no longer in T1) would have cost more link time than the rewrite */
   int64_t device_bytes;       /* device memory the cache holds (pools, frames, lists, scratch) */
   int64_t pinned_bytes;       /* pinned host memory the cache holds */
 } tkv_stats;

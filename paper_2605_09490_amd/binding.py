@@ -53,7 +53,7 @@ class tkv_stats(C.Structure):
         ("attn_kernel_ms", C.c_double), ("attn_kernel_launches", C.c_int64),
         ("classify_ms", C.c_double), ("migrate_ms", C.c_double),
         ("attend_waits", C.c_int64), ("lazy_old_reads", C.c_int64), ("n_classify", C.c_int64), ("n_migrate", C.c_int64),
-        ("n_rehome", C.c_int64), ("host_rows_used", C.c_int64), ("device_bytes", C.c_int64), ("pinned_bytes", C.c_int64),
+        ("n_rehome", C.c_int64), ("host_rows_used", C.c_int64), ("n_repack", C.c_int64), ("device_bytes", C.c_int64), ("pinned_bytes", C.c_int64),
     ]
 
 

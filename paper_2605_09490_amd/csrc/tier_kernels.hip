@@ -751,6 +751,52 @@ hipError_t launch_rehome(const DevView& v, int n, hipStream_t st) {
   hipLaunchKernelGGL(k_rehome, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n);
   return hipGetLastError();
 }
+// Streamed T1, a plan that retires T1 rows: the pinned store is rewritten packed while the plan is applied.  After
+// plan_commit, number the positions T1 holds now 0, 1, ... per sequence in position order (base2[b] first) and list
+// where each one's bits are: in its staging slot of the layer's frame (it was in T1 before, or it returns to T1 with a
+// valid host copy), or, for a row that enters with this plan, in the HBM slot plan_commit noted in its move list.
+__global__ __launch_bounds__(PLAN_THREADS) void k_repack_number(DevView v, int n, const int* __restrict__ base2,
+                                                                int* __restrict__ g2_seq, int* __restrict__ g2_src,
+                                                                int* __restrict__ hloc2) {
+  __shared__ unsigned long long wsum[PLAN_THREADS / 64][4];
+  const int b = blockIdx.x, t = threadIdx.x;
+  const size_t o = (size_t)b * v.Nmax;
+  const int hbase = base2[b];
+  int run = 0;
+  for (int base = 0; base < n; base += PLAN_THREADS) {
+    const int i = base + t;
+    const bool in = i < n;
+    const bool f = in && v.tier[o + i] == 1;
+    Pack4 pk;
+    pk.p[0] = (unsigned long long)f; pk.p[1] = 0; pk.p[2] = 0; pk.p[3] = 0;
+    Pack4 tot;
+    const Pack4 ex = block_excl_scan<PLAN_THREADS>(pk, tot, wsum);
+    if (in) {
+      int hl = -1;
+      if (f) {
+        hl = hbase + run + fld(ex.p[0], 0);
+        const int oldh = v.hloc[o + i];
+        g2_seq[hl] = b;
+        g2_src[hl] = oldh >= v.event_base ? v.g_src[oldh - v.event_base] : v.loc[o + i];
+      }
+      hloc2[o + i] = hl;
+    }
+    run += fld(tot.p[0], 0);
+  }
+}
+__global__ void k_repack_apply(DevView v, int n, const int* __restrict__ hloc2) {
+  const int b = blockIdx.y, i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) v.hloc[(size_t)b * v.Nmax + i] = hloc2[(size_t)b * v.Nmax + i];
+}
+hipError_t launch_repack_number(const DevView& v, int n, const int* base2, int* g2_seq, int* g2_src, int* hloc2, hipStream_t st) {
+  hipLaunchKernelGGL(k_repack_number, dim3(v.B), dim3(PLAN_THREADS), 0, st, v, n, base2, g2_seq, g2_src, hloc2);
+  return hipGetLastError();
+}
+hipError_t launch_repack_apply(const DevView& v, int n, const int* hloc2, hipStream_t st) {
+  hipLaunchKernelGGL(k_repack_apply, dim3((n + 255) / 256, v.B), dim3(256), 0, st, v, n, hloc2);
+  return hipGetLastError();
+}
+
 // streamed T1, after a re-homing: the table of host rows, rebuilt from the positions' new host rows
 __global__ void k_htable_clear(DevView v, int rows) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;

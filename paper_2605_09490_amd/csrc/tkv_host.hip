@@ -63,8 +63,11 @@ struct tkv_cache {
   size_t bounce_bytes = 0;
   bool transfers_in_flight = false;
   int* pin_cnt = nullptr;          // pinned [B][CNT_N]
-  int* pin_base = nullptr;         // pinned [B]
+  int* pin_base = nullptr;         // pinned [2][B]: first host row per sequence for plan_commit; for a repack
   int* d_host_base = nullptr;
+  // streamed T1, repack while a plan is applied: new numbering and gather lists, frame hand-back events
+  int* d_base2 = nullptr; int* g2_seq = nullptr; int* g2_src = nullptr; int* hloc2 = nullptr;
+  hipEvent_t ev_gath[2] = {nullptr, nullptr};
   // streamed T1: two frames, the layer each holds (-1: none), fill / release events
   bool streamed = false;
   char* frameK[2] = {nullptr, nullptr}; char* frameV[2] = {nullptr, nullptr};
@@ -454,6 +457,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
     for (int f = 0; f < 2; ++f) ok = ok && dalloc(c, c->frameK[f], frame_bytes) && dalloc(c, c->frameV[f], frame_bytes);
     ok = ok && dalloc(c, v.s_pos, BN) && dalloc(c, v.s_loc, BN) && dalloc(c, v.h_clr, BN);
     ok = ok && dalloc(c, v.h_seq, (size_t)c->host_rows) && dalloc(c, v.h_dst, (size_t)c->host_rows);
+    ok = ok && dalloc(c, c->d_base2, (size_t)B) && dalloc(c, c->g2_seq, BN) && dalloc(c, c->g2_src, BN) && dalloc(c, c->hloc2, BN);
     if (ok && (hipMemset(v.h_seq, 0xFF, (size_t)c->host_rows * sizeof(int)) != hipSuccess ||
                hipMemset(v.h_dst, 0xFF, (size_t)c->host_rows * sizeof(int)) != hipSuccess))
       return die(TKV_EDEVICE, "tkv_create: state initialisation failed");
@@ -462,7 +466,7 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   if (ok) {
     c->hstore = (char*)pin_alloc(c, (size_t)L * c->host_rows * c->tok_bytes);
     c->pin_cnt = (int*)pin_alloc(c, (size_t)B * CNT_N * sizeof(int));
-    c->pin_base = (int*)pin_alloc(c, (size_t)B * sizeof(int));
+    c->pin_base = (int*)pin_alloc(c, (size_t)2 * B * sizeof(int));
     ok = c->hstore && c->pin_cnt && c->pin_base;
   }
   if (!ok) return die(TKV_ENOMEM, "tkv_create: an allocation failed");
@@ -483,7 +487,8 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   for (int l = 0; l < L && evok; ++l) evok = hipEventCreateWithFlags(&c->ev_ready[l], hipEventDisableTiming) == hipSuccess;
   for (int f = 0; f < 2 && evok && c->streamed; ++f)
     evok = hipEventCreateWithFlags(&c->ev_filled[f], hipEventDisableTiming) == hipSuccess &&
-           hipEventCreateWithFlags(&c->ev_free[f], hipEventDisableTiming) == hipSuccess;
+           hipEventCreateWithFlags(&c->ev_free[f], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&c->ev_gath[f], hipEventDisableTiming) == hipSuccess;
   for (int i = 0; i < RING && evok && c->streamed; ++i)
     evok = hipEventCreateWithFlags(&c->ev_h2d[i], hipEventDisableTiming) == hipSuccess &&
            hipEventCreateWithFlags(&c->ev_scat[i], hipEventDisableTiming) == hipSuccess;
@@ -509,6 +514,7 @@ void tkv_destroy(tkv_cache* c) {
   for (auto e : c->ev_ready) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_filled) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_free) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_gath) if (e) (void)hipEventDestroy(e);
   for (auto& p : c->copy_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (auto& p : c->prof_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (void* p : c->dev_allocs) { if (c->cfg.dev_free) c->cfg.dev_free(p, c->cfg.alloc_ctx); else (void)hipFree(p); }
@@ -776,17 +782,88 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
     // (the table of host rows still names them; they are struck from it afterwards).  Rows that come out of T2 and
     // rows that only move inside HBM do not need the frames.
     HIPCHK(c, launch_decode_moves(v, maxd, st));
-    int64_t from_t1 = 0;
+    int64_t from_t1 = 0, leaving = 0, live1 = 0, new_total = 0;
     int max_leaving = 0;
     for (int b = 0; b < B; ++b) {
       const int* k = c->pin_cnt + b * CNT_N;
       from_t1 += k[C_M10] + k[C_M12];
+      leaving += k[C_M10] + k[C_M12] + k[C_M13];
+      live1 += k[C_N1];
       max_leaving = std::max(max_leaving, k[C_M10] + k[C_M12] + k[C_M13]);
+      c->pin_base[B + b] = (int)new_total; new_total += k[C_P1];
     }
     c->frame_layer[0] = c->frame_layer[1] = -1;
-    if (from_t1 == 0) {
+    // Rows of the pinned store whose position is not in T1 any more cross the link at every later step for nothing.
+    // Rewriting the store packed costs about one copy of T1 (device to host, beside this migrate's fills); it pays
+    // when the stale rows, over the steps until the next plan (taken to be as many as since the last one), would
+    // cost more.
+    const int64_t stale_after = (c->host_next - live1) + leaving;
+    const int64_t steps_between = std::max(1, n - c->n_at_plan);
+    if (max_leaving > 0 && stale_after * steps_between >= new_total) {
+      // The store is rewritten while the plan is applied: every layer passes through a frame (the rows that leave
+      // T1 for T0 or T2 are read from it); behind the movers the offload stream gathers the layer's new T1 set (rows
+      // that stay, from the frame; rows that enter, from their HBM slots) in the new order and copies it over the
+      // layer's part of the store, which the fill has finished reading by then.
+      HIPCHK(c, hipMemcpyAsync(c->d_base2, c->pin_base + B, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, launch_repack_number(v, n, c->d_base2, c->g2_seq, c->g2_src, c->hloc2, st));
+      HIPCHK(c, hipEventRecord(c->ev_plan, st));
+      HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_plan, 0));
+      HIPCHK(c, hipStreamWaitEvent(c->sA, c->ev_plan, 0));
+      const size_t slot_bytes = c->bounce_bytes / RING;
+      const int64_t piece_rows = std::max<int64_t>(1, (int64_t)(slot_bytes / c->tok_bytes));
+      int piece = 0;
+      for (int l = 0; l < L; ++l) {
+        const int f = l & 1;
+        tkv_status fs = issue_fill(c, l, f);
+        if (fs != TKV_OK) return fs;
+        DevView vv = v;
+        vv.frK = c->frameK[f]; vv.frV = c->frameV[f];
+        if (from_t1 > 0) {
+          HIPCHK(c, hipStreamWaitEvent(st, c->ev_filled[f], 0));
+          HIPCHK(c, launch_moves_layer(vv, l, max10, maxq, st));
+        }
+        HIPCHK(c, hipStreamWaitEvent(c->sA, c->ev_filled[f], 0));
+        DevView vg = vv;
+        vg.g_seq = c->g2_seq; vg.g_src = c->g2_src;
+        EvPair* ed = next_pair(c->copy_events, c->copy_events_used);
+        if (!ed) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+        ed->dir = 0; ed->bytes = 0;
+        HIPCHK(c, hipEventRecord(ed->a, c->sA));
+        for (int64_t r0 = 0; r0 < new_total; r0 += piece_rows, ++piece) {
+          const int nrows = (int)std::min<int64_t>(piece_rows, new_total - r0);
+          const size_t bytes = (size_t)nrows * c->tok_bytes;
+          char* ba = c->bounceA + (size_t)(piece % RING) * slot_bytes;   // one stream: a ring slot is refilled after its copy
+          HIPCHK(c, launch_gather(vg, l, (int)r0, nrows, ba, c->sA));
+          if (r0 + piece_rows >= new_total) HIPCHK(c, hipEventRecord(c->ev_gath[f], c->sA));   // the frame has been read
+          HIPCHK(c, hipMemcpyAsync(c->hstore + ((size_t)l * c->host_rows + (size_t)r0) * c->tok_bytes, ba, bytes,
+                                   hipMemcpyDeviceToHost, c->sA));
+          c->st.d2h_bytes += (int64_t)bytes; c->st.d2h_copies++;
+        }
+        if (new_total == 0) HIPCHK(c, hipEventRecord(c->ev_gath[f], c->sA));
+        HIPCHK(c, hipEventRecord(ed->b, c->sA));
+        HIPCHK(c, hipEventRecord(c->ev_ready[l], c->sA));       // the layer's next fill waits for its part of the store
+        c->layer_wait[l] = 1; c->layer_enq[l] = 1;
+        HIPCHK(c, hipStreamWaitEvent(st, c->ev_gath[f], 0));
+        HIPCHK(c, hipEventRecord(c->ev_free[f], st));
+        c->frame_used[f] = true;
+      }
+      if (from_t1 == 0) HIPCHK(c, launch_moves(v, max10, maxq, 0, st));
+      // the new numbering takes over: the fills above went by the old table, the next ones go by the new one
+      for (int f = 0; f < 2; ++f) HIPCHK(c, hipStreamWaitEvent(st, c->ev_filled[f], 0));
+      HIPCHK(c, launch_repack_apply(v, n, c->hloc2, st));
+      HIPCHK(c, launch_rebuild_htable(v, n, (int)c->host_rows, st));
+      for (int f = 0; f < 2; ++f) HIPCHK(c, hipEventRecord(c->ev_free[f], st));
+      c->frame_layer[0] = c->frame_layer[1] = -1;
+      c->host_next = new_total;
+      c->transfers_in_flight = true;
+      c->st.n_repack++;
+      total_new_t1 = 0;                 // the rows that enter T1 went to the store with the rest
+    } else if (from_t1 == 0) {
       HIPCHK(c, launch_moves(v, max10, maxq, 0, st));
+      HIPCHK(c, launch_clear_host_rows(v, max_leaving, st));
     } else {
+      // the rows that leave T1 for T0 or T2 are read from a frame, layer by layer; the table of host rows still names
+      // them and they are struck from it afterwards
       HIPCHK(c, hipEventRecord(c->ev_plan, st));
       HIPCHK(c, hipStreamWaitEvent(c->sB, c->ev_plan, 0));
       for (int l = 0; l < L; ++l) {
@@ -801,8 +878,8 @@ tkv_status tkv_migrate(tkv_cache* c, void* hip_stream) {
         c->frame_used[f] = true;
       }
       c->frame_layer[0] = c->frame_layer[1] = -1;   // the frames hold the rows of the old plan
+      HIPCHK(c, launch_clear_host_rows(v, max_leaving, st));
     }
-    HIPCHK(c, launch_clear_host_rows(v, max_leaving, st));
   }
   // host mirrors of what plan_commit leaves on the device
   for (int t = 0; t < 4; ++t) c->ntier[t] = 0;

@@ -127,6 +127,9 @@ hipError_t launch_decode_moves(const DevView& v, int maxd, hipStream_t st);
 hipError_t launch_clear_host_rows(const DevView& v, int max_leaving, hipStream_t st);
 hipError_t launch_scatter_frame(const DevView& v, int r0, int nrows, const char* bounce, hipStream_t st);
 hipError_t launch_rehome(const DevView& v, int n, hipStream_t st);
+// streamed T1: new packed numbering of the T1 rows of the plan just committed (into g2_seq / g2_src / hloc2), and its adoption
+hipError_t launch_repack_number(const DevView& v, int n, const int* base2, int* g2_seq, int* g2_src, int* hloc2, hipStream_t st);
+hipError_t launch_repack_apply(const DevView& v, int n, const int* hloc2, hipStream_t st);
 hipError_t launch_rebuild_htable(const DevView& v, int n, int rows, hipStream_t st);
 hipError_t launch_gather(const DevView& v, int layer, int r0, int nrows, char* bounce, hipStream_t st);
 hipError_t launch_scatter(const DevView& v, int layer, int r0, int nrows, const char* bounce, hipStream_t st);

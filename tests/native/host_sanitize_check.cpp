@@ -111,7 +111,7 @@ static void run_mode(int mode) {
   std::printf("mode %d: %lld migrates, store rewritten %lld times, %lld rows of it in use, h2d %lld B, d2h %lld B\n", mode,
               (long long)st.n_migrate, (long long)st.n_rehome, (long long)st.host_rows_used, (long long)st.h2d_bytes,
               (long long)st.d2h_bytes);
-  CHECK(st.n_rehome >= 1);
+  CHECK(st.n_rehome + st.n_repack >= 1);
   // two query tokens per sequence at once, over two positions appended after the last migrate
   for (int l = 0; l < L; ++l) OK(tkv_append(c, l, dk, dv, 2, nullptr));
   for (int l = 0; l < L; ++l) OK(tkv_attend_and_score_chunk(c, l, dq, dout, 2, nullptr));
