@@ -582,14 +582,15 @@ def test_value_aware_scorer_walk(mode, kv_dtype, D, Hq, Hkv, t2):
     _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, layers=3, scorer="vatp")
 
 
-def test_value_aware_scorer_whole_steps_and_classify():
+@pytest.mark.parametrize("mode,scorer", [("lazy", "vatp"), ("stream", "vatp"), ("stream", "attention")])
+def test_whole_steps_and_classify(mode, scorer):
     """Whole decode steps (one append launch for all layers, so the norms of the new rows of every layer come from one
     launch) with re-tiering by the value-aware scores: the plan is the oracle's for the GPU's score array, bit for bit,
     and the scores agree with the oracle's to the usual tolerance."""
     from gpu_common import assert_scores_close
     cfg = small_config(n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=700,
                        decode_steps=12, sigma=1.0, k_window=16)
-    p = _pair(cfg, prefetch_mode="lazy", scorer="vatp")
+    p = _pair(cfg, prefetch_mode=mode, scorer=scorer)
     pol = (300000, 400000, 200000, 100000)
     calls = 0
     for step in range(cfg.decode_steps):
@@ -604,14 +605,26 @@ def test_value_aware_scorer_whole_steps_and_classify():
         if step % 4 == 3:
             n = p.gpu.layer_length(0)
             s_gpu = p.gpu.get_scores()
-            assert_scores_close(s_gpu, p.orc.score, n, _mass(cfg, calls) * 20.0, f"step {step}")
+            assert_scores_close(s_gpu, p.orc.score, n, _mass(cfg, calls) * (20.0 if scorer == "vatp" else 1.0), f"step {step}")
             p.gpu.classify(pol)
             plan = p.gpu.get_pending_tiers()[:, :n]
             assert np.array_equal(plan, p.orc.classify(pol, score_f32=s_gpu)[:, :n])
             p.gpu.migrate()
             p.orc.set_tiers(plan); p.orc.migrate()
     # the scores really are not the attention-only ones
-    assert p.orc.score.sum() > 2.0 * cfg.batch * _mass(cfg, calls)
+    if scorer == "vatp":
+        assert p.orc.score.sum() > 2.0 * cfg.batch * _mass(cfg, calls)
+    st = p.gpu.get_stats()
+    print(f"[case] {mode} {scorer}: store rewritten beside a plan {st['n_repack']} times", flush=True)
+    if mode == "stream":
+        # every T1 row of one (layer, sequence, kv head) in the pinned store, bit for bit
+        n = p.gpu.layer_length(0)
+        tiers = p.gpu.get_tiers()[:, :n]
+        for pos in np.nonzero(tiers[1] == 1)[0]:
+            row = p.gpu.get_row(cfg.n_layers - 1, 1, 1, int(pos), 1)
+            row = (row.astype(np.uint32) << 16).view(np.float32)
+            assert np.array_equal(row.astype(np.float64), p.orc.V[cfg.n_layers - 1][1, 1, int(pos)]), pos
+        assert st["n_repack"] >= 1
     p.close()
 
 
