@@ -711,6 +711,49 @@ def test_degenerate_tier_mixes(mix, mode):
     p.close()
 
 
+def test_streamed_t1_store_rewritten_when_t1_rows_are_only_evicted():
+    """Streamed T1, a plan whose only change is that two thirds of T1 are evicted: no row has to be read back through
+    the frames for a mover, but the store is still rewritten packed (its stale rows would outweigh what is left);
+    then a plan that empties T1 altogether.  Outputs, scores and every remaining T1 row's bits in the pinned store."""
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=420,
+                       decode_steps=4, sigma=1.0)
+    p = _pair(cfg, prefetch_mode="stream")
+    rng = np.random.default_rng(41)
+    n = cfg.context
+    tiers = _random_tiers(rng, cfg.batch, n, frac=(0.3, 0.5, 0.2, 0.0))
+    p.force_tiers(tiers)
+    calls = 0
+
+    def step_all(step):
+        nonlocal calls
+        for l in range(cfg.n_layers):
+            p.append(l, *p.wl.step_kv(step, l))
+            got, ref = p.attend(l, p.wl.step_q(step, l))
+            calls += 1
+            assert_out_close(got, ref, "bf16", f"step {step} layer {l}")
+
+    step_all(0)
+    t1 = np.argwhere(tiers == 1)
+    drop = t1[rng.random(len(t1)) < 0.67]
+    tiers2 = np.zeros((cfg.batch, n + 1), np.uint8); tiers2[:, :n] = tiers
+    tiers2[drop[:, 0], drop[:, 1]] = 3
+    p.force_tiers(tiers2)
+    st = p.gpu.get_stats()
+    assert st["n_repack"] == 1 and st["host_rows_used"] == st["tier_count"][1] == int((tiers2 == 1).sum())
+    for pos in np.nonzero(tiers2[1] == 1)[0]:
+        row = (p.gpu.get_row(2, 1, 0, int(pos), 0).astype(np.uint32) << 16).view(np.float32)
+        assert np.array_equal(row.astype(np.float64), p.orc.K[2][1, 0, int(pos)]), pos
+    step_all(1)
+    tiers3 = np.zeros((cfg.batch, n + 2), np.uint8); tiers3[:, :n + 1] = np.where(tiers2 == 1, 3, tiers2)
+    p.force_tiers(tiers3)
+    st = p.gpu.get_stats()
+    assert st["n_repack"] == 2 and st["host_rows_used"] == 0 and st["tier_count"][1] == 0
+    step_all(2)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n + 3, _mass(cfg, calls))
+    p.close()
+
+
 def test_streamed_t1_with_a_sequence_that_has_no_t1_rows():
     """Streamed T1 where one sequence keeps nothing in T1 (its share of the second attention launch has no tiles and
     must contribute neutral partials) and the other keeps nothing in T2."""
