@@ -162,7 +162,8 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
  * out_dtype.  out_h = sum over live positions of softmax(q_h . k_i * softmax_scale) v_i with kv head h / G; evicted
  * positions are skipped and the softmax renormalises over the rest; T2 rows enter as code*scale.  Adds
  * score_scale * sum over all query heads of the weights to score[b, i] for every live position.
- * ESTATE on an empty layer. */
+ * A sequence whose positions are all evicted (only a forced plan can do that) gets an all-zero output and no score
+ * update.  ESTATE on an empty layer. */
 tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream);
 
 /* The same for n_q query tokens per sequence at once (a chunk of drafted or prompt tokens whose rows have been
@@ -176,8 +177,10 @@ tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q
 /* One decode step of Algorithm 1's loop body for all layers, in layer order: for every layer l,
  * tkv_append(l, k_all[l], v_all[l], 1) then tkv_attend_and_score(l, q_all[l], out_all[l]).  Device pointers:
  * k_all, v_all [n_layers, batch, 1, n_kv_heads, head_dim] kv_dtype; q_all [n_layers, batch, n_q_heads, head_dim]
- * kv_dtype; out_all [n_layers, batch, n_q_heads, head_dim] out_dtype.  Same errors as the two calls; a failure
- * at layer l leaves layers < l appended and attended. */
+ * kv_dtype; out_all [n_layers, batch, n_q_heads, head_dim] out_dtype.  Same errors as the two calls.  All capacity and
+ * state checks are made before anything is enqueued; when all layers are at the same length the new rows of every
+ * layer go in with one launch, so a later failure at layer l (a HIP error) leaves the step's rows appended to ALL
+ * layers and only layers < l attended: finish the step with tkv_attend_and_score for layers >= l, or destroy the handle. */
 tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, const void* q_all, void* out_all,
                            void* hip_stream);
 

@@ -924,8 +924,10 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
     for (int k = 0; k < ns; ++k) mm = fmaxf(mm, src[k * 2 * G + g]);
     float ll = 0.f;
     for (int k = 0; k < ns; ++k) ll = fmaf(src[k * 2 * G + G + g], __builtin_amdgcn_exp2f((src[k * 2 * G + g] - mm) * LOG2E), ll);
-    M[t] = mm;
-    IL[t] = 1.0f / ll;
+    // a sequence with no live position at all (every position evicted by a forced plan) has m = -inf, l = 0 in every
+    // split: its output is defined as zero, not 0/0
+    M[t] = mm > -INFINITY ? mm : 0.f;
+    IL[t] = ll > 0.f ? 1.0f / ll : 0.f;
   }
   __syncthreads();
   if (is_tile) {

@@ -59,16 +59,44 @@ class Pair:
         self.gpu.close()
 
 
-def assert_out_close(got, ref, kv_dtype, what="", out_dtype="f32"):
-    """max |o_gpu - o_ref| <= tol * max-norm of the head's reference vector; a bf16 *output* adds its own
-    round-to-nearest step (half a bf16 ulp, 2^-8 of the element)."""
+def assert_out_close(got, ref, kv_dtype, what=""):
+    """max |o_gpu - o_ref| <= tol * max-norm of the head's reference vector (the binary32 output; a 16-bit output is
+    checked elsewhere as exactly one rounding of it)."""
     tol = TOL_OUT[kv_dtype]
     scale = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1e-6)
-    bound = tol * scale + (2.0 ** -8 * np.abs(ref) if out_dtype == "bf16" else 0.0)
     err = np.abs(got - ref)
     worst = (err / scale).max()
-    assert np.all(err <= bound), f"{what}: attention output off by {worst:.3e} of the head max-norm (tol {tol})"
+    assert np.all(err <= tol * scale), f"{what}: attention output off by {worst:.3e} of the head max-norm (tol {tol})"
     return worst
+
+
+def assert_t2_rows_exact(p, tiers, layers=None, seqs=None, kv_heads=None, what=""):
+    """Codes and scales of every T2 row of the chosen (layer, sequence, kv head) sets, K and V, bit for bit against the
+    oracle's binary32 encoder (integer work: no tolerance).  tiers [B, n] is the plan in force.  Returns the number of
+    rows compared."""
+    cfg = p.cfg
+    layers = range(cfg.n_layers) if layers is None else layers
+    seqs = range(cfg.batch) if seqs is None else seqs
+    kv_heads = range(cfg.n_kv_heads) if kv_heads is None else kv_heads
+    rows = 0
+    for b in seqs:
+        for pos in np.nonzero(tiers[b] == 2)[0]:
+            pos = int(pos)
+            for l in layers:
+                oc = p.orc.t2[l][(b, pos)]
+                for which in (0, 1):
+                    for kvh in kv_heads:
+                        codes, scales = p.gpu.get_t2_row(l, b, kvh, pos, which)
+                        ref_codes, ref_scale = oc[2 * which][kvh], oc[2 * which + 1][kvh]
+                        tag = f"{what}: T2 row layer {l} seq {b} kv head {kvh} pos {pos} {'KV'[which]}"
+                        if cfg.t2_format == "int8_row":
+                            assert np.array_equal(codes, ref_codes), tag + " codes"
+                            assert scales.view(np.uint32)[0] == np.float32(ref_scale).view(np.uint32), tag + " scale"
+                        else:
+                            assert np.array_equal(codes, O.pack_int4(ref_codes)), tag + " codes"
+                            assert np.array_equal(scales, np.asarray(ref_scale, np.float32).astype(np.float16).view(np.uint16)), tag + " scales"
+                        rows += 1
+    return rows
 
 
 def assert_scores_close(got32, ref64, n, total_mass, what=""):

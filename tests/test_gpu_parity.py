@@ -23,6 +23,15 @@ def _mass(cfg, calls):
     return calls * cfg.n_q_heads * ss
 
 
+def _total(p, cfg, calls, n, scorer):
+    """What the underflow floor of the score tolerance is a fraction of: the total a sequence's scores have received.
+    Attention scorer: the closed form (one unit per query head and call).  Value-aware scorer: every unit is weighted by
+    a value-row norm, so the total is the reference's own sum over the sequence (the largest over the batch)."""
+    if scorer == "vatp":
+        return float(p.orc.score[:, :n].sum(axis=1).max())
+    return _mass(cfg, calls)
+
+
 @pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,ctx", [
     ("f32", 64, 8, 2, 512),      # group 4, the tiny config's shape
     ("f32", 128, 4, 4, 130),     # group 1, ragged
@@ -111,19 +120,10 @@ def test_forced_tiers_attention_codes_and_lists(kv_dtype, D, Hq, Hkv, t2, mode):
     for b in range(cfg.batch):
         for t in range(4):
             assert np.array_equal(p.gpu.get_index_list(t, b), np.nonzero(tiers[b] == t)[0])
-    # T2 codes and scales are bit-exact against the binary32 definition
-    for (b, pos) in [(0, int(np.nonzero(tiers[0] == 2)[0][0])), (1, int(np.nonzero(tiers[1] == 2)[0][-1]))]:
-        for l in range(cfg.n_layers):
-            for which in (0, 1):
-                for kvh in range(Hkv):
-                    codes, scales = p.gpu.get_t2_row(l, b, kvh, pos, which)
-                    oc = p.orc.t2[l][(b, pos)]
-                    ref_codes, ref_scale = oc[2 * which][kvh], oc[2 * which + 1][kvh]
-                    if t2 == "int8_row":
-                        assert np.array_equal(codes, ref_codes) and scales[0] == ref_scale
-                    else:
-                        assert np.array_equal(codes, O.pack_int4(ref_codes))
-                        assert np.array_equal(scales.view(np.float16).astype(np.float32), ref_scale)
+    # T2 codes and scales of EVERY compressed row (all layers, sequences, kv heads, K and V): bit-exact against the
+    # binary32 definition
+    from gpu_common import assert_t2_rows_exact
+    assert assert_t2_rows_exact(p, tiers, what="first plan") > 0
     # a T1 row reads back from the pinned host store with the bits it was appended with
     b, pos = 0, int(np.nonzero(tiers[0] == 1)[0][3])
     k_ctx, v_ctx = p.wl.context_kv(1)
@@ -154,6 +154,8 @@ def test_forced_tiers_attention_codes_and_lists(kv_dtype, D, Hq, Hkv, t2, mode):
     for b in range(cfg.batch):
         for t in range(4):
             assert np.array_equal(p.gpu.get_index_list(t, b), np.nonzero(tiers2[b] == t)[0])
+    # rows encoded from a staged T1 copy, rows that kept their codes (T2 -> T2), rows re-encoded from a promoted value
+    assert assert_t2_rows_exact(p, tiers2[:, :n], what="second plan") > 0
     for step in range(cfg.decode_steps, cfg.decode_steps + 2):
         for l in range(cfg.n_layers):
             got, ref = p.attend(l, p.wl.step_q(step, l))
@@ -306,7 +308,7 @@ def test_streamed_t1_walk(kv_dtype, D, Hq, Hkv, t2, layers):
 
 
 def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False, rounds=8, layers=2, **create_kw):
-    from gpu_common import assert_out_close, assert_scores_close
+    from gpu_common import assert_out_close, assert_scores_close, assert_t2_rows_exact
     cfg = small_config(n_layers=layers, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
                        context=500, decode_steps=rounds, t2_format=t2, sigma=1.0)
     p = _pair(cfg, prefetch_mode=mode, **({"host_rows": host_rows} if host_rows else {}), **create_kw)
@@ -337,6 +339,9 @@ def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False
                     elif kv_dtype == "f16":
                         row = row.view(np.float16)
                     assert np.array_equal(row.astype(np.float64), store[cfg.n_layers - 1][1, 1, int(pos)]), (rnd, t, pos, which)
+        # codes and scales of every T2 row of one (layer, sequence, kv head): rows encoded from HBM, from a staged or
+        # streamed T1 copy, re-encoded after a promotion, or kept as they were
+        assert_t2_rows_exact(p, tiers, layers=[cfg.n_layers - 1], seqs=[1], kv_heads=[cfg.n_kv_heads - 1], what=f"round {rnd}")
         for l in range(cfg.n_layers):
             k, v = p.wl.step_kv(rnd, l)
             p.append(l, k, v)
@@ -605,7 +610,7 @@ def test_whole_steps_and_classify(mode, scorer):
         if step % 4 == 3:
             n = p.gpu.layer_length(0)
             s_gpu = p.gpu.get_scores()
-            assert_scores_close(s_gpu, p.orc.score, n, _mass(cfg, calls) * (20.0 if scorer == "vatp" else 1.0), f"step {step}")
+            assert_scores_close(s_gpu, p.orc.score, n, _total(p, cfg, calls, n, scorer), f"step {step}")
             p.gpu.classify(pol)
             plan = p.gpu.get_pending_tiers()[:, :n]
             assert np.array_equal(plan, p.orc.classify(pol, score_f32=s_gpu)[:, :n])
@@ -663,8 +668,7 @@ def test_chunks_of_query_tokens(mode, kv_dtype, D, Hq, Hkv, t2, scorer, batch):
                 assert_out_close(got[:, j], ref[:, j], kv_dtype, f"chunk {T} layer {l} query {j}")
         step += T
         n += T
-    mass = _mass(cfg, calls) * (20.0 if scorer == "vatp" else 1.0)
-    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, mass)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _total(p, cfg, calls, n, scorer))
     # 16 positions were appended since the plan: a chunk of 17 would reach into re-tiered positions
     q17 = torch.zeros((cfg.batch, 17, Hq, D), dtype=q.dtype, device=q.device)
     with pytest.raises(tkv.TkvError) as e:
@@ -784,4 +788,138 @@ def test_streamed_t1_with_a_sequence_that_has_no_t1_rows():
         calls += 1
         assert_out_close(got, ref, "bf16", f"no T1 left, layer {l}")
     assert_scores_close(p.gpu.get_scores(), p.orc.score, n + cfg.decode_steps, _mass(cfg, calls))
+    p.close()
+
+
+def _crafted_rows(D, t2, kv_dtype):
+    """Rows [n, D] (binary32 values, all exactly representable in bf16 and, except where noted, binary16) that sit on the
+    encoder's edges: exact halves after the division (round-to-nearest-even decides the code), an all-zero row, a zero
+    group, an absmax whose binary16 scale underflows to zero or to a subnormal, an absmax that makes the binary32 scale
+    subnormal, and a row whose largest element is negative."""
+    rows = []
+    half = np.array([0.5, 1.5, 2.5, 3.5, 4.5, 5.5, 6.5, -0.5, -1.5, -2.5, -3.5, -4.5, -5.5, -6.5], np.float32)
+    if t2 == "int8_row":
+        r = np.zeros(D, np.float32); r[0] = 127.0                      # scale exactly 1: x / scale = x
+        r[1:15] = half; r[15:19] = [126.5, 125.5, -126.5, -125.5]; r[19] = -127.0
+        rows.append(r)
+        r = np.zeros(D, np.float32); r[5] = -254.0                     # largest element negative, scale exactly 2
+        r[6:20] = 2.0 * half; r[20:24] = [1.0, 3.0, -1.0, -3.0]        # quotients 0.5, 1.5, -0.5, -1.5
+        rows.append(r)
+        r = np.zeros(D, np.float32); r[D - 1] = 2.0 ** -14             # small scale 2^-14 / 127; quotients 63.5, -63.5, 0.99
+        r[0:4] = [2.0 ** -15, -(2.0 ** -15), 2.0 ** -21, 0.0]
+        rows.append(r)
+        if kv_dtype != "f16":                                          # below binary16's range
+            r = np.zeros(D, np.float32); r[3] = 2.0 ** -125            # scale = 2^-125 / 127 is a binary32 subnormal
+            r[4:8] = [2.0 ** -126, -(2.0 ** -127), 2.0 ** -130, 2.0 ** -133]
+            rows.append(r)
+    else:
+        r = np.zeros(D, np.float32)
+        for g in range(D // 32):
+            r[32 * g] = 7.0 if g % 2 == 0 else -7.0                    # scale exactly 1 in every group
+            r[32 * g + 1: 32 * g + 15] = half if g % 2 == 0 else -half
+        rows.append(r)
+        r = np.zeros(D, np.float32)
+        r[0:32] = np.arange(-16, 16, dtype=np.float32) * np.float32(0.1875)   # absmax 3: the scale 3/7 is not exact in binary16
+        r[32:64] = 0.0                                                 # a zero group beside live ones
+        if D > 64:
+            r[64] = 2.0 ** -24; r[65] = -(2.0 ** -24); r[66] = 2.0 ** -24   # a/7 < 2^-25: the binary16 scale is zero, codes zero
+            r[96] = 2.0 ** -22; r[97] = 2.0 ** -23; r[98] = -(2.0 ** -24); r[99] = 3 * 2.0 ** -24   # scale = 2^-24 (subnormal): codes 4, 2, -1, 3
+        else:
+            r[32] = 2.0 ** -22; r[33] = 2.0 ** -23; r[34] = -(2.0 ** -24); r[35] = 3 * 2.0 ** -24
+        rows.append(r)
+        r = np.zeros(D, np.float32); r[::32] = 2.0 ** -24                  # every group underflows: all codes and scales zero
+        rows.append(r)
+        r = np.zeros(D, np.float32); r[0] = 14.0; r[1:15] = 2.0 * half     # scale exactly 2: quotients on halves again
+        r[40] = -3.5; r[41] = 1.75; r[42] = -0.25                          # scale 0.5 exactly: 3.5/7
+        rows.append(r)
+    rows.append(np.zeros(D, np.float32))                                   # absmax 0
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("mode", ["wait", "stream"])
+@pytest.mark.parametrize("t2", ["int8_row", "int4_g32"])
+@pytest.mark.parametrize("kv_dtype,D", [("bf16", 128), ("f16", 128), ("f32", 64)])
+def test_t2_codec_on_crafted_rows(kv_dtype, D, t2, mode):
+    """The encoder's edge cases, bit for bit against the oracle's binary32 definition: crafted rows (see _crafted_rows)
+    planted as the K and the V rows of chosen positions, compressed from HBM and (second plan) from a T1 copy, read
+    back code by code and scale by scale; then attention through them, and their promoted values after T2 -> T0."""
+    from gpu_common import assert_out_close, assert_scores_close, assert_t2_rows_exact, to_f64
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=D, kv_dtype=kv_dtype, context=96,
+                       decode_steps=3, t2_format=t2, sigma=1.0, k_sink=0, k_window=0)
+    p = _pair(cfg, prefetch_mode=mode, preload=False)
+    crafted = _crafted_rows(D, t2, kv_dtype)
+    nc = len(crafted)
+    pos_a = [3 + 2 * i for i in range(nc)]            # compressed by the first plan, straight from HBM
+    pos_b = [40 + 3 * i for i in range(nc)]           # first to T1, compressed from there by the second plan
+    for l in range(cfg.n_layers):
+        k, v = p.wl.context_kv(l)
+        for i in range(nc):
+            row = torch.from_numpy(crafted[i]).to(k.dtype).to(k.device)
+            assert torch.equal(row.float().cpu(), torch.from_numpy(crafted[i])), "crafted values must be exact in storage"
+            for pos in (pos_a[i], pos_b[i]):
+                k[:, pos, l % 2] = row            # K row of one kv head (the other keeps its random row)
+                v[:, pos, 1 - l % 2] = row.flip(0) if t2 == "int8_row" else row
+        p.append(l, k.contiguous(), v.contiguous())
+    n = cfg.context
+    rng = np.random.default_rng(3)
+    tiers = _random_tiers(rng, cfg.batch, n, frac=(0.4, 0.3, 0.3, 0.0), protect=(1, 1))
+    tiers[:, pos_a] = 2
+    tiers[:, pos_b] = 1
+    p.force_tiers(tiers)
+    assert assert_t2_rows_exact(p, tiers, what="crafted, from HBM") > 0
+    calls = 0
+    qs = 2.0 ** -5      # the crafted key rows reach 254: small queries keep the logits (and their binary32 rounding) ordinary
+    for step in range(2):
+        for l in range(cfg.n_layers):
+            p.append(l, *p.wl.step_kv(step, l))
+            got, ref = p.attend(l, p.wl.step_q(step, l) * qs)
+            calls += 1
+            assert_out_close(got, ref, kv_dtype, f"crafted step {step} layer {l}")
+    n += 2
+    tiers2 = np.zeros((cfg.batch, n), np.uint8); tiers2[:, :n - 2] = tiers
+    tiers2[:, pos_b] = 2                              # encoded from the staged / streamed T1 copy
+    tiers2[:, pos_a] = 0                              # promoted: binary32(code * scale) rounded to the KV dtype
+    p.force_tiers(tiers2)
+    assert assert_t2_rows_exact(p, tiers2, what="crafted, from T1") > 0
+    for pos in pos_a:
+        for l in range(cfg.n_layers):
+            for kvh in range(cfg.n_kv_heads):
+                for which, store in ((0, p.orc.K), (1, p.orc.V)):
+                    row = p.gpu.get_row(l, 1, kvh, pos, which)
+                    if kv_dtype == "bf16":
+                        row = (row.astype(np.uint32) << 16).view(np.float32)
+                    elif kv_dtype == "f16":
+                        row = row.view(np.float16)
+                    assert np.array_equal(row.astype(np.float64), store[l][1, kvh, pos]), (pos, l, kvh, which)
+    for l in range(cfg.n_layers):
+        p.append(l, *p.wl.step_kv(2, l))
+        got, ref = p.attend(l, p.wl.step_q(2, l) * qs)
+        calls += 1
+        assert_out_close(got, ref, kv_dtype, f"crafted, after the second plan, layer {l}")
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n + 1, _mass(cfg, calls))
+    p.close()
+
+
+@pytest.mark.parametrize("mode", ["wait", "stream"])
+def test_sequence_with_no_live_position_gives_zero_output(mode):
+    """A forced plan that evicts every position of one sequence: that sequence's output is exactly zero (not 0/0) and
+    its scores stay as they were; the other sequence is unaffected."""
+    from gpu_common import assert_out_close, assert_scores_close
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=200,
+                       decode_steps=1, sigma=1.0)
+    p = _pair(cfg, prefetch_mode=mode)
+    n = cfg.context
+    for l in range(cfg.n_layers):
+        p.attend(l, p.wl.step_q(0, l))
+    before = p.gpu.get_scores()[0, :n].copy()
+    tiers = np.zeros((cfg.batch, n), np.uint8)
+    tiers[0, :] = 3
+    tiers[1, 50:120] = 1
+    p.force_tiers(tiers)
+    for l in range(cfg.n_layers):
+        got, ref = p.attend(l, p.wl.step_q(1, l))
+        assert np.all(got[0] == 0.0) and np.all(ref[0] == 0.0)
+        assert_out_close(got[1:], ref[1:], "bf16", f"layer {l}")
+    assert np.array_equal(p.gpu.get_scores()[0, :n], before)
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _mass(cfg, 2 * cfg.n_layers))
     p.close()

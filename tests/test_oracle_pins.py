@@ -234,6 +234,26 @@ def test_int4_properties():
     assert np.all(np.abs(x - xh)[ok] <= bound[ok])
 
 
+def test_codec_subnormal_scales_by_hand():
+    """Edges of the two encoders, expected values worked out by hand.
+    int4: a/7 below 2^-25 rounds to a zero binary16 scale (zero codes); a = 2^-22 gives a/7 = 0.571 * 2^-24, which rounds
+    to the smallest binary16 subnormal 2^-24, so the codes are x / 2^-24 and the largest element does NOT map to 7.
+    int8: a = 2^-125 gives the binary32 subnormal scale rne(2^-125 / 127): 2^-125 / 127 = 132104.06 * 2^-149, i.e.
+    the bit pattern 132104; x / scale is then 127 * 2^k (slightly below, the scale having been rounded down...)
+    for x = 2^(-125+k): codes 127, 64 (63.5 + eps rounds up), -32, 4."""
+    x = np.zeros(64, np.float32)
+    x[0:3] = [2.0 ** -24, -(2.0 ** -24), 2.0 ** -24]
+    x[32:36] = [2.0 ** -22, 2.0 ** -23, -(2.0 ** -24), 3 * 2.0 ** -24]
+    codes, scale = O.quant_int4_g32(x)
+    assert list(scale) == [0.0, 2.0 ** -24]
+    assert np.all(codes[:32] == 0) and list(codes[32:36]) == [4, 2, -1, 3]
+    y = np.zeros(16, np.float32)
+    y[3:8] = [2.0 ** -125, 2.0 ** -126, -(2.0 ** -127), 2.0 ** -130, 2.0 ** -133]
+    codes, scale = O.quant_int8_row(y)
+    assert np.float32(scale).view(np.uint32) == 132104
+    assert list(codes[3:8]) == [127, 64, -32, 4, 0]
+
+
 def test_promotion_value_is_binary32_product_rounded_to_storage():
     codes = np.array([[127, -3, 0, 55]], np.int8)
     scale = np.array([0.0123456789], np.float32)
