@@ -166,6 +166,18 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
  * update.  ESTATE on an empty layer. */
 tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same call as tkv_attend_and_score, same arguments, same bits in out and in the scores, but the
+ * call's scratch (scaled logits, split partials) lives in a fixed 16 MiB array in the library's device image instead
+ * of the handle's own allocations, and the call itself makes no hipMalloc / hipFree / event or stream creation and
+ * issues none of the T1 copies a TKV_PREFETCH_LAZY migrate has left queued (rows still in flight are read from their
+ * old HBM slots, which by Prop. 1 gives the same bits; the next ordinary call issues the copies).
+ * ECAPACITY, with the sizes in tkv_last_error, if the cache's shape needs more scratch than the array holds
+ * (batch * n_q_heads * (max_tokens + 192) * 4 bytes of logits plus the partials); EINVAL with TKV_PREFETCH_STREAM.
+ * All calls on one GPU share that GPU's array and it keeps the last call's contents: calls that overlap on one GPU
+ * (two handles on two streams) race; calls ordered on one stream do not, and nothing in it has to start at zero. */
+tkv_status tkv_attend_and_score_noalloc(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream);
+
 /* The same for n_q query tokens per sequence at once (a chunk of drafted or prompt tokens whose rows have been
  * appended): q device [batch, n_q, n_q_heads, head_dim], out the same shape.  Query j belongs to position
  * n - n_q + j of the layer's n positions and attends to the positions up to and including its own (Eq. 2 sums

@@ -64,6 +64,7 @@ SYMBOLS = {
     "tkv_destroy": (None, [_VP]),
     "tkv_append": (C.c_int, [_VP, _I32, _VP, _VP, _I32, _VP]),
     "tkv_attend_and_score": (C.c_int, [_VP, _I32, _VP, _VP, _VP]),
+    "tkv_attend_and_score_noalloc": (C.c_int, [_VP, _I32, _VP, _VP, _VP]),
     "tkv_attend_and_score_chunk": (C.c_int, [_VP, _I32, _VP, _VP, _I32, _VP]),
     "tkv_decode_step": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _VP]),
     "tkv_set_profile": (C.c_int, [_VP, _I32]),
@@ -221,6 +222,14 @@ class TieredKV:
         self._check(self.lib.tkv_attend_and_score(self._h, layer, self._dev_tensor(q, (B, Hq, D)),
                                                   self._dev_tensor(out, (B, Hq, D), self.out_torch_dtype),
                                                   self._stream(stream)))
+        return out
+
+    def attend_and_score_noalloc(self, layer, q, out, stream=None):
+        """The variant that allocates nothing: `out` must be passed in."""
+        L, B, Hq, Hkv, D = self.shape
+        self._check(self.lib.tkv_attend_and_score_noalloc(self._h, layer, self._dev_tensor(q, (B, Hq, D)),
+                                                          self._dev_tensor(out, (B, Hq, D), self.out_torch_dtype),
+                                                          self._stream(stream)))
         return out
 
     def attend_and_score_chunk(self, layer, q, out=None, stream=None):

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -18,9 +19,32 @@
 
 using namespace tkv;
 
+// ---- scratch of tkv_attend_and_score_noalloc -------------------------------------------------------------------
+// The split partials and the scaled logits of one attention call, for callers that may not allocate: a fixed array
+// in the library's device image instead of the handle's own allocations.  Every GPU the library runs on holds its own
+// copy of the array at its own address (until the process ends); in host code the array's name is only a handle for
+// hipGetSymbolAddress, never an address to pass to a kernel.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int RING = 4;
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each device, looked up once per device
+
+// With cfg.device current: the device address of the scratch array on that device (nullptr on failure).
+void* scratch_on_device(int device) {
+  if (device < 0 || device >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[device] = ptr;
+  }
+  return g_scratch_ptr[device];
+}
 
 struct EvPair { hipEvent_t a, b; int64_t bytes; int dir; };  // dir 0 = D2H, 1 = H2D
 
@@ -48,6 +72,7 @@ struct tkv_cache {
   // attention scratch
   float* xs = nullptr; float* part_ml = nullptr; float* part_o = nullptr;
   int S_alloc = 0, xs_stride = 0;
+  char* static_scratch = nullptr;  // this device's copy of the library's fixed scratch array (tkv_attend_and_score_noalloc)
   // T1 store and transport
   char* hstore = nullptr;
   int64_t host_rows = 0, host_next = 0;
@@ -397,6 +422,8 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
     return s;
   };
   if (hipSetDevice(cfg->device) != hipSuccess) return die(TKV_EDEVICE, "tkv_create: hipSetDevice failed");
+  c->static_scratch = (char*)scratch_on_device(cfg->device);
+  if (!c->static_scratch) return die(TKV_EDEVICE, "tkv_create: hipGetSymbolAddress of the static scratch array failed");
 
   DevView& v = c->dv;
   const int L = cfg->n_layers, B = cfg->batch, Hkv = cfg->n_kv_heads, D = cfg->head_dim, N = cfg->max_tokens;
@@ -554,8 +581,10 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
 // One query token per sequence against one layer.  trim: entries at the end of list F to leave out (later tokens of a
 // chunk); q_bs / o_bs: query heads between consecutive sequences in q / out; last: the layer's last call of this step
 // (the streamed frame is released and refilled, queued transfers are pumped).
+// noalloc: the scratch of the call lives in the library's fixed device array, and nothing on the way may allocate
+// (no event pools, no queued transfers are issued).
 static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* out, int trim, int q_bs, int o_bs, bool last,
-                             hipStream_t st) {
+                             hipStream_t st, bool noalloc = false) {
   const DevView& v = c->dv;
   bool use_old = false;
   const int fr = layer & 1;
@@ -570,10 +599,11 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
     }
   } else if (c->layer_wait[layer]) {
     if (c->cfg.prefetch_mode == TKV_PREFETCH_WAIT) {
-      while (!c->layer_enq[layer] && c->jobs_next < c->jobs.size()) {
+      while (!noalloc && !c->layer_enq[layer] && c->jobs_next < c->jobs.size()) {
         tkv_status ps = pump_transfers(c, 1);
         if (ps != TKV_OK) return ps;
       }
+      if (!c->layer_enq[layer]) return fail(c, TKV_ESTATE, "tkv_attend_and_score: the transfers of layer %d have not been queued", layer);
       HIPCHK(c, hipStreamWaitEvent(st, c->ev_ready[layer], 0));
       c->layer_wait[layer] = 0;
       c->st.attend_waits++;
@@ -605,6 +635,17 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.f_loc = use_old ? v.f_loc_old : v.f_loc; a.f_pos = v.f_pos; a.q_loc = v.q_loc; a.q_pos = v.q_pos;
   a.vnorm = v.vnorm ? v.vnorm + lrows * v.Nmax : nullptr;
   a.cnt = v.cnt; a.score = v.score; a.xs = c->xs; a.part_ml = c->part_ml; a.part_o = c->part_o;
+  if (noalloc) {
+    // the same three arrays, carved out of the fixed scratch array (256-byte aligned each)
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t xs_b = up((size_t)v.B * v.Hq * c->xs_stride * sizeof(float));
+    const size_t ml_b = up((size_t)v.B * v.Hkv * c->S_alloc * 2 * c->G * sizeof(float));
+    const size_t po_b = up((size_t)v.B * v.Hkv * c->S_alloc * c->G * v.D * sizeof(float));
+    if (xs_b + ml_b + po_b > NOALLOC_SCRATCH_BYTES)
+      return fail(c, TKV_ECAPACITY, "tkv_attend_and_score_noalloc: this cache needs %zu bytes of scratch per call, the fixed array holds %zu",
+                  xs_b + ml_b + po_b, NOALLOC_SCRATCH_BYTES);
+    a.xs = (float*)c->static_scratch; a.part_ml = (float*)(c->static_scratch + xs_b); a.part_o = (float*)(c->static_scratch + xs_b + ml_b);
+  }
   a.q_es = c->es;
   if (v.B <= ATTN_ARG_SEQS)
     for (int b = 0; b < v.B; ++b) {
@@ -617,7 +658,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim;
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
-  if (c->cfg.profile) {
+  if (c->cfg.profile && !noalloc) {
     pe = next_pair(c->prof_events, c->prof_used);
     if (!pe) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
     pe->dir = 0;
@@ -639,7 +680,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
     HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->kt, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
   HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
-  if (!last) return TKV_OK;
+  if (!last || noalloc) return TKV_OK;
   if (c->streamed && S2 > 0) {
     HIPCHK(c, hipEventRecord(c->ev_free[fr], st));
     c->frame_used[fr] = true;
@@ -661,6 +702,15 @@ tkv_status tkv_attend_and_score(tkv_cache* c, int32_t layer, const void* q, void
   if (c->len[layer] == 0) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d is empty", layer);
   if (c->len[layer] != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_attend_and_score: layer %d has %d tokens, %d are assigned; append first", layer, c->len[layer], c->n_assigned);
   return attend_one(c, layer, q, out, 0, c->dv.Hq, c->dv.Hq, true, (hipStream_t)hip_stream);
+}
+
+tkv_status tkv_attend_and_score_noalloc(tkv_cache* c, int32_t layer, const void* q, void* out, void* hip_stream) {
+  if (!c) return TKV_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers || !q || !out) return fail(c, TKV_EINVAL, "tkv_attend_and_score_noalloc: bad argument");
+  if (c->streamed) return fail(c, TKV_EINVAL, "tkv_attend_and_score_noalloc: not available with TKV_PREFETCH_STREAM (its frame refills take events from a growing pool)");
+  if (c->len[layer] == 0) return fail(c, TKV_ESTATE, "tkv_attend_and_score_noalloc: layer %d is empty", layer);
+  if (c->len[layer] != c->n_assigned) return fail(c, TKV_ESTATE, "tkv_attend_and_score_noalloc: layer %d has %d tokens, %d are assigned; append first", layer, c->len[layer], c->n_assigned);
+  return attend_one(c, layer, q, out, 0, c->dv.Hq, c->dv.Hq, true, (hipStream_t)hip_stream, true);
 }
 
 tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q, void* out, int32_t n_q, void* hip_stream) {
