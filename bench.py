@@ -4,13 +4,22 @@
 One "step" is one pass of the whole path over a batch of synthetic input: for every layer, append the new
 token's K/V rows and run tiered attention with score accumulation; every Delta steps, classify and migrate
 (T1 offload + prefetch on the side streams).  Inputs are resident in HBM before the timed region starts.
-Prints one JSON line (metric: KV GB/s of the whole job, with the HBM-roofline figure of the attention kernel,
-the T1 prefetch overhead against the all-in-HBM twin, and the CPU oracle timed on a bounded sample).
+
+Whatever --steps / --warmup are, the timed region is a stationary one: every job first runs Delta scored decode
+steps on the all-in-HBM context (so the first ranking has real scores), applies the initial tiering (the cold
+fill), then 2 * Delta further untimed steps with two score-driven re-tiering events whose transfers are left to
+land, then the --warmup steps, and only then the --steps timed ones.  The events inside the timed region are
+therefore ordinary ones; the first score-driven event (which re-sorts a third of T1) is reported on its own.
+
+Prints one JSON line (metric: KV GB/s of the whole job, with the HBM-roofline figure of the attention kernel
+and of the whole attention call, the T1 prefetch overhead against the all-in-HBM twin, the CPU oracle timed on
+a bounded sample, and a compact record for each of the other benchmark shapes).
 """
 import argparse
 import dataclasses
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,45 +28,62 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the attention kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each
-# scaled by the same counter's reading for the library's plain row-copy kernel of known size (the context preload:
-# 134 217 728 bytes read and written per launch; FETCH_SIZE reads 1 per 2031 bytes, WRITE_SIZE 1 per KiB).
-# See profiles/attn_tiered_14b_hbm_traffic.txt.
-MEASURED_TRAFFIC = {"14b": {"fetch_bytes": 122_190_000, "write_bytes": 5_800_000}}
 LINK_PEAK_GBPS = 64.0       # PCIe Gen5 x16, one direction
+SETTLE_EVENTS = 2           # score-driven re-tiering events before anything is timed
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(name):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 --pmc summary of this workload
+    (profiles/attn_tiered_<name>_hbm_traffic.txt, line `traffic_bytes_per_launch fetch=... write=...`), or None."""
+    try:
+        txt = open(os.path.join(ROOT, "profiles", f"attn_tiered_{name}_hbm_traffic.txt")).read()
+        m = re.search(r"^traffic_bytes_per_launch\s+fetch=(\d+)\s+write=(\d+)", txt, flags=re.M)
+        return int(m.group(1)) + int(m.group(2)) if m else None
+    except OSError:
+        return None
+
+
 def call_bytes(cfg, n_full, n_t2, out_es=4):
     """Algorithmic bytes of one layer call: every live row once (K and V), q and out, score read-modify-write.
-    n_full, n_t2 are position counts summed over the batch."""
+    n_full, n_t2 are position counts summed over the batch.  Returns (whole call, the part the attention kernel
+    itself moves: rows and queries)."""
     es = 4 if cfg.kv_dtype == "f32" else 2
     D, Hkv, Hq, B = cfg.head_dim, cfg.n_kv_heads, cfg.n_q_heads, cfg.batch
     t2_row = (D + 4) if cfg.t2_format == "int8_row" else (D // 2 + (D // 32) * 2)
     kv = Hkv * (n_full * 2 * D * es + n_t2 * 2 * t2_row)
-    return kv + B * Hq * D * (es + out_es) + (n_full + n_t2) * 4 * 2
+    q = B * Hq * D * es
+    return kv + q + B * Hq * D * out_es + (n_full + n_t2) * 4 * 2, kv + q
 
 
 BOUNCE_MIB = 0   # --bounce-mib: size of each bounce ring of the T1 transport (0: the library's default)
 SCORER = "attention"   # --scorer
 
 
-def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
+def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0, tight=False):
     import torch
     import paper_2605_09490_amd as tkv
     from tkv_synth import Workload
 
     wl = Workload(cfg, device="cuda")
     sizes = {"bounce_bytes": BOUNCE_MIB << 20, "scorer": SCORER}
+    if tight:
+        # pools sized for the policy's shares (plus the rows that enter a pool before the leavers' slots are released)
+        # instead of the whole context each, and memory straight from hipMalloc / hipHostMalloc: exact sizes, returned
+        # at once when the cache is destroyed (torch's allocators round large pinned blocks up and keep them)
+        n = cfg.max_tokens
+        sizes.update(staging_rows=min(n, int(1.5 * policy[1] * n) // 1_000_000 + 64),
+                     t2_rows=min(n, int(2.0 * policy[2] * n) // 1_000_000 + 64),
+                     host_rows=min(cfg.batch * n, int(1.6 * policy[1] * cfg.batch * n) // 1_000_000 + 64 * cfg.batch),
+                     use_torch_allocator=False)
     if mode == "stream":
         # the two frames are sized for T1's share of the final length plus 30 % (a migrate takes the slots of the rows
         # that enter T1 before it releases those of the rows that leave); the HBM pool still takes the whole context,
         # which is appended before the first tiering
-        n_end = cfg.context + cfg.decode_steps
-        sizes["staging_rows"] = min(cfg.max_tokens, int(1.3 * policy[1] * n_end) // 1_000_000 + 64)
+        sizes["staging_rows"] = min(cfg.max_tokens, int(1.3 * policy[1] * cfg.max_tokens) // 1_000_000 + 64)
     gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                        kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt, k_sink=cfg.k_sink,
                        k_window=cfg.k_window, prefetch_mode=mode, **sizes)
@@ -65,50 +91,77 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
         k, v = wl.context_kv(l)
         gpu.append(l, k, v)
     del k, v
-    total = warmup + steps + profile_steps
+    delta = cfg.reclassify_every
+    pre = delta + SETTLE_EVENTS * delta
+    total = pre + warmup + steps + profile_steps
+    assert total <= cfg.decode_steps
     k_all, v_all, q_all = wl.decode_inputs(0, total)
     out_all = torch.empty((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
-    # one attention pass so the first ranking is not all ties, then the initial tiering + cold fill
-    gpu.decode_step(k_all[0], v_all[0], q_all[0], out_all)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    gpu.classify(policy, count_rule=rule)
-    gpu.migrate()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    gpu.wait_prefetch()
-    t2 = time.perf_counter()
-    st0 = gpu.get_stats()
-    res = {"label": label, "first_migrate_ms": (t1 - t0) * 1e3, "cold_fill_ms": (t2 - t0) * 1e3,
-           "cold_fill_bytes": st0["h2d_bytes"]}
-    delta = cfg.reclassify_every
+    done = [0]                    # decode steps so far
+    counts = [None]               # positions per tier, summed over the batch
 
-    def loop(first, n, count_bytes):
+    def retier():
+        gpu.classify(policy, count_rule=rule)
+        gpu.migrate()
+
+    kernel_bytes = [0]            # the attention kernel's own share of the bytes counted by loop()
+
+    def loop(n, count_bytes=False, events=True):
+        """n decode steps; a re-tiering event after every Delta-th step of the run."""
         nbytes = 0
-        for s in range(first, first + n):
+        for _ in range(n):
+            s = done[0]
             if count_bytes:
-                tc = gpu_counts[0]
-                nbytes += cfg.n_layers * call_bytes(cfg, tc[0] + tc[1] + cfg.batch, tc[2])
+                tc = counts[0]
+                cb = call_bytes(cfg, tc[0] + tc[1] + cfg.batch, tc[2])
+                nbytes += cfg.n_layers * cb[0]
+                kernel_bytes[0] += cfg.n_layers * cb[1]
                 tc[0] += cfg.batch
             gpu.decode_step(k_all[s], v_all[s], q_all[s], out_all)
-            if (s + 1) % delta == 0:
-                gpu.classify(policy, count_rule=rule)
-                gpu.migrate()
+            done[0] = s + 1
+            if events and done[0] % delta == 0:
+                retier()
                 if count_bytes:
-                    gpu_counts[0] = list(gpu.get_stats()["tier_count"])
+                    counts[0] = list(gpu.get_stats()["tier_count"])
         return nbytes
 
-    gpu_counts = [None]
-    loop(1, warmup - 1, False)
+    def timed_event():
+        """One re-tiering event on an idle GPU: (ms until the compute stream is through, ms until every transfer has
+        landed, bytes sent host -> device)."""
+        torch.cuda.synchronize(); gpu.wait_prefetch()
+        b0 = gpu.get_stats()["h2d_bytes"]
+        t0 = time.perf_counter()
+        retier()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        gpu.wait_prefetch()
+        t2 = time.perf_counter()
+        return (t1 - t0) * 1e3, (t2 - t0) * 1e3, gpu.get_stats()["h2d_bytes"] - b0
+
+    # Delta scored steps on the untiered cache, then the initial tiering with its cold fill
+    loop(delta, events=False)
+    first_ms, cold_ms, cold_bytes = timed_event()
+    res = {"label": label, "first_migrate_ms": first_ms, "cold_fill_ms": cold_ms, "cold_fill_bytes": cold_bytes}
+    # two score-driven events, each left to land
+    for i in range(SETTLE_EVENTS):
+        loop(delta, events=False)
+        ev_ms, ev_all_ms, ev_bytes = timed_event()
+        if i == 0:
+            res.update({"first_event_ms": ev_all_ms, "first_event_bytes": ev_bytes})
+        else:
+            res.update({"settle_event_ms": ev_all_ms, "settle_event_bytes": ev_bytes})
+    loop(warmup)
     torch.cuda.synchronize()
     gpu.wait_prefetch()
-    gpu_counts[0] = list(gpu.get_stats()["tier_count"])
+    counts[0] = list(gpu.get_stats()["tier_count"])
     st1 = gpu.get_stats()
+    gpu.set_profile(2)                   # one pair of events around every decode step (not around the kernels)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    nbytes = loop(warmup, steps, True)
-    torch.cuda.synchronize()
+    nbytes = loop(steps, count_bytes=True)
+    torch.cuda.synchronize()             # every stream: transfers still in flight are part of the timed region
     t1 = time.perf_counter()
+    gpu.set_profile(0)
     gpu.wait_prefetch()
     st2 = gpu.get_stats()
     res.update({"wall_s": t1 - t0, "bytes": nbytes, "ms_per_step": (t1 - t0) * 1e3 / steps,
@@ -117,17 +170,25 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
                 "d2h_bytes": st2["d2h_bytes"] - st1["d2h_bytes"], "d2h_ms": st2["d2h_ms"] - st1["d2h_ms"],
                 "classify_ms": st2["classify_ms"] - st1["classify_ms"], "migrate_ms": st2["migrate_ms"] - st1["migrate_ms"],
                 "attend_waits": st2["attend_waits"] - st1["attend_waits"],
-                "lazy_old_reads": st2["lazy_old_reads"] - st1["lazy_old_reads"]})
+                "lazy_old_reads": st2["lazy_old_reads"] - st1["lazy_old_reads"],
+                # one attention call as the timed region saw it: event-timed decode steps over their layer calls (the
+                # step's one append launch is in there, the re-tiering events are not)
+                "call_avg_us": (st2["step_ms"] - st1["step_ms"]) * 1e3 / max(st2["steps_timed"] - st1["steps_timed"], 1) / cfg.n_layers,
+                "call_bytes_per_launch": nbytes / (steps * cfg.n_layers)})
     if profile_steps:
-        gpu.set_profile(True)
-        b0 = loop(warmup + steps, profile_steps, True)
+        gpu.set_profile(1)
+        kernel_bytes[0] = 0
+        b0 = loop(profile_steps, count_bytes=True)
         torch.cuda.synchronize()
         st3 = gpu.get_stats()
-        gpu.set_profile(False)
+        gpu.set_profile(0)
         launches = st3["attn_kernel_launches"] - st2["attn_kernel_launches"]
-        kms = st3["attn_kernel_ms"] - st2["attn_kernel_ms"]
-        res.update({"kernel_launches": launches, "kernel_avg_us": kms * 1e3 / max(launches, 1),
-                    "kernel_bytes_per_launch": b0 / max(launches, 1)})
+        res.update({"kernel_launches": launches,
+                    "kernel_avg_us": (st3["attn_kernel_ms"] - st2["attn_kernel_ms"]) * 1e3 / max(launches, 1),
+                    "finish_avg_us": (st3["attn_finish_ms"] - st2["attn_finish_ms"]) * 1e3 / max(launches, 1),
+                    "call_avg_us_with_kernel_events": (st3["attn_call_ms"] - st2["attn_call_ms"]) * 1e3 / max(launches, 1)})
+        # the kernel's own share of a call's bytes: the rows and the queries (output and score update are the finish kernel's)
+        res["kernel_bytes_per_launch"] = kernel_bytes[0] / max(launches, 1)
         import numpy as np
         n = gpu.layer_length(0)
         sc = np.sort(gpu.get_scores()[:, :n].astype(np.float64), axis=1)[:, ::-1]
@@ -135,9 +196,8 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
         res["bottom50_share"] = float((sc[:, n // 2:].sum(1) / sc.sum(1)).mean())
         # Eq. 1 at full size: every attention call adds one unit of probability per query head, so with the scale
         # 1/(L*Hq) each sequence's scores (evicted positions keep theirs) sum to the number of decode steps so far
-        steps_done = 1 + (warmup - 1) + steps + profile_steps
         if SCORER == "attention":
-            res["score_mass_rel_err"] = float(np.abs(sc.sum(1) / steps_done - 1.0).max())
+            res["score_mass_rel_err"] = float(np.abs(sc.sum(1) / done[0] - 1.0).max())
     res["device_bytes"] = st2["device_bytes"]
     res["pinned_bytes"] = st2["pinned_bytes"]
     res["gpu"] = gpu
@@ -145,55 +205,92 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0):
     return res
 
 
-def cpu_baseline(cfg, res, budget_s=20.0):
-    """The CPU oracle as it stands, timed on a bounded sample of the same workload: the first two layers, all
-    sequences, the GPU run's final tier assignment, a few attention-and-score calls."""
-    import numpy as np
+def release_memory():
+    """torch keeps freed device and pinned blocks cached: hand them back before the next job allocates its own sizes."""
+    import gc
     import torch
+    gc.collect()
+    torch.cuda.empty_cache()
+    try:
+        torch._C._host_emptyCache()
+    except Exception:
+        pass
+
+
+def cpu_baseline(cfg, res, budget_s=20.0, workers=None):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload: the first two layers, all
+    sequences, the GPU run's final tier assignment.  The oracle's own attend_gqa is called once per (sequence, kv head)
+    pair (the pairs are independent) from a pool of threads, one BLAS thread each; `cores` is the CPU time the
+    process used divided by the wall time, i.e. the threads that really worked."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import tkv_oracle as O
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        from threadpoolctl import threadpool_limits
     except Exception:
-        cores = 1
+        threadpool_limits = None
     gpu, wl = res["gpu"], res["wl"]
     layers = [0, 1][: cfg.n_layers]
     n = gpu.layer_length(0)
     tiers = gpu.get_tiers()[:, :n]
-    orc = O.OracleCache(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, n,
-                        kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, k_sink=cfg.k_sink, k_window=cfg.k_window,
-                        layers=layers)
     f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
-    # rows as the GPU holds them are not needed for timing: same shapes and distributions, drawn again
+    # rows as the GPU holds them are not needed for timing: same shapes and distributions, drawn again; T2 rows keep
+    # their full-precision values (the decode is not part of an attention call in the oracle either)
+    K, V = {}, {}
     for l in layers:
         k, v = wl.context_kv(l)
-        pad = n - k.shape[1]
-        kk, vv = f64(k), f64(v)
+        kk, vv = f64(k).transpose(0, 2, 1, 3), f64(v).transpose(0, 2, 1, 3)      # [B, Hkv, ctx, d]
+        pad = n - kk.shape[2]
         if pad > 0:
-            kk = np.concatenate([kk, kk[:, :pad]], axis=1)
-            vv = np.concatenate([vv, vv[:, :pad]], axis=1)
-        orc.append(l, kk, vv)
-    orc.tier[:, :n] = tiers            # placement only; T2 rows keep full-precision values for the timing run
+            kk = np.concatenate([kk, kk[:, :, :pad]], axis=2)
+            vv = np.concatenate([vv, vv[:, :, :pad]], axis=2)
+        K[l], V[l] = np.ascontiguousarray(kk), np.ascontiguousarray(vv)
     q = f64(wl.step_q(0, 0))
+    live = tiers != 3
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    scale = 1.0 / np.sqrt(cfg.head_dim)
+    score = np.zeros((cfg.batch, n))
+    pairs = [(b, h) for b in range(cfg.batch) for h in range(cfg.n_kv_heads)]
+    workers = workers or min(len(pairs), os.cpu_count() or 1, 16)
+
+    def one(layer, b, h):
+        out, alpha = O.attend_gqa(q[b:b + 1, h * G:(h + 1) * G], K[layer][b:b + 1, h:h + 1], V[layer][b:b + 1, h:h + 1],
+                                  live[b:b + 1], scale)
+        return b, O.score_increment(alpha, 1.0 / (cfg.n_layers * cfg.n_q_heads))[0]
+
     n_full = int(((tiers == 0) | (tiers == 1)).sum())
     n_t2 = int((tiers == 2).sum())
-    per_call = call_bytes(cfg, n_full, n_t2)
-    calls, t0 = 0, time.perf_counter()
-    while True:
-        for l in layers:
-            orc.attend_and_score(l, q)
-            calls += 1
-        if time.perf_counter() - t0 > budget_s or calls >= 64:
-            break
-    dt = time.perf_counter() - t0
-    return {"value": per_call * calls / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{calls} attend_and_score calls on layers {layers} of the {cfg.name} workload "
-                      f"(batch {cfg.batch}, {n} tokens, final GPU tier assignment), {dt:.1f} s, numpy fp64",
-            "s_per_layer_call": dt / calls, "s_per_step_extrapolated": dt / calls * cfg.n_layers}
+    per_call = call_bytes(cfg, n_full, n_t2)[0]
+    calls = 0
+    import contextlib
+    with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
+        t0, c0 = time.perf_counter(), time.process_time()
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            while True:
+                for l in layers:
+                    for b, inc in ex.map(lambda p: one(l, *p), pairs):
+                        score[b] += inc
+                    calls += 1
+                if time.perf_counter() - t0 > budget_s or calls >= 64:
+                    break
+        dt, cpu_s = time.perf_counter() - t0, time.process_time() - c0
+    # one re-tiering event of the oracle (explicit sort per sequence) on the GPU run's scores
+    s32 = gpu.get_scores()
+    t1 = time.perf_counter()
+    for b in range(cfg.batch):
+        O.classify_sequence(s32[b], tiers[b], n, cfg.n_prompt, cfg.k_sink, cfg.k_window, cfg.policy_ppm)
+    classify_s = time.perf_counter() - t1
+    return {"value": per_call * calls / dt / 1e9, "unit": "GB/s", "cores": max(1, int(round(cpu_s / dt))), "kind": "oracle",
+            "sample": f"{calls} attend_and_score calls on layers {layers} of the {cfg.name} workload (batch {cfg.batch}, {n} tokens, "
+                      f"the GPU run's final tier assignment; rows drawn again, T2 rows at full precision), {dt:.1f} s, numpy fp64, "
+                      f"{workers} threads over the (sequence, kv head) pairs, {cpu_s / dt:.1f} of them busy on average",
+            "threads": workers, "s_per_layer_call": dt / calls, "s_per_step_extrapolated": dt / calls * cfg.n_layers,
+            "s_per_classify_event": classify_s}
 
 
-def link_probe():
+def link_probe(launch_bytes):
     import torch
+    import paper_2605_09490_amd as tkv
     n = 256 << 20
     d = torch.empty(n, dtype=torch.uint8, device="cuda")
     d2 = torch.empty_like(d)
@@ -208,7 +305,45 @@ def link_probe():
         torch.cuda.synchronize()
         gb = 4 * n / (time.perf_counter() - t0) / 1e9
         out[name + "_GBps"] = round(gb * (2 if name == "d2d_copy" else 1), 1)   # d2d: read + write
+    del d2, h
+    # a bare read-only kernel with the attention kernel's launch shape: over 1 GiB, and over one launch's bytes
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+    out["read_1GiB_GBps"] = round(tkv.probe_hbm_read(big, iters=4), 1)
+    nb = max(1 << 20, int(launch_bytes) // 4096 * 4096)
+    out["read_one_launch_GBps"] = round(tkv.probe_hbm_read(big[:nb], iters=16), 1)
+    out["read_one_launch_bytes"] = nb
     return out
+
+
+def compact_record(name, steps, rule):
+    """twin + lazy once for one of the other benchmark shapes: the figures only."""
+    from tkv_synth import CONFIGS
+    base = CONFIGS[name]
+    delta = base.reclassify_every
+    warm = 2
+    cfg = dataclasses.replace(base, decode_steps=(1 + SETTLE_EVENTS) * delta + warm + steps + delta)
+    pol = cfg.policy_ppm
+    twin_pol = (pol[0] + pol[1], 0, pol[2], pol[3])
+    release_memory()
+    t = run_job(cfg, twin_pol, "lazy", steps, warm, 0, "twin", rule, tight=True)
+    t.pop("gpu").close(); t.pop("wl")
+    release_memory()
+    r = run_job(cfg, pol, "lazy", steps, warm, delta, "lazy", rule, tight=True)
+    r.pop("gpu").close(); r.pop("wl")
+    release_memory()
+    value = r["bytes"] / r["wall_s"] / 1e9
+    kern = r["kernel_bytes_per_launch"] / (r["kernel_avg_us"] * 1e-6) / 1e9
+    call = r["call_bytes_per_launch"] / (r["call_avg_us"] * 1e-6) / 1e9
+    ev = max(r["events"], 1)
+    return {"workload": name, "steps": steps, "value_GBps": round(value, 1), "ms_per_step": round(r["ms_per_step"], 4),
+            "twin_ms_per_step": round(t["ms_per_step"], 4), "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),
+            "kernel_avg_us": round(r["kernel_avg_us"], 2), "kernel_frac": round(kern / HBM_PEAK_GBPS, 4),
+            "call_avg_us": round(r["call_avg_us"], 2), "call_frac": round(call / HBM_PEAK_GBPS, 4),
+            "call_bytes_per_launch": int(r["call_bytes_per_launch"]), "events_in_timed_region": r["events"],
+            "prefetch_overhead_pct": round(100.0 * (r["wall_s"] - t["wall_s"]) / ev / (delta * t["wall_s"] / steps), 2),
+            "cold_fill_ms": round(r["cold_fill_ms"], 1), "cold_fill_bytes": r["cold_fill_bytes"],
+            "tier_count": r["tier_count"], "score_top20_share": round(r.get("top20_share", 0), 3),
+            "score_bottom50_share": round(r.get("bottom50_share", 0), 3)}
 
 
 def main():
@@ -226,6 +361,10 @@ def main():
                          "and steady ones as the timed region)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
+    ap.add_argument("--others", default="7b,32b,prod",
+                    help="comma-separated other workloads to add a compact record for (twin + lazy once each); '' for none. "
+                         "They are skipped, and the line says so, once the run has taken --others-budget seconds")
+    ap.add_argument("--others-budget", type=float, default=100.0)
     ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "f16", "f32"], help="K, V and query type (default: the workload's own)")
     ap.add_argument("--delta", type=int, default=0, help="re-tier every DELTA steps (default: the workload's own)")
     ap.add_argument("--k-window", type=int, default=-1, help="protected recent window (default: the workload's own)")
@@ -246,18 +385,22 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    probe = link_probe()     # before the caches exist: the largest workload leaves little pinned memory to spare
+    t_start = time.perf_counter()
     base = CONFIGS[args.workload]
-    warmup = max(args.warmup, 1)
+    warmup = max(args.warmup, 0)
+    delta = args.delta or base.reclassify_every
     if args.profile_steps < 0:
-        args.profile_steps = args.delta or base.reclassify_every
-    cfg = dataclasses.replace(base, decode_steps=warmup + args.steps + args.profile_steps,
-                              reclassify_every=args.delta or base.reclassify_every,
+        args.profile_steps = delta
+    cfg = dataclasses.replace(base, decode_steps=(1 + SETTLE_EVENTS) * delta + warmup + args.steps + args.profile_steps,
+                              reclassify_every=delta,
                               kv_dtype=args.kv_dtype or base.kv_dtype,
                               k_window=base.k_window if args.k_window < 0 else args.k_window)
     rule = 1 if args.count_rule == "alg1" else 0
     pol = cfg.policy_ppm
     twin_pol = (pol[0] + pol[1], 0, pol[2], pol[3])
+    # before the caches exist: the largest workload leaves little pinned memory to spare
+    est = call_bytes(cfg, int(cfg.batch * cfg.context * (pol[0] + pol[1]) / 1e6), int(cfg.batch * cfg.context * pol[2] / 1e6))[0]
+    probe = link_probe(est)
     log(f"[bench] workload {cfg.name}: L={cfg.n_layers} B={cfg.batch} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} D={cfg.head_dim} "
         f"{cfg.kv_dtype} ctx={cfg.context} policy={pol} t2={cfg.t2_format} mode={args.mode}")
     other_mode = "wait" if args.mode == "lazy" else "lazy"
@@ -270,6 +413,7 @@ def main():
                                               ["twin", other_mode, args.mode, "twin", other_mode, args.mode])
     runs = {k: [] for k in kinds}
     runs_all_in = {k: [] for k in kinds}     # timed loop + the initial tiering with its cold fill
+    events = {}
     main_res, cpu = None, None
     mem = {}
     for kind in kinds:
@@ -278,28 +422,59 @@ def main():
                     args.steps, warmup, args.profile_steps if is_main else 0, kind, rule)
         runs[kind].append(r["wall_s"])
         runs_all_in[kind].append(r["wall_s"] + r["cold_fill_ms"] * 1e-3)
-        log(f"[bench] {kind}: {r['ms_per_step']:.3f} ms/step" + (f", cold fill {r['cold_fill_ms']:.1f} ms" if is_main else ""))
+        events[kind] = r["events"]
+        log(f"[bench] {kind}: {r['ms_per_step']:.3f} ms/step, {r['events']} event(s) in the timed region"
+            + (f", cold fill {r['cold_fill_ms']:.1f} ms, first score-driven event {r['first_event_ms']:.1f} ms" if is_main else ""))
         mem[kind] = r.pop("device_bytes")
         if is_main:
             main_res = r
             if not args.no_cpu:
                 cpu = cpu_baseline(cfg, main_res)
-                log(f"[bench] oracle: {cpu['s_per_layer_call']*1e3:.1f} ms per layer call on {cpu['cores']} threads")
+                log(f"[bench] oracle: {cpu['s_per_layer_call']*1e3:.1f} ms per layer call, {cpu['cores']} cores busy of {cpu['threads']} threads")
         r.pop("gpu").close(); r.pop("wl")
+        release_memory()
     extra = {}
     if not args.no_twin:
         best = {k: min(v) for k, v in runs.items()}
         best_all = {k: min(v) for k, v in runs_all_in.items()}
+        twin_step = best["twin"] / args.steps
+
+        def per_event_ms(kind):
+            return (best[kind] - best["twin"]) * 1e3 / max(events[kind], 1)
+
+        def amortised(kind):
+            # one event every Delta steps: the steady state of a long run, whatever --steps is
+            return round(100.0 * per_event_ms(kind) * 1e-3 / (delta * twin_step), 2)
+
         extra = {
+            "prefetch_overhead_pct": amortised(args.mode),
+            "prefetch_overhead_ms_per_event": round(per_event_ms(args.mode), 3),
+            "prefetch_overhead_timed_region_pct": round(100.0 * (best[args.mode] - best["twin"]) / best["twin"], 2),
             "prefetch_overhead_all_in_pct": round(100.0 * (best_all[args.mode] - best_all["twin"]) / best_all["twin"], 2),
-            "prefetch_overhead_pct": round(100.0 * (best[args.mode] - best["twin"]) / best["twin"], 2),
-            **({} if stream else {f"prefetch_overhead_pct_{other_mode}": round(100.0 * (best[other_mode] - best["twin"]) / best["twin"], 2)}),
+            **({} if stream else {f"prefetch_overhead_pct_{other_mode}": amortised(other_mode),
+                                  f"prefetch_overhead_timed_region_pct_{other_mode}":
+                                      round(100.0 * (best[other_mode] - best["twin"]) / best["twin"], 2)}),
+            "overhead_definition": "(timed-region wall time - the all-in-HBM twin's) per re-tiering event in the region, over "
+                                   "Delta twin steps; *_timed_region_pct is the plain ratio over the --steps timed steps",
             "ms_per_step_runs": {k: [round(w * 1e3 / args.steps, 4) for w in v] for k, v in runs.items()},
         }
     value = main_res["bytes"] / main_res["wall_s"] / 1e9
-    kernel_GBps = main_res["kernel_bytes_per_launch"] / (main_res["kernel_avg_us"] * 1e-6) / 1e9 if main_res.get("kernel_avg_us") else None
+    has_prof = bool(main_res.get("kernel_avg_us"))
+    kernel_GBps = main_res["kernel_bytes_per_launch"] / (main_res["kernel_avg_us"] * 1e-6) / 1e9 if has_prof else None
+    call_GBps = main_res["call_bytes_per_launch"] / (main_res["call_avg_us"] * 1e-6) / 1e9
     h2d_GBps = main_res["h2d_bytes"] / (main_res["h2d_ms"] * 1e-3) / 1e9 if main_res["h2d_ms"] > 0 else None
     d2h_GBps = main_res["d2h_bytes"] / (main_res["d2h_ms"] * 1e-3) / 1e9 if main_res["d2h_ms"] > 0 else None
+    others, skipped = [], []
+    for name in [w for w in args.others.split(",") if w and w != args.workload]:
+        if time.perf_counter() - t_start > args.others_budget:
+            skipped.append(name)
+            continue
+        try:
+            others.append(compact_record(name, 2 * (CONFIGS[name].reclassify_every), rule))
+            log(f"[bench] {name}: {others[-1]['ms_per_step']:.3f} ms/step, kernel {others[-1]['kernel_avg_us']:.1f} us")
+        except Exception as e:  # a shape that does not fit this box must not lose the main line
+            others.append({"workload": name, "error": f"{type(e).__name__}: {e}"[:300]})
+    achievable = probe.get("read_one_launch_GBps")
     line = {
         "metric": "tiered decode-attn KV GB/s & % of HBM peak; T1 prefetch overhead % of step",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": warmup,
@@ -310,20 +485,34 @@ def main():
                                f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"
                                + (f", k_window {cfg.k_window}" if args.k_window >= 0 else "")
                                + (", Algorithm-1 count rule" if rule else "")
-                               + (", value-aware scorer" if SCORER != "attention" else "")},
+                               + (", value-aware scorer" if SCORER != "attention" else ""),
+                   "untimed_pre_roll_steps": (1 + SETTLE_EVENTS) * delta + warmup,
+                   "score_driven_events_before_timing": SETTLE_EVENTS},
         "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),
         "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
         "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(kernel_GBps / HBM_PEAK_GBPS, 4) if kernel_GBps else None,
-                     "traffic": (sum(MEASURED_TRAFFIC[cfg.name].values()) if cfg.name in MEASURED_TRAFFIC else None),
+                     "traffic": measured_traffic(cfg.name),
                      "kernel": "k_attn_tiered", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
                      "algorithmic_bytes_per_launch": int(main_res.get("kernel_bytes_per_launch", 0)),
-                     "launches_timed": main_res.get("kernel_launches")},
+                     "launches_timed": main_res.get("kernel_launches"),
+                     "achievable": achievable,
+                     "frac_of_achievable": round(kernel_GBps / achievable, 4) if kernel_GBps and achievable else None,
+                     "call": {"what": "one tkv_attend_and_score (k_attn_tiered + k_attn_finish) as the timed region ran it: every "
+                                      "decode step bracketed by one pair of HIP events on the compute stream, divided by its layer calls",
+                              "avg_us": round(main_res.get("call_avg_us", 0), 2),
+                              "finish_kernel_avg_us": round(main_res.get("finish_avg_us", 0), 2),
+                              "algorithmic_bytes": int(main_res.get("call_bytes_per_launch", 0)),
+                              "achieved": round(call_GBps, 1) if call_GBps else None,
+                              "frac": round(call_GBps / HBM_PEAK_GBPS, 4) if call_GBps else None}},
         "cpu_baseline": cpu,
         "t1": {"events_in_timed_region": main_res["events"], "h2d_bytes": main_res["h2d_bytes"], "d2h_bytes": main_res["d2h_bytes"],
                "h2d_GBps": round(h2d_GBps, 1) if h2d_GBps else None, "d2h_GBps": round(d2h_GBps, 1) if d2h_GBps else None,
                "h2d_link_frac": round(h2d_GBps / LINK_PEAK_GBPS, 3) if h2d_GBps else None,
                "cold_fill_ms": round(main_res["cold_fill_ms"], 1), "cold_fill_bytes": main_res["cold_fill_bytes"],
+               "first_score_driven_event_ms": round(main_res["first_event_ms"], 1),
+               "first_score_driven_event_bytes": main_res["first_event_bytes"],
+               "settled_event_ms": round(main_res["settle_event_ms"], 1), "settled_event_bytes": main_res["settle_event_bytes"],
                "classify_ms_per_event": round(main_res["classify_ms"] / max(main_res["events"], 1), 3),
                "migrate_ms_per_event": round(main_res["migrate_ms"] / max(main_res["events"], 1), 3),
                "attend_waits": main_res["attend_waits"], "lazy_old_reads": main_res["lazy_old_reads"],
@@ -332,7 +521,8 @@ def main():
         "tier_count": main_res["tier_count"],
         "score_top20_share": round(main_res.get("top20_share", 0), 3), "score_bottom50_share": round(main_res.get("bottom50_share", 0), 3),
         "score_mass_rel_err": main_res.get("score_mass_rel_err"),
-        "probe": probe, "host_cores": os.cpu_count(),
+        "other_workloads": others, "other_workloads_skipped": skipped,
+        "probe": probe, "host_cores": os.cpu_count(), "bench_wall_s": round(time.perf_counter() - t_start, 1),
     }
     print(json.dumps(line), flush=True)
 

@@ -105,7 +105,8 @@ typedef struct {
                                           of one plan plus the rows entering it, not the history of all plans */
   int64_t bounce_bytes;                /* size of each of the two device bounce rings used for T1 traffic; 0 -> 64 MiB */
   int32_t prefetch_mode;               /* tkv_prefetch_mode */
-  int32_t profile;                     /* != 0: time every attention kernel with HIP events (tkv_get_stats) */
+  int32_t profile;                     /* bit 0: time every attention kernel with HIP events; bit 1: time every
+                                          tkv_decode_step with one pair of HIP events (tkv_get_stats) */
   int32_t scorer;                      /* tkv_scorer */
   int32_t device;                      /* HIP device ordinal */
   void* (*dev_alloc)(size_t bytes, void* ctx); /* device memory, 256-byte aligned; NULL -> hipMalloc */
@@ -131,7 +132,7 @@ typedef struct {
   int64_t h2d_bytes, d2h_bytes; /* T1 traffic over the host link since creation */
   int64_t h2d_copies, d2h_copies;
   double h2d_ms, d2h_ms;      /* event-timed busy time of those copies */
-  double attn_kernel_ms;      /* profile != 0: summed duration of the attention kernels */
+  double attn_kernel_ms;      /* profile != 0: summed duration of the attention kernels (the dominant kernel of a call) */
   int64_t attn_kernel_launches;
   double classify_ms, migrate_ms; /* host wall time spent inside the calls */
   int64_t attend_waits;       /* WAIT mode: attention calls that were ordered behind a prefetch event */
@@ -143,6 +144,12 @@ typedef struct {
                                  (positions no longer in T1) would have cost more link time than the rewrite */
   int64_t device_bytes;       /* device memory the cache holds (pools, frames, lists, scratch) */
   int64_t pinned_bytes;       /* pinned host memory the cache holds */
+  double attn_finish_ms;      /* profile != 0: summed duration of the finishing kernels (merge, output, scores) */
+  double attn_call_ms;        /* profile bit 0: summed time from the start of a call's first kernel to the end of its last
+                                 (the event pairs around every kernel stretch the gaps between them) */
+  double step_ms;             /* profile bit 1: summed device time of the tkv_decode_step calls, from an event before the
+                                 append launch to one behind the last layer's finishing kernel */
+  int64_t steps_timed;
 } tkv_stats;
 
 /* ---- life cycle ------------------------------------------------------------------------------ */
@@ -232,8 +239,13 @@ tkv_status tkv_get_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head
  * landed. */
 tkv_status tkv_wait_prefetch(tkv_cache* c);
 tkv_status tkv_get_stats(tkv_cache* c, tkv_stats* out);
-/* Switches the per-kernel HIP-event timing of the attention kernels on or off (see tkv_config.profile). */
+/* Sets the timing bits of tkv_config.profile (0: off, 1: per kernel, 2: per decode step, 3: both). */
 tkv_status tkv_set_profile(tkv_cache* c, int32_t on);
+/* Measurement helper (no cache needed): streams `bytes` of device memory through a read-only kernel with the attention
+ * kernel's launch shape (one 512-lane workgroup per compute unit, 16-byte loads), iters times after one warm-up pass, on
+ * the current device; *ms_per_pass (host) receives the average kernel time from the dispatch's own timestamps.  What a
+ * launch of that size can reach on this GPU at best: the yardstick next to the published peak. */
+tkv_status tkv_probe_hbm_read(const void* device_buf, size_t bytes, int32_t iters, void* hip_stream, float* ms_per_pass);
 int32_t tkv_layer_length(const tkv_cache* c, int32_t layer); /* -1 on bad arguments */
 const char* tkv_last_error(const tkv_cache* c);
 

@@ -54,6 +54,7 @@ class tkv_stats(C.Structure):
         ("classify_ms", C.c_double), ("migrate_ms", C.c_double),
         ("attend_waits", C.c_int64), ("lazy_old_reads", C.c_int64), ("n_classify", C.c_int64), ("n_migrate", C.c_int64),
         ("n_rehome", C.c_int64), ("host_rows_used", C.c_int64), ("n_repack", C.c_int64), ("device_bytes", C.c_int64), ("pinned_bytes", C.c_int64),
+        ("attn_finish_ms", C.c_double), ("attn_call_ms", C.c_double), ("step_ms", C.c_double), ("steps_timed", C.c_int64),
     ]
 
 
@@ -80,6 +81,7 @@ SYMBOLS = {
     "tkv_get_row": (C.c_int, [_VP, _I32, _I32, _I32, _I32, _I32, _VP]),
     "tkv_wait_prefetch": (C.c_int, [_VP]),
     "tkv_get_stats": (C.c_int, [_VP, C.POINTER(tkv_stats)]),
+    "tkv_probe_hbm_read": (C.c_int, [_VP, C.c_size_t, _I32, _VP, C.POINTER(C.c_float)]),
     "tkv_layer_length": (_I32, [_VP, _I32]),
     "tkv_last_error": (C.c_char_p, [_VP]),
     "tkv_tier_counts": (C.c_int, [C.POINTER(tkv_policy), C.c_int64, C.c_int64, C.POINTER(C.c_int64)]),
@@ -118,6 +120,18 @@ def tier_counts(policy_ppm, m, n_already_evicted=0, count_rule=0):
     return tuple(int(x) for x in out)
 
 
+def probe_hbm_read(buf, iters=8, stream=None):
+    """GB/s a read-only streaming kernel reaches over the CUDA tensor `buf` (average of `iters` passes)."""
+    lib = load_library()
+    nbytes = buf.numel() * buf.element_size()
+    ms = C.c_float(0.0)
+    st = lib.tkv_probe_hbm_read(C.c_void_p(buf.data_ptr()), nbytes, int(iters),
+                                C.c_void_p((stream or torch.cuda.current_stream()).cuda_stream), C.byref(ms))
+    if st != TKV_OK:
+        raise TkvError(st, "tkv_probe_hbm_read")
+    return nbytes / (ms.value * 1e-3) / 1e9
+
+
 class TieredKV:
     """Handle on one tkv_cache.  Methods mirror the C entry points; tensors are torch CUDA tensors."""
 
@@ -152,10 +166,13 @@ class TieredKV:
         cfg.device = device
         if use_torch_allocator:
             # PyTorch supplies device and pinned memory; the library only sees raw pointers
+            self._alloc_error = ""
+
             def _dev_alloc(nbytes, _ctx):
                 try:
                     t = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
-                except RuntimeError:
+                except RuntimeError as e:
+                    self._alloc_error = f"device allocation of {int(nbytes)} bytes failed: {str(e)[:200]}"
                     return None
                 self._held[t.data_ptr()] = t
                 return t.data_ptr()
@@ -163,7 +180,8 @@ class TieredKV:
             def _pin_alloc(nbytes, _ctx):
                 try:
                     t = torch.empty(int(nbytes), dtype=torch.uint8, pin_memory=True)
-                except RuntimeError:
+                except RuntimeError as e:
+                    self._alloc_error = f"pinned allocation of {int(nbytes)} bytes failed: {str(e)[:200]}"
                     return None
                 self._held[t.data_ptr()] = t
                 return t.data_ptr()
@@ -177,7 +195,8 @@ class TieredKV:
         h = C.c_void_p()
         st = self.lib.tkv_create(C.byref(cfg), C.byref(h))
         if st != TKV_OK:
-            raise TkvError(st, self.lib.tkv_last_error(None).decode())
+            why = getattr(self, "_alloc_error", "")
+            raise TkvError(st, self.lib.tkv_last_error(None).decode() + (f" ({why})" if why else ""))
         self._h = h
 
     # -- helpers ---------------------------------------------------------------------------------
@@ -254,7 +273,7 @@ class TieredKV:
         return out_all
 
     def set_profile(self, on):
-        self._check(self.lib.tkv_set_profile(self._h, 1 if on else 0))
+        self._check(self.lib.tkv_set_profile(self._h, int(on)))
 
     def classify(self, policy_ppm, stream=None, count_rule=0):
         pol = tkv_policy(*[int(x) for x in policy_ppm], int(count_rule))

@@ -990,10 +990,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 // ---- dispatch ----------------------------------------------------------------------------------------------
 // The file is compiled once per part (TKV_ATTN_PART = 0..3, 5, 6: one (head_dim, KV dtype) pair of attn_tiered each,
 // 4: attn_finish and the launchers), so the parts build in parallel; without the macro it is one translation unit.
-// TKV_ATTN_ONLY_BF16_128 (kernel experiments) builds one unit with the bf16, head_dim 128 kernels alone.
-#if defined(TKV_ATTN_ONLY_BF16_128)
-#define TKV_HAS_PART(p) ((p) == 0 || (p) == 4)
-#elif defined(TKV_ATTN_PART)
+#if defined(TKV_ATTN_PART)
 #define TKV_HAS_PART(p) (TKV_ATTN_PART == (p))
 #else
 #define TKV_HAS_PART(p) 1
@@ -1048,22 +1045,18 @@ TKV_DEFINE_PART(64, KT_F16)
 #endif
 
 #if TKV_HAS_PART(4)
-#if defined(TKV_ATTN_ONLY_BF16_128)
-template <int D, int KT>
-hipError_t tiered_by_group(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipErrorInvalidValue; }
-#else
 template <> hipError_t tiered_by_group<128, KT_BF16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
 template <> hipError_t tiered_by_group<128, KT_F32>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
 template <> hipError_t tiered_by_group<128, KT_F16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
 template <> hipError_t tiered_by_group<64, KT_BF16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
 template <> hipError_t tiered_by_group<64, KT_F32>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
 template <> hipError_t tiered_by_group<64, KT_F16>(const AttnArgs&, int, hipStream_t, hipEvent_t, hipEvent_t);
-#endif
 
 template <int D, int G, int KT>
-static hipError_t run_finish(const AttnArgs& a, hipStream_t st) {
+static hipError_t run_finish(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const int tiles = a.n_tiles;
-  hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, a, tiles);
+  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, ev0, ev1, 0, a, tiles);
+  else hipLaunchKernelGGL((k_attn_finish<D, G>), dim3(tiles + a.Hq, a.B), dim3(256), 0, st, a, tiles);
   return hipGetLastError();
 }
 
@@ -1079,10 +1072,30 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream
 int attn_waves_per_group(int D, int elem_bytes, int G) { return waves_per_group(D * elem_bytes, G); }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
 
-hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st) {
-  if (D == 128) { TKV_DISPATCH_G(run_finish, 128, KT_BF16, a, st) }
-  if (D == 64) { TKV_DISPATCH_G(run_finish, 64, KT_BF16, a, st) }
+hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (D == 128) { TKV_DISPATCH_G(run_finish, 128, KT_BF16, a, st, ev0, ev1) }
+  if (D == 64) { TKV_DISPATCH_G(run_finish, 64, KT_BF16, a, st, ev0, ev1) }
   return hipErrorInvalidValue;
+}
+
+// ---- bandwidth probe: what a plain streaming read of `bytes` reaches with the attention kernel's launch shape ----
+// One workgroup per compute unit, 512 lanes, 16-byte loads, four independent loads in flight per lane; nothing is
+// written unless the data says so (it never does for the probe's buffer), so the traffic is the read alone.
+__global__ __launch_bounds__(512) void k_probe_read(const u32x4* __restrict__ src, size_t n16, uint32_t* sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+    const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) { const u32x4 a = __builtin_nontemporal_load(src + i); acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+  if (acc == 0x9E3779B9u) *sink = acc;
+}
+hipError_t launch_probe_read(const void* src, size_t bytes, int workgroups, uint32_t* sink, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  hipExtLaunchKernelGGL(k_probe_read, dim3(workgroups), dim3(512), 0, st, ev0, ev1, 0, (const u32x4*)src, bytes / 16, sink);
+  return hipGetLastError();
 }
 #endif
 

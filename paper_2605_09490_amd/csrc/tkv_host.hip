@@ -106,6 +106,7 @@ struct tkv_cache {
   int64_t fill_piece = 0;
   std::vector<EvPair> copy_events; size_t copy_events_used = 0;
   std::vector<EvPair> prof_events; size_t prof_used = 0;
+  std::vector<EvPair> step_events; size_t step_used = 0;   // profile & 2: one pair around every tkv_decode_step
   tkv_stats st{};
 };
 
@@ -275,11 +276,32 @@ tkv_status harvest_profile(tkv_cache* c) {
     float ms = 0.f;
     HIPCHK(c, hipEventSynchronize(c->prof_events[i].b));
     if (hipEventElapsedTime(&ms, c->prof_events[i].a, c->prof_events[i].b) == hipSuccess) {
-      c->st.attn_kernel_ms += ms;
-      if (c->prof_events[i].dir != 2) c->st.attn_kernel_launches += 1;   // 2: second launch of the same layer call
+      if (c->prof_events[i].dir == 3) {
+        // the finishing kernel of a call: its own duration, and the whole call from the first kernel's start
+        c->st.attn_finish_ms += ms;
+        float call = 0.f;
+        if (c->prof_events[i].bytes >= 0 &&
+            hipEventElapsedTime(&call, c->prof_events[(size_t)c->prof_events[i].bytes].a, c->prof_events[i].b) == hipSuccess)
+          c->st.attn_call_ms += call;
+      } else {
+        c->st.attn_kernel_ms += ms;
+        if (c->prof_events[i].dir != 2) c->st.attn_kernel_launches += 1;   // 2: second launch of the same layer call
+      }
     }
   }
   c->prof_used = 0;
+  // step pairs: only those whose step has finished (no wait: the call may come in the middle of a timed loop); the
+  // pairs still in flight move to the front of the pool
+  size_t done = 0;
+  while (done < c->step_used && hipEventQuery(c->step_events[done].b) == hipSuccess) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->step_events[done].a, c->step_events[done].b) == hipSuccess) { c->st.step_ms += ms; c->st.steps_timed += 1; }
+    ++done;
+  }
+  if (done > 0) {
+    std::rotate(c->step_events.begin(), c->step_events.begin() + done, c->step_events.begin() + c->step_used);
+    c->step_used -= done;
+  }
   return TKV_OK;
 }
 
@@ -544,6 +566,7 @@ void tkv_destroy(tkv_cache* c) {
   for (auto e : c->ev_gath) if (e) (void)hipEventDestroy(e);
   for (auto& p : c->copy_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (auto& p : c->prof_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (auto& p : c->step_events) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (void* p : c->dev_allocs) { if (c->cfg.dev_free) c->cfg.dev_free(p, c->cfg.alloc_ctx); else (void)hipFree(p); }
   for (void* p : c->pin_allocs) { if (c->cfg.pin_free) c->cfg.pin_free(p, c->cfg.alloc_ctx); else (void)hipHostFree(p); }
   delete c;
@@ -658,17 +681,17 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim;
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
-  if (c->cfg.profile && !noalloc) {
-    pe = next_pair(c->prof_events, c->prof_used);
-    if (!pe) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+  EvPair* pf = nullptr;
+  if ((c->cfg.profile & 1) && !noalloc) {
+    const size_t i0 = c->prof_used;
+    if (!next_pair(c->prof_events, c->prof_used) || (S2 > 0 && !next_pair(c->prof_events, c->prof_used)) ||
+        !next_pair(c->prof_events, c->prof_used))
+      return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+    pe = &c->prof_events[i0];          // taken after the pool has stopped growing
     pe->dir = 0;
-    if (S2 > 0) {
-      const size_t i0 = c->prof_used - 1;
-      pe2 = next_pair(c->prof_events, c->prof_used);
-      if (!pe2) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
-      pe2->dir = 2;
-      pe = &c->prof_events[i0];        // the pool may have grown
-    }
+    if (S2 > 0) { pe2 = &c->prof_events[i0 + 1]; pe2->dir = 2; }
+    pf = &c->prof_events[c->prof_used - 1];
+    pf->dir = 3; pf->bytes = (int64_t)i0;   // index of the call's first kernel
   }
   HIPCHK(c, launch_attn_tiered(a, v.D, c->G, c->kt, st, pe ? pe->a : nullptr, pe ? pe->b : nullptr));
   if (S2 > 0) {
@@ -679,7 +702,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
     a2.S = S2; a2.s0 = S; a2.second = 1;
     HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->kt, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
-  HIPCHK(c, launch_attn_finish(a, v.D, c->G, st));
+  HIPCHK(c, launch_attn_finish(a, v.D, c->G, st, pf ? pf->a : nullptr, pf ? pf->b : nullptr));
   if (!last || noalloc) return TKV_OK;
   if (c->streamed && S2 > 0) {
     HIPCHK(c, hipEventRecord(c->ev_free[fr], st));
@@ -745,6 +768,12 @@ tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, c
     if (n + 1 > c->cfg.max_tokens) return fail(c, TKV_ECAPACITY, "tkv_decode_step: %d + 1 exceeds max_tokens %d", n, c->cfg.max_tokens);
     for (int b = 0; b < v.B; ++b)
       if (c->free0[b] < 1) return fail(c, TKV_ECAPACITY, "tkv_decode_step: HBM pool of sequence %d is full", b);
+    EvPair* se = nullptr;
+    if (c->cfg.profile & 2) {
+      se = next_pair(c->step_events, c->step_used);
+      if (!se) return fail(c, TKV_EDEVICE, "hipEventCreate failed");
+      HIPCHK(c, hipEventRecord(se->a, (hipStream_t)hip_stream));
+    }
     HIPCHK(c, launch_append_step(v, k_all, v_all, n, (hipStream_t)hip_stream));
     for (int b = 0; b < v.B; ++b) { c->free0[b] -= 1; c->nF[b] += 1; }
     c->ntier[0] += v.B;
@@ -754,6 +783,7 @@ tkv_status tkv_decode_step(tkv_cache* c, const void* k_all, const void* v_all, c
       tkv_status s = tkv_attend_and_score(c, l, (const char*)q_all + l * q_stride, (char*)out_all + l * o_stride, hip_stream);
       if (s != TKV_OK) return s;
     }
+    if (se) HIPCHK(c, hipEventRecord(se->b, (hipStream_t)hip_stream));
     return TKV_OK;
   }
   for (int l = 0; l < v.L; ++l) {
@@ -1092,9 +1122,31 @@ tkv_status tkv_get_row(tkv_cache* c, int32_t layer, int32_t seq, int32_t kv_head
   return fail(c, TKV_ESTATE, "tkv_get_row: position %d is in tier %d", pos, tier);
 }
 
+tkv_status tkv_probe_hbm_read(const void* device_buf, size_t bytes, int32_t iters, void* hip_stream, float* ms_per_pass) {
+  if (!device_buf || bytes < 16 || iters < 1 || !ms_per_pass) return TKV_EINVAL;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return TKV_EDEVICE;
+  uint32_t* sink = (uint32_t*)scratch_on_device(dev);      // never written: the probe's condition does not hold for its data
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (!sink || hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return TKV_EDEVICE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  double total = 0.0;
+  tkv_status rc = TKV_OK;
+  for (int i = 0; i < iters + 1 && rc == TKV_OK; ++i) {      // the first pass warms up and is not counted
+    float ms = 0.f;
+    if (launch_probe_read(device_buf, bytes, cus, sink, st, e0, e1) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = TKV_EDEVICE;
+    if (i > 0) total += ms;
+  }
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  *ms_per_pass = (float)(total / iters);
+  return rc;
+}
+
 tkv_status tkv_set_profile(tkv_cache* c, int32_t on) {
   if (!c) return TKV_EINVAL;
-  c->cfg.profile = on ? 1 : 0;
+  c->cfg.profile = on & 3;
   return TKV_OK;
 }
 

@@ -111,7 +111,8 @@ struct AttnArgs {
 // launchers (defined in the .hip files)
 // kt: type of K, V and q (0 binary32, 1 bfloat16, 2 binary16)
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
-hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st);
+hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_probe_read(const void* src, size_t bytes, int workgroups, uint32_t* sink, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 int attn_waves_per_group(int D, int elem_bytes, int G);   // waves per attention workgroup (one workgroup per compute unit)
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles);   // how many of a pair's waves serve the Q list
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
