@@ -77,6 +77,13 @@ __device__ __forceinline__ u32x4 lds_rd128(uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
   return v;
 }
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_rd64(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
 template <int OFF>
 __device__ __forceinline__ uint32_t lds_rd32(uint32_t addr) {
   uint32_t v;
@@ -94,6 +101,7 @@ __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)"
 // values read by lds_rd* may be used only after lds_wait() and tie() of the variable
 __device__ __forceinline__ void tie(u32x4& v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ void tie(uint32_t& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void tie(u32x2& v) { asm volatile("" : "+v"(v)); }
 template <class T, int N>
 __device__ __forceinline__ void tie(T (&v)[N]) {
 #pragma unroll
@@ -409,7 +417,8 @@ __device__ __forceinline__ void row_accumulate(const VStep<D, G, M>& vr, float s
 // LDS regions of one wave (pointers for the direct loads, byte addresses for the reads)
 struct WaveLds {
   char* t; char* sk; char* sv; char* lt;   // tile buffer (K rows, then V rows, in turn), K scales, V scales, slot lists (2 x 64 ints)
-  uint32_t ta, ska, sva, lta, pa;          // the same as LDS addresses, and the probabilities
+  char* p;                                 // probabilities of the current tile (before the first tile: the query block)
+  uint32_t ta, ska, sva, lta, pa;          // the same as LDS addresses
 };
 
 template <int SZ>
@@ -462,29 +471,33 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
 
   if (tile0 * 64 >= n_list) return;
 
-  // the lane's units of the G query vectors
+  // The first tile's slot list is asked for before anything else: the compute unit serves its waves' requests in
+  // the order they were made, and a list request that came behind another wave's rows would wait for all of them.
+  dma<4>(rl, w.lt, (uint32_t)(tile0 * 64 + lane) * 4u, 0);
+
+  // The lane's units of the G query vectors.  16-bit queries (G * D * 2 bytes, contiguous) come in through the
+  // probability region of the LDS, as NQD direct loads of 1 KB whose count the waits below can name; binary32
+  // queries are fetched by ordinary loads (the wait for the list then waits for them as well).
   QRegs<D, G, M, KT> q;
-  {
-    constexpr int qes = QBF ? 2 : 4;
-    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + kvh * G) * D * qes;
+  constexpr int NQD = QBF ? (G * D * 2 + 1023) / 1024 : 0;
+  static_assert(NQD * 1024 <= 64 * GP * 4, "the query block is parked in the probability region");
+  if constexpr (QBF) {
+    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + kvh * G) * D * 2;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc(qb, (uint32_t)(G * D * 2));   // lanes past the block fetch zeros
+#pragma unroll
+    for (int i = 0; i < NQD; ++i) dma<16>(rq, w.p + i * 1024, (uint32_t)(i * 1024 + lane * 16), 0);
+  } else {
+    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + kvh * G) * D * 4;
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
       for (int j = 0; j < KU; ++j) {
-        const char* src = qb + ((size_t)h * D + (size_t)(j * 8 + r8) * EUK) * qes;
+        const char* src = qb + ((size_t)h * D + (size_t)(j * 8 + r8) * EUK) * 4;
         float sacc = 0.f;
-        if constexpr (QBF) {
 #pragma unroll
-          for (int c = 0; c < EUK / 2; ++c) {
-            q.qp[h][j][c] = ((const uint32_t*)src)[c];
-            if constexpr (GE::IS_Q) sacc += H ? f16_lo(q.qp[h][j][c]) + f16_hi(q.qp[h][j][c]) : bf_lo(q.qp[h][j][c]) + bf_hi(q.qp[h][j][c]);
-          }
-        } else {
-#pragma unroll
-          for (int c = 0; c < EUK; ++c) {
-            q.qf[h][j][c] = ((const float*)src)[c];
-            if constexpr (GE::IS_Q) sacc += q.qf[h][j][c];
-          }
+        for (int c = 0; c < EUK; ++c) {
+          q.qf[h][j][c] = ((const float*)src)[c];
+          if constexpr (GE::IS_Q) sacc += q.qf[h][j][c];
         }
         q.qs[h][j] = sacc;
       }
@@ -542,21 +555,74 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
     dma<VS>(rvv, w.t + v * VIB, (uint32_t)lv[it] * (uint32_t)RB + vcol + (uint32_t)u * VS, 1);
   };
 
-  // ---- prologue: the first tile's slot list, then its scales and K rows in the order of a tile period
-  issue_loc(0, tile0);
-  wait_vm<0>();
+  // ---- prologue: the first tile's slot list has been asked for; then its scales and K rows in the order of a tile
+  // period, and the query block out of the LDS into registers
+  wait_vm<NQD>();                                        // the list is in (binary32 queries: and the queries)
   read_locs_k(0, n_list - tile0 * 64);
   issue_loc(1, tile0 + tstride);
   issue_kscale();
   issue_vscale();
 #pragma unroll
   for (int s = 0; s < N_K; ++s) issue_k_piece(s);
+  if constexpr (QBF) {
+    wait_vm<1 + 2 * SCD + N_K>();                        // everything older than the second list: the query block
+    // a unit of a query is EUK 16-bit elements: 8 bytes (one ds_read_b64) or QB pieces of 16
+    constexpr int QW = EUK / 2, QB = QW / 4;
+    static_assert(QW == 2 || QW % 4 == 0, "query units are 8 bytes or whole 16-byte pieces");
+    const uint32_t q_rd = w.pa + (uint32_t)r8 * (EUK * 2);
+    if constexpr (QW == 2) {
+      u32x2 t[G][KU];
+      static_for<G>([&](auto hc) {
+        constexpr int h = decltype(hc)::value;
+        static_for<KU>([&](auto jc) { constexpr int j = decltype(jc)::value; t[h][j] = lds_rd64<h * D * 2 + j * 8 * EUK * 2>(q_rd); });
+      });
+      lds_wait();
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int j = 0; j < KU; ++j) { tie(t[h][j]); q.qp[h][j][0] = t[h][j].x; q.qp[h][j][1] = t[h][j].y; }
+    } else {
+      u32x4 t[G][KU][QB > 0 ? QB : 1];
+      static_for<G>([&](auto hc) {
+        constexpr int h = decltype(hc)::value;
+        static_for<KU>([&](auto jc) {
+          constexpr int j = decltype(jc)::value;
+          static_for<QB>([&](auto cc) { constexpr int c = decltype(cc)::value; t[h][j][c] = lds_rd128<h * D * 2 + j * 8 * EUK * 2 + c * 16>(q_rd); });
+        });
+      });
+      lds_wait();
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int j = 0; j < KU; ++j)
+#pragma unroll
+          for (int c = 0; c < QB; ++c) {
+            tie(t[h][j][c]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q.qp[h][j][c * 4 + e] = elem(t[h][j][c], e);
+          }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int j = 0; j < KU; ++j) {
+        float sacc = 0.f;
+        if constexpr (GE::IS_Q) {
+#pragma unroll
+          for (int c = 0; c < QW; ++c) sacc += H ? f16_lo(q.qp[h][j][c]) + f16_hi(q.qp[h][j][c]) : bf_lo(q.qp[h][j][c]) + bf_hi(q.qp[h][j][c]);
+        }
+        q.qs[h][j] = sacc;
+      }
+  }
 
   int par = 1;                                           // LDS half that holds the next tile's slot list
   auto tile_body = [&](int tile, auto more_c) {
     constexpr bool MORE = decltype(more_c)::value;
     constexpr int X = MORE ? 1 : 0;                      // operations of the parts a last tile does not issue
     const bool valid = tile * 64 + lane < n_list;
+    // The two waves of a SIMD are issued oldest first, which lets the first wave of a pair run a whole tile ahead and
+    // leaves the second one to finish on its own; the wave with more phases still to do goes first instead.
+    __builtin_amdgcn_s_setprio(MORE ? 3 : 1);
     // -- V-side slots of this tile; K-side slots of the next one; fetch the list after that
     read_locs_v(par ^ 1);
     if constexpr (MORE) {
@@ -662,6 +728,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
       }
     }
     // -- V scales of this tile
+    __builtin_amdgcn_s_setprio(MORE ? 2 : 0);
     float vsc[LPRV];
     if constexpr (GE::IS_Q) {
       wait_vm<N_K + X * (1 + SCD) + N_V>();
@@ -763,6 +830,11 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
   __shared__ __attribute__((aligned(16))) char sm_lt[NW * 512];
   __shared__ __attribute__((aligned(16))) float sm_p[NW * 64 * GP];
   __shared__ float sm_ml[NW * 16];
+  // A wave's row groups (64 / LPRV of them) each hold a partial sum of every output element.  As many of them as the
+  // tile buffer has room for are parked side by side and added up by the merge below; only if there are more (64-byte
+  // rows) are the upper ones first folded into the lower ones by shuffles.
+  constexpr int NG = 64 / LPRV, FIT = TILE_BYTES / (G * D * 4);
+  constexpr int NGK = NG <= FIT ? NG : (FIT >= 4 ? 4 : FIT >= 2 ? 2 : 1);
   const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
   int nF, nQ, xsb = 0;
@@ -782,7 +854,8 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
   w.t = sm_t + wave * TILE_BYTES;
   w.sk = sm_sc + wave * 1024; w.sv = w.sk + 512; w.lt = sm_lt + wave * 512;
   w.ta = lds_addr(w.t); w.ska = lds_addr(w.sk); w.sva = lds_addr(w.sv); w.lta = lds_addr(w.lt);
-  w.pa = lds_addr(sm_p + wave * 64 * GP);
+  w.p = (char*)(sm_p + wave * 64 * GP);
+  w.pa = lds_addr(w.p);
   float* my_o = (float*)w.t;          // after the wave's last tile: its output partial, [G][D]
 
   float o[G][EV], m_run[G], l_lane[G];
@@ -821,22 +894,25 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
 #pragma unroll
           for (int e = 0; e < 8; ++e) my_o[h * D + lane * 8 + e] = o8[h][e];
       }
+      // the merge adds NGK parked row groups per wave: this wave has one, the others are zero
+      for (int i = lane; i < (NGK - 1) * G * D; i += 64) my_o[G * D + i] = 0.f;
       o_written = true;
     }
   }
   // ---- wave partial: sum the row groups and the per-lane denominators, then merge the waves through LDS
   if (!o_written) {
 #pragma unroll
-    for (int st = LPRV; st < 64; st <<= 1)
+    for (int st = LPRV * NGK; st < 64; st <<= 1)
 #pragma unroll
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < EV; ++e) o[h][e] += __shfl_xor(o[h][e], st);
-    if (lane < LPRV) {
+    if (lane < LPRV * NGK) {
+      float* dst = my_o + (lane / LPRV) * (G * D) + (lane % LPRV) * EV;
 #pragma unroll
       for (int h = 0; h < G; ++h)
 #pragma unroll
-        for (int e = 0; e < EV; ++e) my_o[h * D + lane * EV + e] = o[h][e];
+        for (int e = 0; e < EV; ++e) dst[h * D + e] = o[h][e];
     }
   }
 #pragma unroll
@@ -854,8 +930,13 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
     float acc = 0.f;
     if (mb > -INFINITY) {
 #pragma unroll
-      for (int ww = 0; ww < NW; ++ww)
-        acc = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 16 + h] - mb) * LOG2E), ((const float*)(sm_t + ww * TILE_BYTES))[i], acc);
+      for (int ww = 0; ww < NW; ++ww) {
+        const float* src = (const float*)(sm_t + ww * TILE_BYTES) + i;
+        float part = src[0];                                // the wave's row groups, in order
+#pragma unroll
+        for (int g = 1; g < NGK; ++g) part += src[g * (G * D)];
+        acc = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 16 + h] - mb) * LOG2E), part, acc);
+      }
     }
     po[i] = acc;
   }
