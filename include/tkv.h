@@ -70,7 +70,12 @@ typedef enum { TKV_T2_INT8_ROW = 0, TKV_T2_INT4_G32 = 1 } tkv_t2_format;
  *        HBM then holds T0, T2 and two frames; every decode step moves all of T1 over the host link (and the rows of
  *        the pinned store whose positions have left T1 since the store was last rewritten; tkv_migrate rewrites it
  *        packed, beside the frame pass it makes anyway, when those rows would cost more link time until the next
- *        plan than the rewrite). */
+ *        plan than the rewrite).
+ *        STREAM is the one mode that does NOT promise Prop. 1's bit identity: the T1 rows of a layer are served by a
+ *        second launch over the frame, with tiles and splits of its own, so the binary32 summation order depends on
+ *        which rows are in T1.  Row bits are still exact (the T1 rows attended are the rows appended), and outputs and
+ *        scores agree with the all-in-HBM placement to binary32 rounding (a few 1e-7 relative), far inside the
+ *        tolerances of the method; only bit equality is given up. */
 typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1, TKV_PREFETCH_STREAM = 2 } tkv_prefetch_mode;
 
 /* What a layer call adds to the cumulative score of a position:
