@@ -90,6 +90,14 @@ __device__ __forceinline__ uint32_t lds_rd32(uint32_t addr) {
   asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
   return v;
 }
+// Transposing read: within every 16 lanes, the 4 lanes 4j .. 4j+3 point at 4 x 8 bytes that together are 16
+// consecutive 16-bit elements of matrix row j (j < 4); lane i of the 16 receives element i of rows 0..3.
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_rd64_tr16(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
 template <int OFF>
 __device__ __forceinline__ void lds_wr128(uint32_t addr, u32x4 v) {
   asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
@@ -442,7 +450,7 @@ __device__ __forceinline__ void dma(const __amdgpu_buffer_rsrc_t& rs, char* lds,
 // Accumulates into o (offset-corrected for code rows), m_run, l_lane (per-lane partial sums of the softmax
 // denominator, relative to m_run); leaves the scaled logits in xs.
 template <int D, int G, Mode M, int KT>
-__device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, int b, int kvh, int lane,
+__device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, int b, int jq, int kvh, int lane,
                                           int tile0, int tstride, int n_list, const int* loc_list, int xs_tile0,
                                           float (&o)[G][Geo<D, M>::EV], float (&m_run)[G], float (&l_lane)[G]) {
   using GE = Geo<D, M>;
@@ -482,12 +490,12 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   constexpr int NQD = QBF ? (G * D * 2 + 1023) / 1024 : 0;
   static_assert(NQD * 1024 <= 64 * GP * 4, "the query block is parked in the probability region");
   if constexpr (QBF) {
-    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + kvh * G) * D * 2;
+    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + (size_t)jq * a.Hq + kvh * G) * D * 2;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc(qb, (uint32_t)(G * D * 2));   // lanes past the block fetch zeros
 #pragma unroll
     for (int i = 0; i < NQD; ++i) dma<16>(rq, w.p + i * 1024, (uint32_t)(i * 1024 + lane * 16), 0);
   } else {
-    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + kvh * G) * D * 4;
+    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + (size_t)jq * a.Hq + kvh * G) * D * 4;
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -682,7 +690,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
     // -- online softmax, one entry per lane; the denominator is summed per lane and reduced once at the end
     float corr[G];
     {
-      const size_t xbase = ((size_t)(b * a.Hq + kvh * G)) * a.xs_stride + (size_t)(xs_tile0 + tile) * 64 + lane;
+      const size_t xbase = ((size_t)((b * a.n_q + jq) * a.Hq + kvh * G)) * a.xs_stride + (size_t)(xs_tile0 + tile) * 64 + lane;
       float pv[GP];
 #pragma unroll
       for (int h = 0; h < GP; ++h) pv[h] = 0.f;
@@ -785,6 +793,291 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, const WaveLds& w, i
   }
 }
 
+// ---- one wave on the matrix cores: tiles of list F with 16-bit rows ------------------------------------------------
+// The G query heads of the kv head are padded to the 16 columns of a 16x16x32 matrix instruction.
+//   logits  : C[entry][head] = K[entry][:] . q[head][:], 16 entries per instruction, D/32 instructions deep.  Lane
+//             (head = lane % 16, kb = lane / 16) ends up with the logits of entries 16*rb + 4*kb + 0..3 of its head,
+//             which is exactly the layout of the left operand of the second product, so the probabilities never leave
+//             the registers.
+//   softmax : online per head; a lane's 16 entries of a tile, the maximum completed over the 4 lanes of the head.
+//   output  : O[head][d] += P[head][entry] * V[entry][d], 32 entries per instruction; the right operand needs, per
+//             lane, the same column of 4 + 4 rows: a transposing LDS read delivers it.  P is fed as two 16-bit terms
+//             (leading bits and remainder), so the product carries 16 significant bits of every weight.
+// Rows still come in by direct-to-LDS loads of 1 KB (8 rows x 8 pieces of 16 bytes, 128 contiguous bytes per row).
+// Within a row's 128 bytes the pieces are rotated by an amount that depends on the row, so that the 16 lanes of an
+// operand read (16 different rows, same piece) fall on 16 different bank groups; the rotation is undone by the read
+// addresses.  K rows of a tile, its V rows and the next tile's K rows pass through the one tile buffer as in attn_wave:
+// the K rows of 16 entries are replaced by V pieces once read, half a tile of V rows by the next tile's K pieces.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int KT>
+__device__ __forceinline__ f32x4 mfma_16x16x32(const u32x4& x, const u32x4& y, f32x4 c) {
+  if constexpr (KT == KT_BF16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x), __builtin_bit_cast(bf16x8, y), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, x), __builtin_bit_cast(f16x8, y), c, 0, 0, 0);
+}
+// value of lane (lane ^ MASK)
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float x, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, __builtin_bit_cast(int, x)));
+}
+// A binary32 weight as a sum of 16-bit terms, each the leading bits (by truncation) of what the terms before it left.
+// bfloat16: three terms of 8 significant bits are the weight exactly.  binary16: two terms of 11 bits (22 of the 24);
+// the weights are taken times 2^P_SHIFT there, so that small ones stay clear of binary16's narrow exponent range
+// (the factor is taken out of the accumulators at the end).
+template <int KT>
+struct PSplit {
+  static constexpr int N = KT == KT_BF16 ? 3 : 2;
+  static constexpr float P_SHIFT = KT == KT_BF16 ? 0.f : 14.f;
+};
+template <int KT>
+__device__ __forceinline__ void split_pair(float p0, float p1, uint32_t (&t)[PSplit<KT>::N]) {
+  if constexpr (KT == KT_BF16) {
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const uint32_t u0 = __builtin_bit_cast(uint32_t, p0) & 0xffff0000u, u1 = __builtin_bit_cast(uint32_t, p1) & 0xffff0000u;
+      t[i] = u1 | (u0 >> 16);
+      p0 -= __builtin_bit_cast(float, u0);
+      p1 -= __builtin_bit_cast(float, u1);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const f16x2 h = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(p0, p1));
+      t[i] = __builtin_bit_cast(uint32_t, h);
+      p0 -= (float)h.x;
+      p1 -= (float)h.y;
+    }
+  }
+}
+
+template <int D, int G, int KT>
+__device__ __forceinline__ void attn_wave_mfma(const AttnArgs& a, const WaveLds& w, int b, int jq, int kvh, int lane,
+                                               int tile0, int tstride, int n_list, const int* loc_list, int xs_tile0,
+                                               f32x4 (&o)[D / 16], float& m_run, float& l_run) {
+  static_assert(KT == KT_BF16 || KT == KT_F16, "16-bit rows");
+  static_assert(D % 64 == 0 && G <= 8, "head_dim in whole 128-byte row halves; the heads of a group in one operand");
+  constexpr int RB = 2 * D;                    // bytes per row
+  constexpr int KU = RB / 128;                 // 1 KB pieces per batch of 8 rows
+  constexpr int NP = 8 * KU;                   // pieces per tile, K or V
+  constexpr int NKS = D / 32, NDB = D / 16;    // instructions deep (logits), output column blocks
+  constexpr int PB = 1024;
+  const int g = lane >> 3, r = lane & 7;       // fetch side: row of a batch, piece of the row's 128 bytes
+  const int n = lane & 15, kb = lane >> 4;     // operand side
+
+  const size_t off = (size_t)(b * a.Hkv + kvh) * a.capF * RB;
+  const __amdgpu_buffer_rsrc_t rk = make_rsrc(a.fpK + off, (uint32_t)a.capF * RB), rvv = make_rsrc(a.fpV + off, (uint32_t)a.capF * RB);
+  const __amdgpu_buffer_rsrc_t rl = make_rsrc(loc_list, (uint32_t)a.Nmax * 4u);
+  if (tile0 * 64 >= n_list) return;
+
+  // the first tile's slot list before anything else (requests are served in the order they were made), then the
+  // query block into the probability region, which this path does not otherwise use
+  dma<4>(rl, w.lt, (uint32_t)(tile0 * 64 + lane) * 4u, 0);
+  constexpr int NQD = (G * D * 2 + 1023) / 1024;
+  {
+    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + (size_t)jq * a.Hq + kvh * G) * D * 2;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc(qb, (uint32_t)(G * D * 2));   // lanes past the block fetch zeros
+#pragma unroll
+    for (int i = 0; i < NQD; ++i) dma<16>(rq, w.p + i * 1024, (uint32_t)(i * 1024 + lane * 16), 0);
+  }
+
+  // fetch side.  Batch i holds entries 8*i + g; its K rows are rotated by 2*(g/2) + (i & 1) pieces, its V rows by g & 6.
+  const uint32_t kcol0 = (uint32_t)((r + 2 * (g >> 1)) & 7) * 16u, kcol1 = (uint32_t)((r + 2 * (g >> 1) + 1) & 7) * 16u;
+  const uint32_t vcol = (uint32_t)((r + (g & 6)) & 7) * 16u;
+  // operand side.  Logits: lane (n, kb) reads piece 4*ks + kb of entry 16*rb + n, which is row n & 7 of batch
+  // 2*rb + n/8; one address per parity of ks, the rest are immediates.
+  uint32_t k_rd[2];
+  {
+    const int ii = n >> 3, gg = n & 7, rot = 2 * (gg >> 1) + ii;
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+      k_rd[par] = w.ta + (uint32_t)(ii * KU * PB) + (uint32_t)(8 * gg + ((4 * par + kb - rot) & 7)) * 16u;
+  }
+  // Output: in the 16 lanes of block kb, lane 4*jj + q points at elements 4*q .. 4*q+3 of column block db of entry
+  // 16*rb + 4*kb + jj (row 4*(kb & 1) + jj of batch 2*rb + kb/2); one address per db & 3
+  uint32_t v_rd[4];
+  {
+    const int jj = (lane >> 2) & 3, qq = lane & 3, ii = kb >> 1, gg = 4 * (kb & 1) + jj;
+#pragma unroll
+    for (int dl = 0; dl < 4; ++dl)
+      v_rd[dl] = w.ta + (uint32_t)(ii * KU * PB) + (uint32_t)(8 * gg + ((2 * dl - (gg & 6)) & 7) + (qq >> 1)) * 16u + (uint32_t)(qq & 1) * 8u;
+  }
+
+  int lk[8];                                   // slots of entries 8*i + g of the tile whose K rows are fetched next
+  auto read_locs = [&](int par, int nvalid) {
+    const uint32_t base = w.lta + (uint32_t)par * 256u;
+    if (nvalid < 64) {                                   // wave-uniform: a list's last tile
+      if (lane >= nvalid) lds_wr32(base + (uint32_t)lane * 4u, 0xffffffffu);   // no row: fetches land as zeros
+    }
+    uint32_t t[8];
+    static_for<8>([&](auto ic) { constexpr int i = decltype(ic)::value; t[i] = lds_rd32<i * 32>(base + (uint32_t)g * 4u); });
+    lds_wait(); tie(t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lk[i] = (int)t[i];
+  };
+  auto issue_loc = [&](int par, int tile) { dma<4>(rl, w.lt + par * 256, (uint32_t)(tile * 64 + lane) * 4u, 0); };
+  auto issue_k_piece = [&](int s) {                      // K piece s = (batch s / KU, row half s % KU)
+    const int i = s / KU, j = s % KU;
+    dma<16>(rk, w.t + s * PB, (uint32_t)lk[i] * (uint32_t)RB + (uint32_t)j * 128u + ((i & 1) ? kcol1 : kcol0), 1);
+  };
+
+  wait_vm<NQD>();                                        // the list is in
+  read_locs(0, n_list - tile0 * 64);
+  issue_loc(1, tile0 + tstride);
+#pragma unroll
+  for (int s = 0; s < NP; ++s) issue_k_piece(s);
+  wait_vm<1 + NP>();                                     // the query block is in
+  // right operand of the logits: lane (n, kb) holds elements 32*ks + 8*kb .. +7 of head n (zeros for n >= G)
+  u32x4 qreg[NKS];
+  {
+    const uint32_t q_rd = w.pa + (uint32_t)((n < G ? n : 0) * D + 8 * kb) * 2u;
+    static_for<NKS>([&](auto kc) { constexpr int ks = decltype(kc)::value; qreg[ks] = lds_rd128<ks * 64>(q_rd); });
+    lds_wait(); tie(qreg);
+    if (n >= G) {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) qreg[ks] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  const size_t xrow = ((size_t)((b * a.n_q + jq) * a.Hq + kvh * G + (n < G ? n : 0))) * a.xs_stride + (size_t)(4 * kb);
+
+  int par = 1;                                           // LDS half that holds the next tile's slot list
+  auto tile_body = [&](int tile, auto more_c) {
+    constexpr bool MORE = decltype(more_c)::value;
+    constexpr int X = MORE ? 1 : 0;
+    __builtin_amdgcn_s_setprio(MORE ? 3 : 1);
+    int lv[8];                                           // this tile's V rows are fetched from the same slots
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lv[i] = lk[i];
+    auto issue_v_piece = [&](int v) {
+      const int i = v / KU, j = v % KU;
+      dma<16>(rvv, w.t + v * PB, (uint32_t)lv[i] * (uint32_t)RB + (uint32_t)j * 128u + vcol, 1);
+    };
+    if constexpr (MORE) {
+      wait_vm<NP>();                                     // younger than the next list: this tile's K pieces
+      read_locs(par, n_list - (tile + tstride) * 64);
+      issue_loc(par ^ 1, tile + 2 * tstride);
+    }
+    // -- logits, 16 entries at a time; the K rows that have been read are replaced by V pieces
+    f32x4 c[4];
+    u32x4 ka[2][NKS];
+    auto read_k = [&](auto rc, u32x4 (&dst)[NKS]) {
+      constexpr int rb = decltype(rc)::value;
+      // younger than these K pieces: the later K pieces, this period's list fetch, the V pieces so far
+      wait_vm<NP - 2 * KU + X>();
+      static_for<NKS>([&](auto kc) {
+        constexpr int ks = decltype(kc)::value;
+        dst[ks] = lds_rd128<(rb * 2 * KU + (ks >> 1)) * PB>(k_rd[ks & 1]);
+      });
+    };
+    read_k(std::integral_constant<int, 0>{}, ka[0]);
+    static_for<4>([&](auto rc) {
+      constexpr int rb = decltype(rc)::value;
+      lds_wait(); tie(ka[rb & 1]);
+#pragma unroll
+      for (int v = 2 * rb * KU; v < (2 * rb + 2) * KU; ++v) issue_v_piece(v);
+      if constexpr (rb + 1 < 4) read_k(std::integral_constant<int, (rb + 1 < 4 ? rb + 1 : 3)>{}, ka[(rb + 1) & 1]);
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) acc = mfma_16x16x32<KT>(ka[rb & 1][ks], qreg[ks], acc);
+      c[rb] = acc;
+    });
+    // -- online softmax: the lane has entries 16*rb + 4*kb + j of head n
+    float p[4][4];
+    {
+      float mx = -INFINITY;
+      const int e0 = tile * 64 + 4 * kb;
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        f32x4 x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          x[j] = (e0 + 16 * rb + j < n_list) ? c[rb][j] * a.softmax_scale : -INFINITY;
+          p[rb][j] = x[j];
+          mx = fmaxf(mx, x[j]);
+        }
+        if (n < G) *(f32x4*)(a.xs + xrow + (size_t)(xs_tile0 + tile) * 64 + 16 * rb) = x;
+      }
+      mx = fmaxf(mx, lane_xor<16>(mx, lane));
+      mx = fmaxf(mx, lane_xor<32>(mx, lane));
+      // m_run starts at -inf and every tile has a live entry: corr = exp2(-inf) = 0 against zero accumulators
+      const float mn = fmaxf(m_run, mx);
+      const float corr = __builtin_amdgcn_exp2f((m_run - mn) * LOG2E);
+      float ps = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { p[rb][j] = __builtin_amdgcn_exp2f(fmaf(p[rb][j] - mn, LOG2E, PSplit<KT>::P_SHIFT)); ps += p[rb][j]; }
+      l_run = fmaf(l_run, corr, ps);
+      m_run = mn;
+      // the output accumulators of this lane belong to heads 4*kb + j: their factors come from those heads' lanes;
+      // once the maxima have settled nothing needs rescaling (x * 1.0f is exact)
+      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
+        float cj[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          cj[j] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((4 * kb + j) << 2, __builtin_bit_cast(int, corr)));
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[db][j] *= cj[j];
+      }
+    }
+    // -- output: 32 entries per instruction; half a tile of V rows that has been read is replaced by K pieces
+    __builtin_amdgcn_s_setprio(MORE ? 2 : 0);
+    static_for<2>([&](auto tc) {
+      constexpr int t = decltype(tc)::value;
+      constexpr int NT = PSplit<KT>::N;
+      u32x4 pt[NT];
+      {
+        uint32_t s0[NT], s1[NT], s2[NT], s3[NT];
+        split_pair<KT>(p[2 * t][0], p[2 * t][1], s0);
+        split_pair<KT>(p[2 * t][2], p[2 * t][3], s1);
+        split_pair<KT>(p[2 * t + 1][0], p[2 * t + 1][1], s2);
+        split_pair<KT>(p[2 * t + 1][2], p[2 * t + 1][3], s3);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) pt[i] = u32x4{s0[i], s1[i], s2[i], s3[i]};
+      }
+      // younger than this half's V pieces: the other half's, then the K pieces issued after the first half
+      wait_vm<(NP / 2) * (1 - t) + X * t * (NP / 2)>();
+      u32x2 vv[2][NDB];
+      static_for<2>([&](auto r2c) {
+        constexpr int r2 = decltype(r2c)::value;
+        static_for<NDB>([&](auto dc) {
+          constexpr int db = decltype(dc)::value;
+          vv[r2][db] = lds_rd64_tr16<((2 * t + r2) * 2 * KU + (db >> 2)) * PB>(v_rd[db & 3]);
+        });
+      });
+      lds_wait(); tie(vv[0]); tie(vv[1]);
+      if constexpr (MORE) {
+#pragma unroll
+        for (int s = t * (NP / 2); s < (t + 1) * (NP / 2); ++s) issue_k_piece(s);
+      }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const u32x4 vb = u32x4{vv[0][db].x, vv[0][db].y, vv[1][db].x, vv[1][db].y};
+#pragma unroll
+        for (int i = NT - 1; i >= 0; --i) o[db] = mfma_16x16x32<KT>(pt[i], vb, o[db]);
+      }
+    });
+    par ^= 1;
+  };
+
+  int tile = tile0;
+  for (; (tile + tstride) * 64 < n_list; tile += tstride) tile_body(tile, std::true_type{});
+  tile_body(tile, std::false_type{});
+  if constexpr (PSplit<KT>::P_SHIFT != 0.f) {
+    const float back = __builtin_amdgcn_exp2f(-PSplit<KT>::P_SHIFT);
+    l_run *= back;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[db][j] *= back;
+  }
+}
+
 // Waves per SIMD the kernel is compiled for: two while a wave's registers (query slices and output accumulators grow
 // with the group size) fit half a SIMD's file, else one.
 constexpr int waves_per_simd(int G) { return G <= 5 ? 2 : 1; }
@@ -835,19 +1128,23 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
   // rows) are the upper ones first folded into the lower ones by shuffles.
   constexpr int NG = 64 / LPRV, FIT = TILE_BYTES / (G * D * 4);
   constexpr int NGK = NG <= FIT ? NG : (FIT >= 4 ? 4 : FIT >= 2 ? 2 : 1);
-  const int s = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int s = blockIdx.x, kvh = blockIdx.y;
+  // several query tokens per sequence: query jq of sequence b; it is n_q - 1 - jq positions older than the last one,
+  // and those positions (the tail of list F) are not its to see
+  const int b = a.n_q > 1 ? (int)blockIdx.z / a.n_q : (int)blockIdx.z, jq = a.n_q > 1 ? (int)blockIdx.z % a.n_q : 0;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
   int nF, nQ, xsb = 0;
   if (!a.second) {
     if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
     else { nF = a.cnt[b * CNT_N + C_NF] - a.trim; nQ = a.cnt[b * CNT_N + C_NQ]; }
+    nF -= a.n_q - 1 - jq;
   } else {
     nF = a.cnt[b * CNT_N + C_NS]; nQ = 0;
     xsb = ((a.cnt[b * CNT_N + C_NF] - a.trim + 63) >> 6) + ((a.cnt[b * CNT_N + C_NQ] + 63) >> 6);
   }
   const int nft = (nF + 63) >> 6, nqt = (nQ + 63) >> 6;
   const int nwv = a.S * NW;
-  const int nwq = a.second ? 0 : (a.B <= ATTN_ARG_SEQS) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
+  const int nwq = a.second ? 0 : (a.B <= ATTN_ARG_SEQS && a.n_q == 1) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
   const int u = s * NW + wave;
 
   WaveLds w;
@@ -865,13 +1162,35 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
 #pragma unroll
     for (int e = 0; e < EV; ++e) o[h][e] = 0.f;
   }
-  bool o_written = false;
+  bool o_written = false, mfma_wave = false;
   if (u < nwf) {
-    attn_wave<D, G, KG::MF, KT>(a, w, b, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
+    if constexpr (KT != KT_F32) {
+      // 16-bit rows go through the matrix cores; the wave's result arrives complete, in one slice
+      f32x4 om[D / 16];
+#pragma unroll
+      for (int db = 0; db < D / 16; ++db) om[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+      float mr = -INFINITY, lr = 0.f;
+      attn_wave_mfma<D, G, KT>(a, w, b, jq, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, om, mr, lr);
+      lr += lane_xor<16>(lr, lane);
+      lr += lane_xor<32>(lr, lane);
+      if (lane < G) { sm_ml[wave * 16 + lane] = mr; sm_ml[wave * 16 + 8 + lane] = lr; }
+#pragma unroll
+      for (int db = 0; db < D / 16; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int h = 4 * (lane >> 4) + j;
+          if (h < G) my_o[h * D + 16 * db + (lane & 15)] = om[db][j];
+        }
+      for (int i = lane; i < (NGK - 1) * G * D; i += 64) my_o[G * D + i] = 0.f;
+      mfma_wave = true;
+      o_written = true;
+    } else {
+      attn_wave<D, G, KG::MF, KT>(a, w, b, jq, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
+    }
   } else {
     if constexpr (EV == 8) {
-      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
-      else attn_wave<D, G, Q_INT4, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, jq, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, KT>(a, w, b, jq, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
     } else {
       // binary32 rows use 4 elements per lane, code rows 8: separate accumulators, parked directly
       float o8[G][8];
@@ -879,8 +1198,8 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o8[h][e] = 0.f;
-      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
-      else attn_wave<D, G, Q_INT4, KT>(a, w, b, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
+      if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, jq, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
+      else attn_wave<D, G, Q_INT4, KT>(a, w, b, jq, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o8, m_run, l_lane);
       constexpr int L8 = D / 8;
 #pragma unroll
       for (int st = L8; st < 64; st <<= 1)
@@ -915,13 +1234,16 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
         for (int e = 0; e < EV; ++e) dst[h * D + e] = o[h][e];
     }
   }
+  if (!mfma_wave) {
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    const float ls = wave_sum(l_lane[h]);
-    if (lane == 0) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = ls; }
+    for (int h = 0; h < G; ++h) {
+      const float ls = wave_sum(l_lane[h]);
+      if (lane == 0) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = ls; }
+    }
   }
   __syncthreads();
-  float* po = a.part_o + ((size_t)((b * a.Hkv + kvh) * a.S_total + a.s0 + s) * G) * D;
+  const int bq = b * a.n_q + jq;
+  float* po = a.part_o + ((size_t)((bq * a.Hkv + kvh) * a.S_total + a.s0 + s) * G) * D;
   for (int i = t; i < G * D; i += NW * 64) {
     const int h = i / D;
     float mb = sm_ml[h];
@@ -949,7 +1271,7 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) ll = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 16 + t] - mb) * LOG2E), sm_ml[ww * 16 + 8 + t], ll);
     }
-    float* pm = a.part_ml + ((size_t)((b * a.Hkv + kvh) * a.S_total + a.s0 + s) * 2) * G;
+    float* pm = a.part_ml + ((size_t)((bq * a.Hkv + kvh) * a.S_total + a.s0 + s) * 2) * G;
     pm[t] = mb;
     pm[G + t] = ll;
   }
@@ -1068,6 +1390,97 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   }
 }
 
+// ---- finish for several query tokens per sequence (one launch served n_q of them) ----------------------------
+// Grid (64-entry slots of the longest query's lists + Hq * n_q, B).  Slot workgroups: every list entry gets the
+// weights of the n_q queries added in query order (what n_q single-token calls would have done, with the same
+// arithmetic per query: thread (e, hg) sums kv heads hg, hg+4, ..., the four partial sums are added in the order
+// hg = 0..3).  Query jq does not see the last n_q - 1 - jq entries of list F, and its Q-list logits start at its own
+// number of F tiles.  The other workgroups merge the splits of one (query, head) into out.
+template <int D, int G>
+__global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int n_tiles) {
+  constexpr int MAXQ = 8;
+  __shared__ float M[MAXQ][128], IL[MAXQ][128];
+  __shared__ float sm_part[256];
+  const int t = threadIdx.x, b = blockIdx.y, nq = a.n_q, ns = a.S_total;
+  int nF, nQ;
+  if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+  else { nF = a.cnt[b * CNT_N + C_NF] - a.trim; nQ = a.cnt[b * CNT_N + C_NQ]; }
+  const int cf = (nF + TB - 1) / TB;                       // F tiles of the last query (the longest list)
+  const bool is_tile = (int)blockIdx.x < n_tiles;
+  if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
+  // global (m, 1/l) of every (query, head) of this sequence
+  for (int i = t; i < nq * a.Hq; i += 256) {
+    const int jq = i / a.Hq, hq = i % a.Hq, kvh = hq / G, g = hq % G;
+    const float* src = a.part_ml + (size_t)((b * nq + jq) * a.Hkv + kvh) * ns * 2 * G;
+    float mm = -INFINITY;
+    for (int k = 0; k < ns; ++k) mm = fmaxf(mm, src[k * 2 * G + g]);
+    float ll = 0.f;
+    for (int k = 0; k < ns; ++k) ll = fmaf(src[k * 2 * G + G + g], __builtin_amdgcn_exp2f((src[k * 2 * G + g] - mm) * LOG2E), ll);
+    M[jq][hq] = mm > -INFINITY ? mm : 0.f;
+    IL[jq][hq] = ll > 0.f ? 1.0f / ll : 0.f;
+  }
+  __syncthreads();
+  if (is_tile) {
+    const int e = t & 63, hg = t >> 6;
+    const int sl = blockIdx.x * 64 + e;                     // slot in the longest query's layout
+    const bool is_f = sl < nF, is_q = sl >= cf * TB && sl - cf * TB < nQ;
+    int pos = -1;
+    if (is_f) pos = a.f_pos[(size_t)b * a.Nmax + sl];
+    else if (is_q) pos = a.q_pos[(size_t)b * a.Nmax + (sl - cf * TB)];
+    float score = (hg == 0 && pos >= 0) ? a.score[(size_t)b * a.Nmax + pos] : 0.f;
+    for (int jq = 0; jq < nq; ++jq) {
+      const int nFj = nF - (nq - 1 - jq), cfj = (nFj + TB - 1) / TB;
+      const bool seen = is_q || (is_f && sl < nFj);         // wave-divergent at most in a list's last tile
+      const int col = is_q ? cfj * TB + (sl - cf * TB) : sl;
+      float acc = 0.f;
+      if (seen) {
+        for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
+          float x[G];
+#pragma unroll
+          for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)(b * nq + jq) * a.Hq + kvh * G + g) * a.xs_stride + col];
+          if (a.vnorm) {
+            float w = 0.f;
+#pragma unroll
+            for (int g = 0; g < G; ++g) w += __builtin_amdgcn_exp2f((x[g] - M[jq][kvh * G + g]) * LOG2E) * IL[jq][kvh * G + g];
+            acc = fmaf(w, a.vnorm[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
+          } else {
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[jq][kvh * G + g]) * LOG2E) * IL[jq][kvh * G + g];
+          }
+        }
+      }
+      __syncthreads();
+      sm_part[hg * 64 + e] = acc;
+      __syncthreads();
+      if (hg == 0 && seen) score = score + a.score_scale * (((sm_part[e] + sm_part[64 + e]) + sm_part[128 + e]) + sm_part[192 + e]);
+    }
+    if (hg == 0 && pos >= 0) a.score[(size_t)b * a.Nmax + pos] = score;
+  } else {
+    constexpr int NSG = 256 / D;
+    const int idx = blockIdx.x - n_tiles, jq = idx / a.Hq, hq = idx % a.Hq, kvh = hq / G, h = hq % G;
+    const int d = t % D, sg = t / D;
+    const float* pm = a.part_ml + (size_t)((b * nq + jq) * a.Hkv + kvh) * ns * 2 * G;
+    const float* pob = a.part_o + ((size_t)((b * nq + jq) * a.Hkv + kvh) * ns * G) * D + h * D + d;
+    const float mg = M[jq][hq];
+    float acc = 0.f;
+#pragma unroll 4
+    for (int k = sg; k < ns; k += NSG)
+      acc = fmaf(__builtin_amdgcn_exp2f((pm[k * 2 * G + h] - mg) * LOG2E), pob[(size_t)k * G * D], acc);
+    sm_part[sg * D + d] = acc;
+    __syncthreads();
+    if (sg == 0) {
+      float tot = sm_part[d];
+#pragma unroll
+      for (int g2 = 1; g2 < NSG; ++g2) tot += sm_part[g2 * D + d];
+      tot *= IL[jq][hq];
+      const size_t oi = ((size_t)b * a.o_bs + (size_t)jq * a.Hq + hq) * D + d;
+      if (a.out_kind == KT_BF16) ((uint16_t*)a.out)[oi] = f32_to_bf16(tot);
+      else if (a.out_kind == KT_F16) ((_Float16*)a.out)[oi] = (_Float16)tot;
+      else ((float*)a.out)[oi] = tot;
+    }
+  }
+}
+
 // ---- dispatch ----------------------------------------------------------------------------------------------
 // The file is compiled once per part (TKV_ATTN_PART = 0..3, 5, 6: one (head_dim, KV dtype) pair of attn_tiered each,
 // 4: attn_finish and the launchers), so the parts build in parallel; without the macro it is one translation unit.
@@ -1093,7 +1506,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 // With a pair of events the launch is timed by the dispatch's own begin / end timestamps (no bracket overhead).
 template <int D, int G, int KT>
 static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  dim3 grid(a.S, a.Hkv, a.B);
+  dim3 grid(a.S, a.Hkv, a.B * a.n_q);
   constexpr int threads = KernelGeo<D, G, KT>::NW * 64;
   if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
   else hipLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, a);
@@ -1152,6 +1565,18 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream
 }
 int attn_waves_per_group(int D, int elem_bytes, int G) { return waves_per_group(D * elem_bytes, G); }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
+
+template <int D, int G, int KT>
+static hipError_t run_finish_chunk(const AttnArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((k_attn_finish_chunk<D, G>), dim3(a.n_tiles + a.Hq * a.n_q, a.B), dim3(256), 0, st, a, a.n_tiles);
+  return hipGetLastError();
+}
+hipError_t launch_attn_finish_chunk(const AttnArgs& a, int D, int G, hipStream_t st) {
+  if (a.n_q < 1 || a.n_q > 8 || a.Hq > 128) return hipErrorInvalidValue;
+  if (D == 128) { TKV_DISPATCH_G(run_finish_chunk, 128, KT_BF16, a, st) }
+  if (D == 64) { TKV_DISPATCH_G(run_finish_chunk, 64, KT_BF16, a, st) }
+  return hipErrorInvalidValue;
+}
 
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (D == 128) { TKV_DISPATCH_G(run_finish, 128, KT_BF16, a, st, ev0, ev1) }

@@ -71,6 +71,7 @@ struct tkv_cache {
   bool plan_pending = false;
   // attention scratch
   float* xs = nullptr; float* part_ml = nullptr; float* part_o = nullptr;
+  float* xs_chunk = nullptr; float* ml_chunk = nullptr; float* po_chunk = nullptr;   // the same for chunk launches
   int S_alloc = 0, xs_stride = 0;
   char* static_scratch = nullptr;  // this device's copy of the library's fixed scratch array (tkv_attend_and_score_noalloc)
   // T1 store and transport
@@ -601,14 +602,37 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
   return TKV_OK;
 }
 
-// One query token per sequence against one layer.  trim: entries at the end of list F to leave out (later tokens of a
-// chunk); q_bs / o_bs: query heads between consecutive sequences in q / out; last: the layer's last call of this step
-// (the streamed frame is released and refilled, queued transfers are pumped).
+// Most query tokens of a chunk that one launch serves; longer chunks go in groups of this many.
+constexpr int CHUNK_MAX_Q = 8;
+
+// Scratch for launches that serve several query tokens per sequence: logits and split partials per (sequence, query).
+// Allocated on the first such call, for CHUNK_MAX_Q queries, and kept until the cache is destroyed.
+static tkv_status chunk_scratch(tkv_cache* c) {
+  if (c->xs_chunk) return TKV_OK;
+  const DevView& v = c->dv;
+  const size_t nb = (size_t)v.B * CHUNK_MAX_Q;
+  float *x = nullptr, *ml = nullptr, *po = nullptr;
+  if (!dalloc(c, x, nb * v.Hq * c->xs_stride) || !dalloc(c, ml, nb * v.Hkv * c->S_alloc * 2 * c->G) ||
+      !dalloc(c, po, nb * v.Hkv * c->S_alloc * c->G * v.D))
+    return fail(c, TKV_ENOMEM, "tkv_attend_and_score_chunk: no device memory for the scratch of %d query tokens per launch", CHUNK_MAX_Q);
+  c->xs_chunk = x; c->ml_chunk = ml; c->po_chunk = po;
+  return TKV_OK;
+}
+
+// m query tokens per sequence (m = 1: a decode step's one) against one layer.  trim: entries at the end of list F that
+// the last of the m queries leaves out (later tokens of a chunk); query j of the m leaves m - 1 - j more out.  q_bs /
+// o_bs: query heads between consecutive sequences in q / out, the m queries of a sequence being Hq heads apart; last:
+// the layer's last call of this step (the streamed frame is released and refilled, queued transfers are pumped).
 // noalloc: the scratch of the call lives in the library's fixed device array, and nothing on the way may allocate
 // (no event pools, no queued transfers are issued).
 static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* out, int trim, int q_bs, int o_bs, bool last,
-                             hipStream_t st, bool noalloc = false) {
+                             hipStream_t st, bool noalloc = false, int m = 1) {
   const DevView& v = c->dv;
+  if (m > 1) {
+    if (c->streamed || noalloc || m > CHUNK_MAX_Q) return fail(c, TKV_EINVAL, "attend_one: %d queries per launch not possible here", m);
+    tkv_status cs = chunk_scratch(c);
+    if (cs != TKV_OK) return cs;
+  }
   bool use_old = false;
   const int fr = layer & 1;
   if (c->streamed) {
@@ -658,6 +682,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.f_loc = use_old ? v.f_loc_old : v.f_loc; a.f_pos = v.f_pos; a.q_loc = v.q_loc; a.q_pos = v.q_pos;
   a.vnorm = v.vnorm ? v.vnorm + lrows * v.Nmax : nullptr;
   a.cnt = v.cnt; a.score = v.score; a.xs = c->xs; a.part_ml = c->part_ml; a.part_o = c->part_o;
+  if (m > 1) { a.xs = c->xs_chunk; a.part_ml = c->ml_chunk; a.part_o = c->po_chunk; }
   if (noalloc) {
     // the same three arrays, carved out of the fixed scratch array (256-byte aligned each)
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -678,7 +703,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capP; a.cap2 = v.cap2;
   a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_kind = c->cfg.out_dtype;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
-  a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim;
+  a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim; a.n_q = m;
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
   EvPair* pf = nullptr;
@@ -702,7 +727,8 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
     a2.S = S2; a2.s0 = S; a2.second = 1;
     HIPCHK(c, launch_attn_tiered(a2, v.D, c->G, c->kt, st, pe2 ? pe2->a : nullptr, pe2 ? pe2->b : nullptr));
   }
-  HIPCHK(c, launch_attn_finish(a, v.D, c->G, st, pf ? pf->a : nullptr, pf ? pf->b : nullptr));
+  if (m > 1) HIPCHK(c, launch_attn_finish_chunk(a, v.D, c->G, st));
+  else HIPCHK(c, launch_attn_finish(a, v.D, c->G, st, pf ? pf->a : nullptr, pf ? pf->b : nullptr));
   if (!last || noalloc) return TKV_OK;
   if (c->streamed && S2 > 0) {
     HIPCHK(c, hipEventRecord(c->ev_free[fr], st));
@@ -746,9 +772,14 @@ tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q
     return fail(c, TKV_ESTATE, "tkv_attend_and_score_chunk: %d query tokens, but only %d positions were appended since the last tkv_migrate", n_q, c->n_assigned - c->n_at_plan);
   const DevView& v = c->dv;
   const size_t q_tok = (size_t)v.Hq * v.D * c->es, o_tok = (size_t)v.Hq * v.D * (c->cfg.out_dtype == TKV_F32 ? 4 : 2);
-  for (int j = 0; j < n_q; ++j) {
-    tkv_status s = attend_one(c, layer, (const char*)q + j * q_tok, (char*)out + j * o_tok, n_q - 1 - j, n_q * v.Hq, n_q * v.Hq,
-                              j == n_q - 1, (hipStream_t)hip_stream);
+  // The cache is read once for up to CHUNK_MAX_Q of the chunk's tokens: one launch whose workgroups of consecutive
+  // tokens run side by side on the same rows.  The streamed mode, whose frame serves one launch pair at a time, takes
+  // the tokens one by one.
+  const int per = c->streamed ? 1 : CHUNK_MAX_Q;
+  for (int j = 0; j < n_q; j += per) {
+    const int m = std::min(per, n_q - j);
+    tkv_status s = attend_one(c, layer, (const char*)q + j * q_tok, (char*)out + j * o_tok, n_q - j - m, n_q * v.Hq, n_q * v.Hq,
+                              j + m == n_q, (hipStream_t)hip_stream, false, m);
     if (s != TKV_OK) return s;
   }
   return TKV_OK;

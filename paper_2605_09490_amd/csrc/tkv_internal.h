@@ -97,9 +97,12 @@ struct AttnArgs {
   const int* s_pos; // [B][Nmax] positions of the T1 list (streamed T1), for the finishing kernel
   const float* vnorm; // [B][Hkv][Nmax] this layer's value-row norms (value-aware scorer), else NULL
   int n_tiles;      // max over the sequences of F tiles + Q tiles (+ T1 tiles)
-  int q_bs, o_bs;   // query heads between consecutive sequences in q and in out: Hq, or n_q * Hq for one token of a chunk
+  int q_bs, o_bs;   // query heads between consecutive sequences in q and in out: Hq, or n_q * Hq for the tokens of a chunk
   int trim;         // entries at the end of list F this call leaves out (the chunk's later tokens); nF[] has them
                     // taken off already, the device counter has not
+  int n_q;          // query tokens per sequence served by this launch (>= 1): grid z = B * n_q, query jq of a sequence
+                    // is Hq heads further on in q and out, leaves n_q - 1 - jq more entries of list F out (it is that
+                    // many positions older), and has logits and split partials of its own (index b * n_q + jq)
   int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_kind, q_es;   // out_kind: 0 binary32, 1 bfloat16, 2 binary16
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
@@ -112,6 +115,7 @@ struct AttnArgs {
 // kt: type of K, V and q (0 binary32, 1 bfloat16, 2 binary16)
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_attn_finish_chunk(const AttnArgs& a, int D, int G, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, int workgroups, uint32_t* sink, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 int attn_waves_per_group(int D, int elem_bytes, int G);   // waves per attention workgroup (one workgroup per compute unit)
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles);   // how many of a pair's waves serve the Q list
