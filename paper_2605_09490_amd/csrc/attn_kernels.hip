@@ -854,37 +854,97 @@ __device__ __forceinline__ void split_pair(float p0, float p1, uint32_t (&t)[PSp
   }
 }
 
-template <int D, int G, int KT>
-__device__ __forceinline__ void attn_wave_mfma(const AttnArgs& a, const WaveLds& w, int b, int jq, int kvh, int lane,
+// 16 code values (one byte each, or two per byte) as 16-bit floating point: the matrix cores multiply them exactly
+// (a code + 128, or + 8, has at most 8 significant bits).  Two values per 32-bit word, low element first.
+template <int KT>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi) {
+  if constexpr (KT == KT_BF16) return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi), __builtin_bit_cast(uint32_t, lo), 0x07060302u);
+  else return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+__device__ __forceinline__ float ubyte_f(uint32_t w, int n) {    // byte n of w as a float (one conversion instruction)
+  return (float)((w >> (8 * n)) & 0xFFu);
+}
+// one word of int8 codes (4, as code + 128) -> two words; one word of int4 codes (8, as code + 8) -> four words
+template <int KT>
+__device__ __forceinline__ void widen_int8(uint32_t w, uint32_t& o0, uint32_t& o1) {
+  w ^= 0x80808080u;
+  o0 = pack16<KT>(ubyte_f(w, 0), ubyte_f(w, 1));
+  o1 = pack16<KT>(ubyte_f(w, 2), ubyte_f(w, 3));
+}
+template <int KT>
+__device__ __forceinline__ u32x4 widen_int4(uint32_t w) {
+  w ^= 0x88888888u;
+  const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;    // elements 0, 2, 4, 6 and 1, 3, 5, 7
+  return u32x4{pack16<KT>(ubyte_f(lo, 0), ubyte_f(hi, 0)), pack16<KT>(ubyte_f(lo, 1), ubyte_f(hi, 1)),
+               pack16<KT>(ubyte_f(lo, 2), ubyte_f(hi, 2)), pack16<KT>(ubyte_f(lo, 3), ubyte_f(hi, 3))};
+}
+
+// M: F_BF16 / F_F16 (list F; the element type is KT's) or Q_INT8 / Q_INT4 (list Q).  NCB: blocks of 16 columns; a
+// column is one (query token, head of the group) pair, query-major, a.cq query tokens in all (a decode step: one).
+// Code rows (list Q) are fetched as they are stored (16-byte pieces, consecutive lanes along a row), and half a tile at
+// a time is widened to 16-bit values of code + OFF into the free upper half of the wave's tile buffer, in the layout the
+// full-precision rows arrive in, where the same operand reads pick it up.  Scales stay outside the products: a K row's
+// scale multiplies its logits (per 32-element group: one product per group), a V row's scale its weights; the offset
+// comes out through the sums of the query elements and of the scaled weights.
+template <int D, int G, int KT, Mode M, int NCB>
+__device__ __forceinline__ void attn_wave_mfma(const AttnArgs& a, const WaveLds& w, int b, int jz, int kvh, int lane,
                                                int tile0, int tstride, int n_list, const int* loc_list, int xs_tile0,
-                                               f32x4 (&o)[D / 16], float& m_run, float& l_run) {
-  static_assert(KT == KT_BF16 || KT == KT_F16, "16-bit rows");
-  static_assert(D % 64 == 0 && G <= 8, "head_dim in whole 128-byte row halves; the heads of a group in one operand");
-  constexpr int RB = 2 * D;                    // bytes per row
-  constexpr int KU = RB / 128;                 // 1 KB pieces per batch of 8 rows
-  constexpr int NP = 8 * KU;                   // pieces per tile, K or V
+                                               f32x4 (&o)[NCB][D / 16], float (&m_run)[NCB], float (&l_run)[NCB]) {
+  static_assert(KT == KT_BF16 || KT == KT_F16, "16-bit operands");
+  static_assert(D % 64 == 0, "head_dim in whole 128-byte row halves");
+  constexpr bool IS_Q = (M == Q_INT8 || M == Q_INT4);
+  constexpr int RB = 2 * D;                    // bytes per row as the matrix cores read it
+  constexpr int KU = RB / 128;                 // 1 KB pieces per batch of 8 rows (operand layout)
   constexpr int NKS = D / 32, NDB = D / 16;    // instructions deep (logits), output column blocks
   constexpr int PB = 1024;
-  const int g = lane >> 3, r = lane & 7;       // fetch side: row of a batch, piece of the row's 128 bytes
+  constexpr int CRB = !IS_Q ? RB : (M == Q_INT8 ? D : D / 2);   // bytes per row as fetched
+  constexpr int NP = IS_Q ? CRB / 16 : 8 * KU;                  // 1 KB pieces per tile, K or V
+  constexpr int NPH = NP / 2;
+  constexpr int LPR = CRB / 16, RPP = 64 / LPR;                 // list Q: lanes per row, rows per piece
+  constexpr int SCD = (M == Q_INT8) ? 1 : (M == Q_INT4) ? D / 64 : 0;   // dwords of scales per row
+  constexpr int NGD = (M == Q_INT4) ? D / 32 : 1;               // scale groups along a row
+  constexpr float OFF = (M == Q_INT4) ? 8.f : 128.f;
+  constexpr uint32_t SCR = IS_Q ? 32 * RB : 0;                  // where the widened half tile sits
+  static_assert(NP >= 2 && (!IS_Q || 64 * CRB <= 32 * RB), "two halves; code rows leave the upper half of the buffer free");
+  const int g = lane >> 3, r = lane & 7;       // F fetch side: row of a batch, piece of the row's 128 bytes
   const int n = lane & 15, kb = lane >> 4;     // operand side
 
-  const size_t off = (size_t)(b * a.Hkv + kvh) * a.capF * RB;
-  const __amdgpu_buffer_rsrc_t rk = make_rsrc(a.fpK + off, (uint32_t)a.capF * RB), rvv = make_rsrc(a.fpV + off, (uint32_t)a.capF * RB);
+  __amdgpu_buffer_rsrc_t rk, rvv, rsk, rsv;
+  if constexpr (!IS_Q) {
+    const size_t off = (size_t)(b * a.Hkv + kvh) * a.capF * RB;
+    rk = make_rsrc(a.fpK + off, (uint32_t)a.capF * RB); rvv = make_rsrc(a.fpV + off, (uint32_t)a.capF * RB);
+    rsk = rk; rsv = rvv;
+  } else {
+    const size_t rows = (size_t)(b * a.Hkv + kvh) * a.cap2;
+    rk = make_rsrc(a.c2K + rows * a.cb, (uint32_t)a.cap2 * a.cb); rvv = make_rsrc(a.c2V + rows * a.cb, (uint32_t)a.cap2 * a.cb);
+    rsk = make_rsrc(a.s2K + rows * a.sb, (uint32_t)a.cap2 * a.sb); rsv = make_rsrc(a.s2V + rows * a.sb, (uint32_t)a.cap2 * a.sb);
+  }
   const __amdgpu_buffer_rsrc_t rl = make_rsrc(loc_list, (uint32_t)a.Nmax * 4u);
   if (tile0 * 64 >= n_list) return;
 
-  // the first tile's slot list before anything else (requests are served in the order they were made), then the
-  // query block into the probability region, which this path does not otherwise use
+  // the first tile's slot list before anything else (requests are served in the order they were made)
   dma<4>(rl, w.lt, (uint32_t)(tile0 * 64 + lane) * 4u, 0);
-  constexpr int NQD = (G * D * 2 + 1023) / 1024;
-  {
-    const char* qb = (const char*)a.q + ((size_t)b * a.q_bs + (size_t)jq * a.Hq + kvh * G) * D * 2;
-    const __amdgpu_buffer_rsrc_t rq = make_rsrc(qb, (uint32_t)(G * D * 2));   // lanes past the block fetch zeros
+
+  // columns of this lane: (query token, head); right operand of the logits: elements 32*ks + 8*kb .. +7 of the
+  // column's query vector (zeros for a column past the last)
+  const int ncol = a.cq * G;
+  bool live[NCB];
+  int n_seen[NCB];                             // list entries the column's query may see (the chunk's later tokens are cut off list F)
+  size_t xrow[NCB];
+  u32x4 qreg[NCB][NKS];
 #pragma unroll
-    for (int i = 0; i < NQD; ++i) dma<16>(rq, w.p + i * 1024, (uint32_t)(i * 1024 + lane * 16), 0);
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int col = 16 * cb + n, jq = col / G, h = col % G;
+    live[cb] = col < ncol;
+    n_seen[cb] = IS_Q ? n_list : n_list - (live[cb] ? a.cq - 1 - jq : 0);
+    const int qi = live[cb] ? jq * a.Hq + kvh * G + h : kvh * G;
+    xrow[cb] = ((size_t)((b * a.n_q + jz) * a.cq * a.Hq + qi)) * a.xs_stride + (size_t)(4 * kb);
+    const u32x4* qp = (const u32x4*)((const char*)a.q + (((size_t)b * a.q_bs + (size_t)jz * a.cq * a.Hq + qi) * D + 8 * kb) * 2);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qreg[cb][ks] = live[cb] ? qp[ks * 4] : u32x4{0u, 0u, 0u, 0u};
   }
 
-  // fetch side.  Batch i holds entries 8*i + g; its K rows are rotated by 2*(g/2) + (i & 1) pieces, its V rows by g & 6.
+  // F fetch side.  Batch i holds entries 8*i + g; its K rows are rotated by 2*(g/2) + (i & 1) pieces, its V rows by g & 6.
   const uint32_t kcol0 = (uint32_t)((r + 2 * (g >> 1)) & 7) * 16u, kcol1 = (uint32_t)((r + 2 * (g >> 1) + 1) & 7) * 16u;
   const uint32_t vcol = (uint32_t)((r + (g & 6)) & 7) * 16u;
   // operand side.  Logits: lane (n, kb) reads piece 4*ks + kb of entry 16*rb + n, which is row n & 7 of batch
@@ -894,7 +954,7 @@ __device__ __forceinline__ void attn_wave_mfma(const AttnArgs& a, const WaveLds&
     const int ii = n >> 3, gg = n & 7, rot = 2 * (gg >> 1) + ii;
 #pragma unroll
     for (int par = 0; par < 2; ++par)
-      k_rd[par] = w.ta + (uint32_t)(ii * KU * PB) + (uint32_t)(8 * gg + ((4 * par + kb - rot) & 7)) * 16u;
+      k_rd[par] = w.ta + SCR + (uint32_t)(ii * KU * PB) + (uint32_t)(8 * gg + ((4 * par + kb - rot) & 7)) * 16u;
   }
   // Output: in the 16 lanes of block kb, lane 4*jj + q points at elements 4*q .. 4*q+3 of column block db of entry
   // 16*rb + 4*kb + jj (row 4*(kb & 1) + jj of batch 2*rb + kb/2); one address per db & 3
@@ -903,163 +963,339 @@ __device__ __forceinline__ void attn_wave_mfma(const AttnArgs& a, const WaveLds&
     const int jj = (lane >> 2) & 3, qq = lane & 3, ii = kb >> 1, gg = 4 * (kb & 1) + jj;
 #pragma unroll
     for (int dl = 0; dl < 4; ++dl)
-      v_rd[dl] = w.ta + (uint32_t)(ii * KU * PB) + (uint32_t)(8 * gg + ((2 * dl - (gg & 6)) & 7) + (qq >> 1)) * 16u + (uint32_t)(qq & 1) * 8u;
+      v_rd[dl] = w.ta + SCR + (uint32_t)(ii * KU * PB) + (uint32_t)(8 * gg + ((2 * dl - (gg & 6)) & 7) + (qq >> 1)) * 16u + (uint32_t)(qq & 1) * 8u;
   }
+  // list Q: the lane's piece of a code row is widened and stored where the operand reads expect it.  Piece sl of a
+  // half tile holds the half's entries RPP*sl + lane/LPR; the lane's 16 bytes are CPL 16-byte pieces of the wide row.
+  constexpr int CPL = IS_Q ? RB / CRB : 1;
+  auto wide_addr = [&](int sl, int k, bool v_side) -> uint32_t {
+    const int el = RPP * sl + lane / LPR, i = el >> 3, gg = el & 7, cc = (lane % LPR) * CPL + k;
+    const int rot = v_side ? (gg & 6) : 2 * (gg >> 1) + (i & 1);
+    return w.ta + SCR + (uint32_t)((i * KU + (cc >> 3)) * PB) + (uint32_t)(8 * gg + (((cc & 7) - rot) & 7)) * 16u;
+  };
 
-  int lk[8];                                   // slots of entries 8*i + g of the tile whose K rows are fetched next
+  constexpr int NLK = IS_Q ? NP : 8;
+  int lk[NLK], lrow = 0;                       // slots of the rows this lane fetches next (K side), and of entry `lane`
   auto read_locs = [&](int par, int nvalid) {
     const uint32_t base = w.lta + (uint32_t)par * 256u;
     if (nvalid < 64) {                                   // wave-uniform: a list's last tile
       if (lane >= nvalid) lds_wr32(base + (uint32_t)lane * 4u, 0xffffffffu);   // no row: fetches land as zeros
     }
-    uint32_t t[8];
-    static_for<8>([&](auto ic) { constexpr int i = decltype(ic)::value; t[i] = lds_rd32<i * 32>(base + (uint32_t)g * 4u); });
-    lds_wait(); tie(t);
+    uint32_t t[NLK], me = 0;
+    if constexpr (!IS_Q) {
+      static_for<8>([&](auto ic) { constexpr int i = decltype(ic)::value; t[i] = lds_rd32<i * 32>(base + (uint32_t)g * 4u); });
+    } else {
+      static_for<NP>([&](auto ic) { constexpr int i = decltype(ic)::value; t[i] = lds_rd32<i * RPP * 4>(base + (uint32_t)(lane / LPR) * 4u); });
+      me = lds_rd32<0>(base + (uint32_t)lane * 4u);
+    }
+    lds_wait(); tie(t); tie(me);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) lk[i] = (int)t[i];
+    for (int i = 0; i < NLK; ++i) lk[i] = (int)t[i];
+    lrow = (int)me;
   };
   auto issue_loc = [&](int par, int tile) { dma<4>(rl, w.lt + par * 256, (uint32_t)(tile * 64 + lane) * 4u, 0); };
-  auto issue_k_piece = [&](int s) {                      // K piece s = (batch s / KU, row half s % KU)
-    const int i = s / KU, j = s % KU;
-    dma<16>(rk, w.t + s * PB, (uint32_t)lk[i] * (uint32_t)RB + (uint32_t)j * 128u + ((i & 1) ? kcol1 : kcol0), 1);
+  auto issue_scales = [&]() {                            // K scales, then V scales, of the entry `lane`
+#pragma unroll
+    for (int j = 0; j < SCD; ++j) dma<4>(rsk, w.sk + j * 256, (uint32_t)lrow * (uint32_t)a.sb + j * 4u, 0);
+#pragma unroll
+    for (int j = 0; j < SCD; ++j) dma<4>(rsv, w.sv + j * 256, (uint32_t)lrow * (uint32_t)a.sb + j * 4u, 0);
+  };
+  auto issue_k_piece = [&](int s) {
+    if constexpr (!IS_Q) {                               // (batch s / KU, row half s % KU)
+      const int i = s / KU, j = s % KU;
+      dma<16>(rk, w.t + s * PB, (uint32_t)lk[i] * (uint32_t)RB + (uint32_t)j * 128u + ((i & 1) ? kcol1 : kcol0), 1);
+    } else {
+      dma<16>(rk, w.t + s * PB, (uint32_t)lk[s] * (uint32_t)CRB + (uint32_t)(lane % LPR) * 16u, 1);
+    }
   };
 
-  wait_vm<NQD>();                                        // the list is in
+  wait_vm<0>();                                          // the list is in (and the query vectors)
   read_locs(0, n_list - tile0 * 64);
   issue_loc(1, tile0 + tstride);
+  issue_scales();
 #pragma unroll
   for (int s = 0; s < NP; ++s) issue_k_piece(s);
-  wait_vm<1 + NP>();                                     // the query block is in
-  // right operand of the logits: lane (n, kb) holds elements 32*ks + 8*kb .. +7 of head n (zeros for n >= G)
-  u32x4 qreg[NKS];
-  {
-    const uint32_t q_rd = w.pa + (uint32_t)((n < G ? n : 0) * D + 8 * kb) * 2u;
-    static_for<NKS>([&](auto kc) { constexpr int ks = decltype(kc)::value; qreg[ks] = lds_rd128<ks * 64>(q_rd); });
-    lds_wait(); tie(qreg);
-    if (n >= G) {
+
+  // sums of the query elements, per scale group (the codes' offset comes out through them): a product with ones
+  float qsum[NCB][NGD];
+  if constexpr (IS_Q) {
+    const uint32_t one2 = KT == KT_BF16 ? 0x3f803f80u : 0x3c003c00u;
+    const u32x4 ones = u32x4{one2, one2, one2, one2};
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) qreg[ks] = u32x4{0u, 0u, 0u, 0u};
+    for (int cb = 0; cb < NCB; ++cb) {
+      float tot = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const f32x4 s4 = mfma_16x16x32<KT>(ones, qreg[cb][ks], f32x4{0.f, 0.f, 0.f, 0.f});
+        if constexpr (M == Q_INT4) qsum[cb][ks] = s4[0]; else tot += s4[0];
+      }
+      if constexpr (M == Q_INT8) qsum[cb][0] = tot;
     }
   }
-  const size_t xrow = ((size_t)((b * a.n_q + jq) * a.Hq + kvh * G + (n < G ? n : 0))) * a.xs_stride + (size_t)(4 * kb);
+  float osub[NCB][NGD];                                  // sums of the scaled weights, per lane (list Q)
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int gd = 0; gd < NGD; ++gd) osub[cb][gd] = 0.f;
 
   int par = 1;                                           // LDS half that holds the next tile's slot list
   auto tile_body = [&](int tile, auto more_c) {
     constexpr bool MORE = decltype(more_c)::value;
     constexpr int X = MORE ? 1 : 0;
     __builtin_amdgcn_s_setprio(MORE ? 3 : 1);
-    int lv[8];                                           // this tile's V rows are fetched from the same slots
+    int lv[NLK];                                         // this tile's V rows are fetched from the same slots
 #pragma unroll
-    for (int i = 0; i < 8; ++i) lv[i] = lk[i];
+    for (int i = 0; i < NLK; ++i) lv[i] = lk[i];
     auto issue_v_piece = [&](int v) {
-      const int i = v / KU, j = v % KU;
-      dma<16>(rvv, w.t + v * PB, (uint32_t)lv[i] * (uint32_t)RB + (uint32_t)j * 128u + vcol, 1);
+      if constexpr (!IS_Q) {
+        const int i = v / KU, j = v % KU;
+        dma<16>(rvv, w.t + v * PB, (uint32_t)lv[i] * (uint32_t)RB + (uint32_t)j * 128u + vcol, 1);
+      } else {
+        dma<16>(rvv, w.t + v * PB, (uint32_t)lv[v] * (uint32_t)CRB + (uint32_t)(lane % LPR) * 16u, 1);
+      }
     };
     if constexpr (MORE) {
-      wait_vm<NP>();                                     // younger than the next list: this tile's K pieces
+      wait_vm<2 * SCD + NP>();                           // younger than the next list: this tile's scales and K pieces
       read_locs(par, n_list - (tile + tstride) * 64);
       issue_loc(par ^ 1, tile + 2 * tstride);
     }
-    // -- logits, 16 entries at a time; the K rows that have been read are replaced by V pieces
-    f32x4 c[4];
-    u32x4 ka[2][NKS];
-    auto read_k = [&](auto rc, u32x4 (&dst)[NKS]) {
+    // -- logits, 16 entries at a time
+    f32x4 c[NCB][4];
+    auto logits_of = [&](auto rc, const u32x4 (&ka)[NKS]) {    // rc: the 16-entry block
       constexpr int rb = decltype(rc)::value;
-      // younger than these K pieces: the later K pieces, this period's list fetch, the V pieces so far
-      wait_vm<NP - 2 * KU + X>();
-      static_for<NKS>([&](auto kc) {
-        constexpr int ks = decltype(kc)::value;
-        dst[ks] = lds_rd128<(rb * 2 * KU + (ks >> 1)) * PB>(k_rd[ks & 1]);
-      });
+      if constexpr (M == Q_INT4) {
+        // one product per scale group; the four entries' scales of dword ks/2, half ks & 1
+        u32x4 sc[SCD];
+        static_for<SCD>([&](auto jc) { constexpr int j = decltype(jc)::value; sc[j] = lds_rd128<j * 256 + rb * 64>(w.ska + (uint32_t)kb * 16u); });
+        lds_wait(); tie(sc);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < NKS; ++ks) {
+            const f32x4 part = mfma_16x16x32<KT>(ka[ks], qreg[cb][ks], f32x4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = fmaf(half_of(elem(sc[ks >> 1], j), ks & 1), fmaf(-OFF, qsum[cb][ks], part[j]), acc[j]);
+          }
+          c[cb][rb] = acc;
+        }
+      } else {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < NKS; ++ks) acc = mfma_16x16x32<KT>(ka[ks], qreg[cb][ks], acc);
+          c[cb][rb] = acc;
+        }
+        if constexpr (M == Q_INT8) {
+          u32x4 sc = lds_rd128<rb * 64>(w.ska + (uint32_t)kb * 16u);
+          lds_wait(); tie(sc);
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[cb][rb][j] = elem_f(sc, j) * fmaf(-OFF, qsum[cb][0], c[cb][rb][j]);
+        }
+      }
     };
-    read_k(std::integral_constant<int, 0>{}, ka[0]);
-    static_for<4>([&](auto rc) {
-      constexpr int rb = decltype(rc)::value;
-      lds_wait(); tie(ka[rb & 1]);
+    if constexpr (!IS_Q) {
+      // the K rows of 16 entries that have been read are replaced by V pieces
+      u32x4 ka[2][NKS];
+      auto read_k = [&](auto rc, u32x4 (&dst)[NKS]) {
+        constexpr int rb = decltype(rc)::value;
+        // younger than these K pieces: the later K pieces, this period's list fetch, the V pieces so far
+        wait_vm<NP - 2 * KU + X>();
+        static_for<NKS>([&](auto kc) {
+          constexpr int ks = decltype(kc)::value;
+          dst[ks] = lds_rd128<(rb * 2 * KU + (ks >> 1)) * PB>(k_rd[ks & 1]);
+        });
+      };
+      read_k(std::integral_constant<int, 0>{}, ka[0]);
+      static_for<4>([&](auto rc) {
+        constexpr int rb = decltype(rc)::value;
+        lds_wait(); tie(ka[rb & 1]);
 #pragma unroll
-      for (int v = 2 * rb * KU; v < (2 * rb + 2) * KU; ++v) issue_v_piece(v);
-      if constexpr (rb + 1 < 4) read_k(std::integral_constant<int, (rb + 1 < 4 ? rb + 1 : 3)>{}, ka[(rb + 1) & 1]);
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int v = 2 * rb * KU; v < (2 * rb + 2) * KU; ++v) issue_v_piece(v);
+        if constexpr (rb + 1 < 4) read_k(std::integral_constant<int, (rb + 1 < 4 ? rb + 1 : 3)>{}, ka[(rb + 1) & 1]);
+        logits_of(rc, ka[rb & 1]);
+      });
+    } else {
+      // half a tile of code rows is widened, then replaced by V pieces
+      static_for<2>([&](auto hc) {
+        constexpr int hf = decltype(hc)::value;
+        // younger than this half's K pieces: the other half's, this period's list fetch, the V pieces so far
+        wait_vm<NP - NPH + X>();
+        u32x4 cu[NPH];
+        static_for<NPH>([&](auto sc) { constexpr int sl = decltype(sc)::value; cu[sl] = lds_rd128<(hf * NPH + sl) * PB>(w.ta + (uint32_t)lane * 16u); });
+        lds_wait(); tie(cu);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) acc = mfma_16x16x32<KT>(ka[rb & 1][ks], qreg[ks], acc);
-      c[rb] = acc;
-    });
-    // -- online softmax: the lane has entries 16*rb + 4*kb + j of head n
-    float p[4][4];
+        for (int v = hf * NPH; v < (hf + 1) * NPH; ++v) issue_v_piece(v);
+#pragma unroll
+        for (int sl = 0; sl < NPH; ++sl) {
+          if constexpr (M == Q_INT8) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+              uint32_t w0, w1, w2, w3;
+              widen_int8<KT>(elem(cu[sl], 2 * k), w0, w1);
+              widen_int8<KT>(elem(cu[sl], 2 * k + 1), w2, w3);
+              lds_wr128<0>(wide_addr(sl, k, false), u32x4{w0, w1, w2, w3});
+            }
+          } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) lds_wr128<0>(wide_addr(sl, k, false), widen_int4<KT>(elem(cu[sl], k)));
+          }
+        }
+        static_for<2>([&](auto rlc) {
+          constexpr int rl2 = decltype(rlc)::value;
+          u32x4 ka[NKS];
+          static_for<NKS>([&](auto kc) {
+            constexpr int ks = decltype(kc)::value;
+            ka[ks] = lds_rd128<(rl2 * 2 * KU + (ks >> 1)) * PB>(k_rd[ks & 1]);
+          });
+          lds_wait(); tie(ka);
+          logits_of(std::integral_constant<int, 2 * hf + rl2>{}, ka);
+        });
+      });
+    }
+    // -- online softmax: the lane has entries 16*rb + 4*kb + j of its column
+    float p[NCB][4][4];
     {
-      float mx = -INFINITY;
       const int e0 = tile * 64 + 4 * kb;
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        f32x4 x;
+      for (int cb = 0; cb < NCB; ++cb) {
+        float mx = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          x[j] = (e0 + 16 * rb + j < n_list) ? c[rb][j] * a.softmax_scale : -INFINITY;
-          p[rb][j] = x[j];
-          mx = fmaxf(mx, x[j]);
+        for (int rb = 0; rb < 4; ++rb) {
+          f32x4 x;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            x[j] = (e0 + 16 * rb + j < n_seen[cb]) ? c[cb][rb][j] * a.softmax_scale : -INFINITY;
+            p[cb][rb][j] = x[j];
+            mx = fmaxf(mx, x[j]);
+          }
+          if (live[cb]) *(f32x4*)(a.xs + xrow[cb] + (size_t)(xs_tile0 + tile) * 64 + 16 * rb) = x;
         }
-        if (n < G) *(f32x4*)(a.xs + xrow + (size_t)(xs_tile0 + tile) * 64 + 16 * rb) = x;
-      }
-      mx = fmaxf(mx, lane_xor<16>(mx, lane));
-      mx = fmaxf(mx, lane_xor<32>(mx, lane));
-      // m_run starts at -inf and every tile has a live entry: corr = exp2(-inf) = 0 against zero accumulators
-      const float mn = fmaxf(m_run, mx);
-      const float corr = __builtin_amdgcn_exp2f((m_run - mn) * LOG2E);
-      float ps = 0.f;
+        mx = fmaxf(mx, lane_xor<16>(mx, lane));
+        mx = fmaxf(mx, lane_xor<32>(mx, lane));
+        // m_run starts at -inf: corr = exp2(-inf) = 0 against zero accumulators.  A tile of which the column sees
+        // nothing (an early token of a chunk, the list's last tile) leaves mn at -inf: nothing to add, nothing to rescale.
+        const float mn = fmaxf(m_run[cb], mx);
+        const float corr = mn > -INFINITY ? __builtin_amdgcn_exp2f((m_run[cb] - mn) * LOG2E) : 1.0f;
+        float ps = 0.f;
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+        for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { p[rb][j] = __builtin_amdgcn_exp2f(fmaf(p[rb][j] - mn, LOG2E, PSplit<KT>::P_SHIFT)); ps += p[rb][j]; }
-      l_run = fmaf(l_run, corr, ps);
-      m_run = mn;
-      // the output accumulators of this lane belong to heads 4*kb + j: their factors come from those heads' lanes;
-      // once the maxima have settled nothing needs rescaling (x * 1.0f is exact)
-      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
-        float cj[4];
+          for (int j = 0; j < 4; ++j) {
+            p[cb][rb][j] = mn > -INFINITY ? __builtin_amdgcn_exp2f(fmaf(p[cb][rb][j] - mn, LOG2E, PSplit<KT>::P_SHIFT)) : 0.f;
+            ps += p[cb][rb][j];
+          }
+        l_run[cb] = fmaf(l_run[cb], corr, ps);
+        m_run[cb] = mn;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          cj[j] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((4 * kb + j) << 2, __builtin_bit_cast(int, corr)));
+        for (int gd = 0; gd < NGD; ++gd) osub[cb][gd] *= corr;
+        // the output accumulators of this lane belong to columns 4*kb + j: their factors come from those columns'
+        // lanes; once the maxima have settled nothing needs rescaling (x * 1.0f is exact)
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
+          float cj[4];
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
+          for (int j = 0; j < 4; ++j)
+            cj[j] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((4 * kb + j) << 2, __builtin_bit_cast(int, corr)));
 #pragma unroll
-          for (int j = 0; j < 4; ++j) o[db][j] *= cj[j];
+          for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[cb][db][j] *= cj[j];
+        }
       }
     }
     // -- output: 32 entries per instruction; half a tile of V rows that has been read is replaced by K pieces
     __builtin_amdgcn_s_setprio(MORE ? 2 : 0);
+    constexpr int NT = PSplit<KT>::N;
+    // V scales of the tile: the 4 entries' of each 16-entry block (all older than the K pieces: they are in)
+    u32x4 vsc[IS_Q ? SCD : 1][4];
+    if constexpr (IS_Q) {
+      static_for<SCD>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        static_for<4>([&](auto rc) { constexpr int rb = decltype(rc)::value; vsc[j][rb] = lds_rd128<j * 256 + rb * 64>(w.sva + (uint32_t)kb * 16u); });
+      });
+      lds_wait();
+#pragma unroll
+      for (int j = 0; j < SCD; ++j) tie(vsc[j]);
+      if constexpr (MORE) issue_scales();                // both scale regions are free: the next tile's
+    }
+    // weights of the half's 32 entries as operand terms; list Q: times the V row's scale (of scale group gd)
+    auto weights = [&](auto tc, int cb, int gd, u32x4 (&pt)[NT]) {
+      constexpr int t = decltype(tc)::value;
+      float pw[2][4];
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float v = p[cb][2 * t + r2][j];
+          if constexpr (M == Q_INT8) v *= elem_f(vsc[0][2 * t + r2], j);
+          if constexpr (M == Q_INT4) v *= half_of(elem(vsc[gd >> 1][2 * t + r2], j), gd & 1);
+          if constexpr (IS_Q) osub[cb][gd] += v;
+          pw[r2][j] = v;
+        }
+      uint32_t s0[NT], s1[NT], s2[NT], s3[NT];
+      split_pair<KT>(pw[0][0], pw[0][1], s0);
+      split_pair<KT>(pw[0][2], pw[0][3], s1);
+      split_pair<KT>(pw[1][0], pw[1][1], s2);
+      split_pair<KT>(pw[1][2], pw[1][3], s3);
+#pragma unroll
+      for (int i = 0; i < NT; ++i) pt[i] = u32x4{s0[i], s1[i], s2[i], s3[i]};
+    };
     static_for<2>([&](auto tc) {
       constexpr int t = decltype(tc)::value;
-      constexpr int NT = PSplit<KT>::N;
-      u32x4 pt[NT];
-      {
-        uint32_t s0[NT], s1[NT], s2[NT], s3[NT];
-        split_pair<KT>(p[2 * t][0], p[2 * t][1], s0);
-        split_pair<KT>(p[2 * t][2], p[2 * t][3], s1);
-        split_pair<KT>(p[2 * t + 1][0], p[2 * t + 1][1], s2);
-        split_pair<KT>(p[2 * t + 1][2], p[2 * t + 1][3], s3);
+      // younger than this half's V pieces: the other half's, the next tile's scales, the K pieces issued after the first half
+      wait_vm<NPH * (1 - t) + X * (2 * SCD + t * NPH)>();
+      if constexpr (IS_Q) {
+        u32x4 cu[NPH];
+        static_for<NPH>([&](auto sc) { constexpr int sl = decltype(sc)::value; cu[sl] = lds_rd128<(t * NPH + sl) * PB>(w.ta + (uint32_t)lane * 16u); });
+        lds_wait(); tie(cu);
+        if constexpr (MORE) {
 #pragma unroll
-        for (int i = 0; i < NT; ++i) pt[i] = u32x4{s0[i], s1[i], s2[i], s3[i]};
+          for (int s = t * NPH; s < (t + 1) * NPH; ++s) issue_k_piece(s);
+        }
+#pragma unroll
+        for (int sl = 0; sl < NPH; ++sl) {
+          if constexpr (M == Q_INT8) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+              uint32_t w0, w1, w2, w3;
+              widen_int8<KT>(elem(cu[sl], 2 * k), w0, w1);
+              widen_int8<KT>(elem(cu[sl], 2 * k + 1), w2, w3);
+              lds_wr128<0>(wide_addr(sl, k, true), u32x4{w0, w1, w2, w3});
+            }
+          } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) lds_wr128<0>(wide_addr(sl, k, true), widen_int4<KT>(elem(cu[sl], k)));
+          }
+        }
       }
-      // younger than this half's V pieces: the other half's, then the K pieces issued after the first half
-      wait_vm<(NP / 2) * (1 - t) + X * t * (NP / 2)>();
+      constexpr int RB0 = IS_Q ? 0 : 2 * t;              // the widened half sits at the start of its area
       u32x2 vv[2][NDB];
       static_for<2>([&](auto r2c) {
         constexpr int r2 = decltype(r2c)::value;
         static_for<NDB>([&](auto dc) {
           constexpr int db = decltype(dc)::value;
-          vv[r2][db] = lds_rd64_tr16<((2 * t + r2) * 2 * KU + (db >> 2)) * PB>(v_rd[db & 3]);
+          vv[r2][db] = lds_rd64_tr16<((RB0 + r2) * 2 * KU + (db >> 2)) * PB>(v_rd[db & 3]);
         });
       });
       lds_wait(); tie(vv[0]); tie(vv[1]);
-      if constexpr (MORE) {
+      if constexpr (!IS_Q && MORE) {
 #pragma unroll
-        for (int s = t * (NP / 2); s < (t + 1) * (NP / 2); ++s) issue_k_piece(s);
+        for (int s = t * NPH; s < (t + 1) * NPH; ++s) issue_k_piece(s);
       }
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        const u32x4 vb = u32x4{vv[0][db].x, vv[0][db].y, vv[1][db].x, vv[1][db].y};
+      for (int cb = 0; cb < NCB; ++cb) {
+        u32x4 pt[NT];
+        if constexpr (M != Q_INT4) weights(tc, cb, 0, pt);
 #pragma unroll
-        for (int i = NT - 1; i >= 0; --i) o[db] = mfma_16x16x32<KT>(pt[i], vb, o[db]);
+        for (int db = 0; db < NDB; ++db) {
+          if constexpr (M == Q_INT4) { if (db % 2 == 0) weights(tc, cb, db / 2, pt); }
+          const u32x4 vb = u32x4{vv[0][db].x, vv[0][db].y, vv[1][db].x, vv[1][db].y};
+#pragma unroll
+          for (int i = NT - 1; i >= 0; --i) o[cb][db] = mfma_16x16x32<KT>(pt[i], vb, o[cb][db]);
+        }
       }
     });
     par ^= 1;
@@ -1068,13 +1304,36 @@ __device__ __forceinline__ void attn_wave_mfma(const AttnArgs& a, const WaveLds&
   int tile = tile0;
   for (; (tile + tstride) * 64 < n_list; tile += tstride) tile_body(tile, std::true_type{});
   tile_body(tile, std::false_type{});
+
+  if constexpr (IS_Q) {
+    // the codes went in as code + OFF: take OFF times the sum of the scaled weights back out, per column (the
+    // accumulators of this lane belong to columns 4*kb + j)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int gd = 0; gd < NGD; ++gd) {
+        float s = osub[cb][gd];
+        s += lane_xor<16>(s, lane);
+        s += lane_xor<32>(s, lane);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float sj = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((4 * kb + j) << 2, __builtin_bit_cast(int, s)));
+#pragma unroll
+          for (int db = 0; db < NDB; ++db)
+            if (NGD == 1 || db / 2 == gd) o[cb][db][j] = fmaf(-OFF, sj, o[cb][db][j]);
+        }
+      }
+  }
   if constexpr (PSplit<KT>::P_SHIFT != 0.f) {
     const float back = __builtin_amdgcn_exp2f(-PSplit<KT>::P_SHIFT);
-    l_run *= back;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+    for (int cb = 0; cb < NCB; ++cb) {
+      l_run[cb] *= back;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) o[db][j] *= back;
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[cb][db][j] *= back;
+    }
   }
 }
 
@@ -1162,31 +1421,9 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
 #pragma unroll
     for (int e = 0; e < EV; ++e) o[h][e] = 0.f;
   }
-  bool o_written = false, mfma_wave = false;
+  bool o_written = false;
   if (u < nwf) {
-    if constexpr (KT != KT_F32) {
-      // 16-bit rows go through the matrix cores; the wave's result arrives complete, in one slice
-      f32x4 om[D / 16];
-#pragma unroll
-      for (int db = 0; db < D / 16; ++db) om[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-      float mr = -INFINITY, lr = 0.f;
-      attn_wave_mfma<D, G, KT>(a, w, b, jq, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, om, mr, lr);
-      lr += lane_xor<16>(lr, lane);
-      lr += lane_xor<32>(lr, lane);
-      if (lane < G) { sm_ml[wave * 16 + lane] = mr; sm_ml[wave * 16 + 8 + lane] = lr; }
-#pragma unroll
-      for (int db = 0; db < D / 16; ++db)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int h = 4 * (lane >> 4) + j;
-          if (h < G) my_o[h * D + 16 * db + (lane & 15)] = om[db][j];
-        }
-      for (int i = lane; i < (NGK - 1) * G * D; i += 64) my_o[G * D + i] = 0.f;
-      mfma_wave = true;
-      o_written = true;
-    } else {
-      attn_wave<D, G, KG::MF, KT>(a, w, b, jq, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
-    }
+    attn_wave<D, G, KG::MF, KT>(a, w, b, jq, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, o, m_run, l_lane);
   } else {
     if constexpr (EV == 8) {
       if (a.t2fmt == 0) attn_wave<D, G, Q_INT8, KT>(a, w, b, jq, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, o, m_run, l_lane);
@@ -1234,12 +1471,10 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
         for (int e = 0; e < EV; ++e) dst[h * D + e] = o[h][e];
     }
   }
-  if (!mfma_wave) {
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float ls = wave_sum(l_lane[h]);
-      if (lane == 0) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = ls; }
-    }
+  for (int h = 0; h < G; ++h) {
+    const float ls = wave_sum(l_lane[h]);
+    if (lane == 0) { sm_ml[wave * 16 + h] = m_run[h]; sm_ml[wave * 16 + 8 + h] = ls; }
   }
   __syncthreads();
   const int bq = b * a.n_q + jq;
@@ -1274,6 +1509,108 @@ __global__ __launch_bounds__((KernelGeo<D, G, KT>::NW * 64), (KernelGeo<D, G, KT
     float* pm = a.part_ml + ((size_t)((bq * a.Hkv + kvh) * a.S_total + a.s0 + s) * 2) * G;
     pm[t] = mb;
     pm[G + t] = ll;
+  }
+}
+
+// ---- the same launch for 16-bit rows: every wave on the matrix cores ------------------------------------------------
+// Eight waves per workgroup whatever the group size (the accumulators are 16 columns wide either way), a 64-row tile
+// buffer each; with a second block of 16 columns (chunks of query tokens) the registers allow four.  A wave's result
+// arrives complete (no row-group partials): [column][D] parked in its tile buffer.
+constexpr int mc_waves(int ncb) { return ncb == 1 ? 8 : 4; }
+template <int D, int G, int KT, int NCB>
+__global__ __launch_bounds__(mc_waves(NCB) * 64, mc_waves(NCB) / 4) void k_attn_tiered_mc(const AttnArgs a) {
+  constexpr int NW = mc_waves(NCB), RB = 2 * D, TILE_BYTES = 64 * RB;
+  constexpr Mode MF = KT == KT_BF16 ? F_BF16 : F_F16;
+  static_assert(16 * NCB * D * 4 <= TILE_BYTES, "a wave's output partial is parked in its tile buffer");
+  __shared__ __attribute__((aligned(16))) char sm_t[NW * TILE_BYTES];
+  __shared__ __attribute__((aligned(16))) char sm_sc[NW * 2 * 512];
+  __shared__ __attribute__((aligned(16))) char sm_lt[NW * 512];
+  __shared__ float sm_ml[NW * 64];                       // per wave: m of 32 columns, then l
+  const int s = blockIdx.x, kvh = blockIdx.y;
+  // query tokens beyond one per sequence: a.cq of them as columns of this workgroup, a.n_q such groups along grid z.
+  // The group's last token is (n_q - 1 - jz) * cq positions older than the chunk's last, and that many entries at the
+  // end of list F are not the group's to see (its earlier tokens cut off more, column by column).
+  const int b = a.n_q > 1 ? (int)blockIdx.z / a.n_q : (int)blockIdx.z, jz = a.n_q > 1 ? (int)blockIdx.z % a.n_q : 0;
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  int nF, nQ, xsb = 0;
+  if (!a.second) {
+    if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
+    else { nF = a.cnt[b * CNT_N + C_NF] - a.trim; nQ = a.cnt[b * CNT_N + C_NQ]; }
+    nF -= (a.n_q - 1 - jz) * a.cq;
+  } else {
+    nF = a.cnt[b * CNT_N + C_NS]; nQ = 0;
+    xsb = ((a.cnt[b * CNT_N + C_NF] - a.trim + 63) >> 6) + ((a.cnt[b * CNT_N + C_NQ] + 63) >> 6);
+  }
+  const int nft = (nF + 63) >> 6, nqt = (nQ + 63) >> 6;
+  const int nwv = a.S * NW;
+  const int nwq = a.second ? 0 : (a.B <= ATTN_ARG_SEQS && a.n_q == 1) ? a.nWq[b] : q_waves(nwv, nft, nqt), nwf = nwv - nwq;
+  const int u = s * NW + wave;
+  const int ncol = a.cq * G;
+
+  WaveLds w;
+  w.t = sm_t + wave * TILE_BYTES;
+  w.sk = sm_sc + wave * 1024; w.sv = w.sk + 512; w.lt = sm_lt + wave * 512;
+  w.ta = lds_addr(w.t); w.ska = lds_addr(w.sk); w.sva = lds_addr(w.sv); w.lta = lds_addr(w.lt);
+  w.p = nullptr; w.pa = 0;
+  float* my_o = (float*)w.t;          // after the wave's last tile: its output partial, [column][D]
+
+  f32x4 om[NCB][D / 16];
+  float mr[NCB], lr[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    mr[cb] = -INFINITY; lr[cb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < D / 16; ++db) om[cb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  if (u < nwf) attn_wave_mfma<D, G, KT, MF, NCB>(a, w, b, jz, kvh, lane, u, nwf, nF, a.f_loc + (size_t)b * a.Nmax, xsb, om, mr, lr);
+  else if (a.t2fmt == 0) attn_wave_mfma<D, G, KT, Q_INT8, NCB>(a, w, b, jz, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, om, mr, lr);
+  else attn_wave_mfma<D, G, KT, Q_INT4, NCB>(a, w, b, jz, kvh, lane, u - nwf, nwq, nQ, a.q_loc + (size_t)b * a.Nmax, xsb + nft, om, mr, lr);
+  // ---- wave partial into LDS: lane (n, kb) has the statistics of column 16*cb + n and the outputs of columns
+  // 16*cb + 4*kb + j, element 16*db + n
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    float ls = lr[cb];
+    ls += lane_xor<16>(ls, lane);
+    ls += lane_xor<32>(ls, lane);
+    const int col = 16 * cb + lane;
+    if (lane < 16 && col < ncol) { sm_ml[wave * 64 + col] = mr[cb]; sm_ml[wave * 64 + 32 + col] = ls; }
+#pragma unroll
+    for (int db = 0; db < D / 16; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = 16 * cb + 4 * (lane >> 4) + j;
+        if (c < ncol) my_o[c * D + 16 * db + (lane & 15)] = om[cb][db][j];
+      }
+  }
+  __syncthreads();
+  // ---- merge the waves: one split partial (m, l, o[G][D]) per query token
+  const int bq0 = (b * a.n_q + jz) * a.cq;
+  for (int i = t; i < ncol * D; i += NW * 64) {
+    const int col = i / D, d = i % D, jq = col / G, h = col % G;
+    float mb = sm_ml[col];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) mb = fmaxf(mb, sm_ml[ww * 64 + col]);
+    float acc = 0.f;
+    if (mb > -INFINITY) {
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww)
+        acc = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 64 + col] - mb) * LOG2E), ((const float*)(sm_t + ww * TILE_BYTES))[i], acc);
+    }
+    a.part_o[((size_t)(((bq0 + jq) * a.Hkv + kvh) * a.S_total + a.s0 + s) * G + h) * D + d] = acc;
+  }
+  if (t < ncol) {
+    const int jq = t / G, h = t % G;
+    float mb = sm_ml[t];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) mb = fmaxf(mb, sm_ml[ww * 64 + t]);
+    float ll = 0.f;
+    if (mb > -INFINITY) {
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) ll = fmaf(__builtin_amdgcn_exp2f((sm_ml[ww * 64 + t] - mb) * LOG2E), sm_ml[ww * 64 + 32 + t], ll);
+    }
+    float* pm = a.part_ml + ((size_t)(((bq0 + jq) * a.Hkv + kvh) * a.S_total + a.s0 + s) * 2) * G;
+    pm[h] = mb;
+    pm[G + h] = ll;
   }
 }
 
@@ -1390,18 +1727,19 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   }
 }
 
-// ---- finish for several query tokens per sequence (one launch served n_q of them) ----------------------------
-// Grid (64-entry slots of the longest query's lists + Hq * n_q, B).  Slot workgroups: every list entry gets the
-// weights of the n_q queries added in query order (what n_q single-token calls would have done, with the same
-// arithmetic per query: thread (e, hg) sums kv heads hg, hg+4, ..., the four partial sums are added in the order
-// hg = 0..3).  Query jq does not see the last n_q - 1 - jq entries of list F, and its Q-list logits start at its own
-// number of F tiles.  The other workgroups merge the splits of one (query, head) into out.
+// ---- finish for several query tokens per sequence (one launch served n_q * cq of them) --------------------------
+// Grid (64-entry slots of the last token's lists + Hq * queries, B).  Slot workgroups: every list entry gets the
+// weights of the queries added in query order (what single-token calls would have done, with the same arithmetic per
+// query: thread (e, hg) sums kv heads hg, hg+4, ..., the four partial sums are added in the order hg = 0..3).  Query
+// jt does not see the last queries - 1 - jt entries of list F; its Q-list logits start where the F tiles of its
+// group (the cq tokens of one workgroup, laid out for the group's last token) end.  The other workgroups merge the
+// splits of one (query, head) into out.
 template <int D, int G>
 __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int n_tiles) {
-  constexpr int MAXQ = 8;
+  constexpr int MAXQ = 16;
   __shared__ float M[MAXQ][128], IL[MAXQ][128];
   __shared__ float sm_part[256];
-  const int t = threadIdx.x, b = blockIdx.y, nq = a.n_q, ns = a.S_total;
+  const int t = threadIdx.x, b = blockIdx.y, nq = a.n_q * a.cq, ns = a.S_total;
   int nF, nQ;
   if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
   else { nF = a.cnt[b * CNT_N + C_NF] - a.trim; nQ = a.cnt[b * CNT_N + C_NQ]; }
@@ -1410,42 +1748,43 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
   if (is_tile && (int)blockIdx.x * 64 >= cf * TB + nQ) return;
   // global (m, 1/l) of every (query, head) of this sequence
   for (int i = t; i < nq * a.Hq; i += 256) {
-    const int jq = i / a.Hq, hq = i % a.Hq, kvh = hq / G, g = hq % G;
-    const float* src = a.part_ml + (size_t)((b * nq + jq) * a.Hkv + kvh) * ns * 2 * G;
+    const int jt = i / a.Hq, hq = i % a.Hq, kvh = hq / G, g = hq % G;
+    const float* src = a.part_ml + (size_t)((b * nq + jt) * a.Hkv + kvh) * ns * 2 * G;
     float mm = -INFINITY;
     for (int k = 0; k < ns; ++k) mm = fmaxf(mm, src[k * 2 * G + g]);
     float ll = 0.f;
     for (int k = 0; k < ns; ++k) ll = fmaf(src[k * 2 * G + G + g], __builtin_amdgcn_exp2f((src[k * 2 * G + g] - mm) * LOG2E), ll);
-    M[jq][hq] = mm > -INFINITY ? mm : 0.f;
-    IL[jq][hq] = ll > 0.f ? 1.0f / ll : 0.f;
+    M[jt][hq] = mm > -INFINITY ? mm : 0.f;
+    IL[jt][hq] = ll > 0.f ? 1.0f / ll : 0.f;
   }
   __syncthreads();
   if (is_tile) {
     const int e = t & 63, hg = t >> 6;
-    const int sl = blockIdx.x * 64 + e;                     // slot in the longest query's layout
+    const int sl = blockIdx.x * 64 + e;                     // slot in the last query's layout
     const bool is_f = sl < nF, is_q = sl >= cf * TB && sl - cf * TB < nQ;
     int pos = -1;
     if (is_f) pos = a.f_pos[(size_t)b * a.Nmax + sl];
     else if (is_q) pos = a.q_pos[(size_t)b * a.Nmax + (sl - cf * TB)];
     float score = (hg == 0 && pos >= 0) ? a.score[(size_t)b * a.Nmax + pos] : 0.f;
-    for (int jq = 0; jq < nq; ++jq) {
-      const int nFj = nF - (nq - 1 - jq), cfj = (nFj + TB - 1) / TB;
+    for (int jt = 0; jt < nq; ++jt) {
+      const int nFj = nF - (nq - 1 - jt);                                   // what the query sees of list F
+      const int cfz = (nF - (a.n_q - 1 - jt / a.cq) * a.cq + TB - 1) / TB;  // F tiles in its group's layout
       const bool seen = is_q || (is_f && sl < nFj);         // wave-divergent at most in a list's last tile
-      const int col = is_q ? cfj * TB + (sl - cf * TB) : sl;
+      const int col = is_q ? cfz * TB + (sl - cf * TB) : sl;
       float acc = 0.f;
       if (seen) {
         for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
           float x[G];
 #pragma unroll
-          for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)(b * nq + jq) * a.Hq + kvh * G + g) * a.xs_stride + col];
+          for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)(b * nq + jt) * a.Hq + kvh * G + g) * a.xs_stride + col];
           if (a.vnorm) {
             float w = 0.f;
 #pragma unroll
-            for (int g = 0; g < G; ++g) w += __builtin_amdgcn_exp2f((x[g] - M[jq][kvh * G + g]) * LOG2E) * IL[jq][kvh * G + g];
+            for (int g = 0; g < G; ++g) w += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
             acc = fmaf(w, a.vnorm[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
           } else {
 #pragma unroll
-            for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[jq][kvh * G + g]) * LOG2E) * IL[jq][kvh * G + g];
+            for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
           }
         }
       }
@@ -1457,11 +1796,11 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
     if (hg == 0 && pos >= 0) a.score[(size_t)b * a.Nmax + pos] = score;
   } else {
     constexpr int NSG = 256 / D;
-    const int idx = blockIdx.x - n_tiles, jq = idx / a.Hq, hq = idx % a.Hq, kvh = hq / G, h = hq % G;
+    const int idx = blockIdx.x - n_tiles, jt = idx / a.Hq, hq = idx % a.Hq, kvh = hq / G, h = hq % G;
     const int d = t % D, sg = t / D;
-    const float* pm = a.part_ml + (size_t)((b * nq + jq) * a.Hkv + kvh) * ns * 2 * G;
-    const float* pob = a.part_o + ((size_t)((b * nq + jq) * a.Hkv + kvh) * ns * G) * D + h * D + d;
-    const float mg = M[jq][hq];
+    const float* pm = a.part_ml + (size_t)((b * nq + jt) * a.Hkv + kvh) * ns * 2 * G;
+    const float* pob = a.part_o + ((size_t)((b * nq + jt) * a.Hkv + kvh) * ns * G) * D + h * D + d;
+    const float mg = M[jt][hq];
     float acc = 0.f;
 #pragma unroll 4
     for (int k = sg; k < ns; k += NSG)
@@ -1472,8 +1811,8 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
       float tot = sm_part[d];
 #pragma unroll
       for (int g2 = 1; g2 < NSG; ++g2) tot += sm_part[g2 * D + d];
-      tot *= IL[jq][hq];
-      const size_t oi = ((size_t)b * a.o_bs + (size_t)jq * a.Hq + hq) * D + d;
+      tot *= IL[jt][hq];
+      const size_t oi = ((size_t)b * a.o_bs + (size_t)jt * a.Hq + hq) * D + d;
       if (a.out_kind == KT_BF16) ((uint16_t*)a.out)[oi] = f32_to_bf16(tot);
       else if (a.out_kind == KT_F16) ((_Float16*)a.out)[oi] = (_Float16)tot;
       else ((float*)a.out)[oi] = tot;
@@ -1507,9 +1846,21 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
 template <int D, int G, int KT>
 static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   dim3 grid(a.S, a.Hkv, a.B * a.n_q);
-  constexpr int threads = KernelGeo<D, G, KT>::NW * 64;
-  if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
-  else hipLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, a);
+  if constexpr (KT == KT_F32) {
+    if (a.cq != 1) return hipErrorInvalidValue;
+    constexpr int threads = KernelGeo<D, G, KT>::NW * 64;
+    if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
+    else hipLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, a);
+  } else {
+    if (a.cq < 1 || a.cq * G > 32) return hipErrorInvalidValue;
+    if (a.cq * G <= 16) {
+      if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered_mc<D, G, KT, 1>), grid, dim3(mc_waves(1) * 64), 0, st, ev0, ev1, 0, a);
+      else hipLaunchKernelGGL((k_attn_tiered_mc<D, G, KT, 1>), grid, dim3(mc_waves(1) * 64), 0, st, a);
+    } else {
+      if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered_mc<D, G, KT, 2>), grid, dim3(mc_waves(2) * 64), 0, st, ev0, ev1, 0, a);
+      else hipLaunchKernelGGL((k_attn_tiered_mc<D, G, KT, 2>), grid, dim3(mc_waves(2) * 64), 0, st, a);
+    }
+  }
   return hipGetLastError();
 }
 template <int D, int KT>
@@ -1563,16 +1914,19 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream
   if (D == 64 && kt == KT_F16) return tiered_by_group<64, KT_F16>(a, G, st, ev0, ev1);
   return hipErrorInvalidValue;
 }
-int attn_waves_per_group(int D, int elem_bytes, int G) { return waves_per_group(D * elem_bytes, G); }
+int attn_waves_per_group(int D, int elem_bytes, int G, int cq) {
+  return elem_bytes == 2 ? mc_waves(cq * G <= 16 ? 1 : 2) : waves_per_group(D * elem_bytes, G);
+}
+int attn_cols_per_launch(int elem_bytes, int G) { return elem_bytes == 2 ? (32 / G < 16 ? 32 / G : 16) : 1; }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }
 
 template <int D, int G, int KT>
 static hipError_t run_finish_chunk(const AttnArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((k_attn_finish_chunk<D, G>), dim3(a.n_tiles + a.Hq * a.n_q, a.B), dim3(256), 0, st, a, a.n_tiles);
+  hipLaunchKernelGGL((k_attn_finish_chunk<D, G>), dim3(a.n_tiles + a.Hq * a.n_q * a.cq, a.B), dim3(256), 0, st, a, a.n_tiles);
   return hipGetLastError();
 }
 hipError_t launch_attn_finish_chunk(const AttnArgs& a, int D, int G, hipStream_t st) {
-  if (a.n_q < 1 || a.n_q > 8 || a.Hq > 128) return hipErrorInvalidValue;
+  if (a.n_q < 1 || a.cq < 1 || a.n_q * a.cq > 16 || a.Hq > 128) return hipErrorInvalidValue;
   if (D == 128) { TKV_DISPATCH_G(run_finish_chunk, 128, KT_BF16, a, st) }
   if (D == 64) { TKV_DISPATCH_G(run_finish_chunk, 64, KT_BF16, a, st) }
   return hipErrorInvalidValue;

@@ -602,19 +602,23 @@ tkv_status tkv_append(tkv_cache* c, int32_t layer, const void* k, const void* v,
   return TKV_OK;
 }
 
-// Most query tokens of a chunk that one launch serves; longer chunks go in groups of this many.
-constexpr int CHUNK_MAX_Q = 8;
+// Most query tokens of a chunk that one launch serves; longer chunks go in groups.  16-bit rows: as many as fit the
+// 16 columns of a workgroup's accumulators beside the group's heads (the cache is read once for all of them); binary32
+// rows: one workgroup set per token along the grid.
+static int chunk_tokens_per_launch(const tkv_cache* c) {
+  return c->es == 2 ? attn_cols_per_launch(2, c->G) : 8;
+}
 
 // Scratch for launches that serve several query tokens per sequence: logits and split partials per (sequence, query).
-// Allocated on the first such call, for CHUNK_MAX_Q queries, and kept until the cache is destroyed.
+// Allocated on the first such call, for as many queries as one launch takes, and kept until the cache is destroyed.
 static tkv_status chunk_scratch(tkv_cache* c) {
   if (c->xs_chunk) return TKV_OK;
   const DevView& v = c->dv;
-  const size_t nb = (size_t)v.B * CHUNK_MAX_Q;
+  const size_t nb = (size_t)v.B * chunk_tokens_per_launch(c);
   float *x = nullptr, *ml = nullptr, *po = nullptr;
   if (!dalloc(c, x, nb * v.Hq * c->xs_stride) || !dalloc(c, ml, nb * v.Hkv * c->S_alloc * 2 * c->G) ||
       !dalloc(c, po, nb * v.Hkv * c->S_alloc * c->G * v.D))
-    return fail(c, TKV_ENOMEM, "tkv_attend_and_score_chunk: no device memory for the scratch of %d query tokens per launch", CHUNK_MAX_Q);
+    return fail(c, TKV_ENOMEM, "tkv_attend_and_score_chunk: no device memory for the scratch of %d query tokens per launch", chunk_tokens_per_launch(c));
   c->xs_chunk = x; c->ml_chunk = ml; c->po_chunk = po;
   return TKV_OK;
 }
@@ -629,7 +633,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
                              hipStream_t st, bool noalloc = false, int m = 1) {
   const DevView& v = c->dv;
   if (m > 1) {
-    if (c->streamed || noalloc || m > CHUNK_MAX_Q) return fail(c, TKV_EINVAL, "attend_one: %d queries per launch not possible here", m);
+    if (c->streamed || noalloc || m > chunk_tokens_per_launch(c)) return fail(c, TKV_EINVAL, "attend_one: %d queries per launch not possible here", m);
     tkv_status cs = chunk_scratch(c);
     if (cs != TKV_OK) return cs;
   }
@@ -670,7 +674,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   }
   if (n_tiles * TOK_PER_BLOCK > c->xs_stride) return fail(c, TKV_ESTATE, "tkv_attend_and_score: internal tile count %d exceeds the scratch", n_tiles);
   // no more workgroups per pair than there are tiles for their waves
-  const int nw = attn_waves_per_group(v.D, c->es, c->G);
+  const int nw = attn_waves_per_group(v.D, c->es, c->G, m);
   const int S = std::max(1, std::min(c->S_alloc, (n_tiles - n_tiles_s + nw - 1) / nw));
   const int S2 = n_tiles_s > 0 ? std::max(1, std::min(c->S_alloc, (n_tiles_s + nw - 1) / nw)) : 0;
   AttnArgs a{};
@@ -703,7 +707,8 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.B = v.B; a.Hq = v.Hq; a.Hkv = v.Hkv; a.Nmax = v.Nmax; a.capF = v.capP; a.cap2 = v.cap2;
   a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_kind = c->cfg.out_dtype;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
-  a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim; a.n_q = m;
+  a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim;
+  if (c->es == 2) { a.n_q = 1; a.cq = m; } else { a.n_q = m; a.cq = 1; }
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
   EvPair* pf = nullptr;
@@ -772,10 +777,9 @@ tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q
     return fail(c, TKV_ESTATE, "tkv_attend_and_score_chunk: %d query tokens, but only %d positions were appended since the last tkv_migrate", n_q, c->n_assigned - c->n_at_plan);
   const DevView& v = c->dv;
   const size_t q_tok = (size_t)v.Hq * v.D * c->es, o_tok = (size_t)v.Hq * v.D * (c->cfg.out_dtype == TKV_F32 ? 4 : 2);
-  // The cache is read once for up to CHUNK_MAX_Q of the chunk's tokens: one launch whose workgroups of consecutive
-  // tokens run side by side on the same rows.  The streamed mode, whose frame serves one launch pair at a time, takes
-  // the tokens one by one.
-  const int per = c->streamed ? 1 : CHUNK_MAX_Q;
+  // The chunk's tokens go in groups of as many as one launch takes (16-bit rows: the cache is read once per group).
+  // The streamed mode, whose frame serves one launch pair at a time, takes the tokens one by one.
+  const int per = c->streamed ? 1 : chunk_tokens_per_launch(c);
   for (int j = 0; j < n_q; j += per) {
     const int m = std::min(per, n_q - j);
     tkv_status s = attend_one(c, layer, (const char*)q + j * q_tok, (char*)out + j * o_tok, n_q - j - m, n_q * v.Hq, n_q * v.Hq,

@@ -100,9 +100,11 @@ struct AttnArgs {
   int q_bs, o_bs;   // query heads between consecutive sequences in q and in out: Hq, or n_q * Hq for the tokens of a chunk
   int trim;         // entries at the end of list F this call leaves out (the chunk's later tokens); nF[] has them
                     // taken off already, the device counter has not
-  int n_q;          // query tokens per sequence served by this launch (>= 1): grid z = B * n_q, query jq of a sequence
-                    // is Hq heads further on in q and out, leaves n_q - 1 - jq more entries of list F out (it is that
-                    // many positions older), and has logits and split partials of its own (index b * n_q + jq)
+  int n_q, cq;      // query tokens per sequence served by this launch: n_q groups along grid z (grid z = B * n_q) of cq
+                    // tokens each (columns of one workgroup; 16-bit rows only, cq * G <= 32).  Token jt = jz * cq + jc of
+                    // a sequence is jt * Hq heads further on in q and out, leaves n_q * cq - 1 - jt more entries of
+                    // list F out (it is that many positions older), and has logits and split partials of its own
+                    // (index b * n_q * cq + jt)
   int B, Hq, Hkv, Nmax, capF, cap2, xs_stride, cb, sb, t2fmt, out_kind, q_es;   // out_kind: 0 binary32, 1 bfloat16, 2 binary16
   float softmax_scale, score_scale;
   int nF[ATTN_ARG_SEQS], nQ[ATTN_ARG_SEQS];   // list lengths per sequence (host mirror), used when B <= ATTN_ARG_SEQS
@@ -116,8 +118,9 @@ struct AttnArgs {
 hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish(const AttnArgs& a, int D, int G, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attn_finish_chunk(const AttnArgs& a, int D, int G, hipStream_t st);
+int attn_cols_per_launch(int elem_bytes, int G);   // query tokens one workgroup can take as columns
 hipError_t launch_probe_read(const void* src, size_t bytes, int workgroups, uint32_t* sink, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
-int attn_waves_per_group(int D, int elem_bytes, int G);   // waves per attention workgroup (one workgroup per compute unit)
+int attn_waves_per_group(int D, int elem_bytes, int G, int cq = 1);   // waves per attention workgroup (one workgroup per compute unit)
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles);   // how many of a pair's waves serve the Q list
 hipError_t launch_append(const DevView& v, int layer, const void* k, const void* v_, int pos0, int n_new,
                          bool assign, hipStream_t st);
