@@ -315,6 +315,51 @@ def link_probe(launch_bytes):
     return out
 
 
+def chunk_probe(cfg, n_q=4, layers=4, calls=200):
+    """tkv_attend_and_score_chunk at the workload's per-layer shape (a few layers, tiers from one score-driven event):
+    the time of one layer call with n_q query tokens per sequence, beside the single-token call on the same cache."""
+    import torch
+    import paper_2605_09490_amd as tkv
+    from tkv_synth import Workload
+    c = dataclasses.replace(cfg, n_layers=layers, decode_steps=1 + n_q)
+    wl = Workload(c, device="cuda")
+    gpu = tkv.TieredKV(c.n_layers, c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.max_tokens, kv_dtype=c.kv_dtype,
+                       t2_format=c.t2_format, k_sink=c.k_sink, k_window=c.k_window, prefetch_mode="lazy")
+    for l in range(layers):
+        k, v = wl.context_kv(l)
+        gpu.append(l, k, v)
+    del k, v
+    k_all, v_all, q_all = wl.decode_inputs(0, 1 + n_q)
+    gpu.decode_step(k_all[0], v_all[0], q_all[0])
+    gpu.classify(c.policy_ppm)
+    gpu.migrate()
+    gpu.wait_prefetch()
+    for l in range(layers):
+        gpu.append(l, torch.cat([k_all[1 + j, l] for j in range(n_q)], dim=1), torch.cat([v_all[1 + j, l] for j in range(n_q)], dim=1))
+    qs = [torch.stack([q_all[1 + j, l] for j in range(n_q)], dim=1).contiguous() for l in range(layers)]
+    outs = [torch.empty(q.shape, dtype=gpu.out_torch_dtype, device="cuda") for q in qs]
+    q1 = [q[:, n_q - 1].contiguous() for q in qs]
+    o1 = [torch.empty(q.shape, dtype=gpu.out_torch_dtype, device="cuda") for q in q1]
+    res = {}
+    for name, fn in (("chunk", lambda i: gpu.attend_and_score_chunk(i % layers, qs[i % layers], outs[i % layers])),
+                     ("single", lambda i: gpu.attend_and_score(i % layers, q1[i % layers], o1[i % layers]))):
+        for i in range(8):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(calls):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = e0.elapsed_time(e1) * 1e3 / calls
+    gpu.close()
+    return {"what": f"tkv_attend_and_score_chunk, {n_q} query tokens per sequence, per layer call at this workload's shape "
+                    f"({layers} layers, tiers from a score-driven event); event-timed over {calls} calls in a row",
+            "n_q": n_q, "per_layer_call_us": round(res["chunk"], 2), "single_token_call_us": round(res["single"], 2),
+            "ratio_to_single": round(res["chunk"] / res["single"], 2)}
+
+
 def compact_record(name, steps, rule):
     """twin + lazy once for one of the other benchmark shapes: the figures only."""
     from tkv_synth import CONFIGS
@@ -464,6 +509,12 @@ def main():
     call_GBps = main_res["call_bytes_per_launch"] / (main_res["call_avg_us"] * 1e-6) / 1e9
     h2d_GBps = main_res["h2d_bytes"] / (main_res["h2d_ms"] * 1e-3) / 1e9 if main_res["h2d_ms"] > 0 else None
     d2h_GBps = main_res["d2h_bytes"] / (main_res["d2h_ms"] * 1e-3) / 1e9 if main_res["d2h_ms"] > 0 else None
+    try:
+        chunk = chunk_probe(cfg)
+        log(f"[bench] chunk of {chunk['n_q']}: {chunk['per_layer_call_us']:.1f} us per layer call (single token {chunk['single_token_call_us']:.1f})")
+    except Exception as e:
+        chunk = {"error": f"{type(e).__name__}: {e}"[:300]}
+    release_memory()
     others, skipped = [], []
     for name in [w for w in args.others.split(",") if w and w != args.workload]:
         if time.perf_counter() - t_start > args.others_budget:
@@ -493,12 +544,12 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(kernel_GBps, 1) if kernel_GBps else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(kernel_GBps / HBM_PEAK_GBPS, 4) if kernel_GBps else None,
                      "traffic": measured_traffic(cfg.name),
-                     "kernel": "k_attn_tiered", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
+                     "kernel": "k_attn_tiered_mc" if cfg.kv_dtype != "f32" else "k_attn_tiered", "avg_us": round(main_res.get("kernel_avg_us", 0), 2),
                      "algorithmic_bytes_per_launch": int(main_res.get("kernel_bytes_per_launch", 0)),
                      "launches_timed": main_res.get("kernel_launches"),
                      "achievable": achievable,
                      "frac_of_achievable": round(kernel_GBps / achievable, 4) if kernel_GBps and achievable else None,
-                     "call": {"what": "one tkv_attend_and_score (k_attn_tiered + k_attn_finish) as the timed region ran it: every "
+                     "call": {"what": "one tkv_attend_and_score (attention launch + k_attn_finish) as the timed region ran it: every "
                                       "decode step bracketed by one pair of HIP events on the compute stream, divided by its layer calls",
                               "avg_us": round(main_res.get("call_avg_us", 0), 2),
                               "finish_kernel_avg_us": round(main_res.get("finish_avg_us", 0), 2),
@@ -506,6 +557,7 @@ def main():
                               "achieved": round(call_GBps, 1) if call_GBps else None,
                               "frac": round(call_GBps / HBM_PEAK_GBPS, 4) if call_GBps else None}},
         "cpu_baseline": cpu,
+        "chunk": chunk,
         "t1": {"events_in_timed_region": main_res["events"], "h2d_bytes": main_res["h2d_bytes"], "d2h_bytes": main_res["d2h_bytes"],
                "h2d_GBps": round(h2d_GBps, 1) if h2d_GBps else None, "d2h_GBps": round(d2h_GBps, 1) if d2h_GBps else None,
                "h2d_link_frac": round(h2d_GBps / LINK_PEAK_GBPS, 3) if h2d_GBps else None,
