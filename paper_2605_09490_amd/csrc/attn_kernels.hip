@@ -21,10 +21,16 @@
 //                 into the global (m, 1/l) of every query head.  Tile workgroups then turn the stored logits
 //                 into softmax weights, summed over all query heads in a fixed order, into score[b, pos]; the
 //                 Hq remaining workgroups merge the split outputs of one query head each into out[b, hq].
+//   attn_tiered_mc : the same launch for a chunk of query tokens (tkv_attend_and_score_chunk, 16-bit rows).  The
+//                 tokens ride as extra columns beside the G heads of the group (up to 32 columns per workgroup), so
+//                 a tile is fetched once for all of them: per tile a (64 rows x D) by (D x columns) product and its
+//                 transpose-side twin for the output, which is a dense contraction and runs on the matrix cores
+//                 (16x16x32 instructions; code rows widened to 16-bit values in LDS first).  attn_finish_chunk
+//                 adds the tokens' weights to the scores in token order.
 // The tile boundaries, the wave assignment and the fp32 summation order depend only on the lists' logical order and
 // lengths, never on whether a row lives in the HBM pool or the staging buffer (both are one slot space), which is
-// what makes T1 placement bit-invisible (Prop. 1).  No MFMA: the path is bound by HBM, and the per-row work is G
-// dot products.
+// what makes T1 placement bit-invisible (Prop. 1).  A decode step (one query token) uses no matrix instructions: the
+// launch is bound by HBM, and the per-row work is G dot products.
 #include <hip/hip_ext.h>
 
 #include <utility>
@@ -1846,11 +1852,15 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
 template <int D, int G, int KT>
 static hipError_t run_tiered(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   dim3 grid(a.S, a.Hkv, a.B * a.n_q);
-  if constexpr (KT == KT_F32) {
-    if (a.cq != 1) return hipErrorInvalidValue;
+  // One query token per workgroup (a decode step; binary32 rows always): the vector kernel, G dot products per row.
+  // Several query tokens as columns of one workgroup (16-bit rows): a (rows x D) by (D x G * cq) contraction, on the
+  // matrix cores.
+  if (a.cq == 1) {
     constexpr int threads = KernelGeo<D, G, KT>::NW * 64;
     if (ev0 && ev1) hipExtLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, ev0, ev1, 0, a);
     else hipLaunchKernelGGL((k_attn_tiered<D, G, KT>), grid, dim3(threads), 0, st, a);
+  } else if constexpr (KT == KT_F32) {
+    return hipErrorInvalidValue;
   } else {
     if (a.cq < 1 || a.cq * G > 32) return hipErrorInvalidValue;
     if (a.cq * G <= 16) {
@@ -1915,7 +1925,7 @@ hipError_t launch_attn_tiered(const AttnArgs& a, int D, int G, int kt, hipStream
   return hipErrorInvalidValue;
 }
 int attn_waves_per_group(int D, int elem_bytes, int G, int cq) {
-  return elem_bytes == 2 ? mc_waves(cq * G <= 16 ? 1 : 2) : waves_per_group(D * elem_bytes, G);
+  return (elem_bytes == 2 && cq > 1) ? mc_waves(cq * G <= 16 ? 1 : 2) : waves_per_group(D * elem_bytes, G);
 }
 int attn_cols_per_launch(int elem_bytes, int G) { return elem_bytes == 2 ? (32 / G < 16 ? 32 / G : 16) : 1; }
 int attn_q_waves(int n_waves, int n_f_tiles, int n_q_tiles) { return q_waves(n_waves, n_f_tiles, n_q_tiles); }

@@ -708,7 +708,7 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.S = S; a.S_total = S + S2; a.s0 = 0; a.second = 0; a.s_pos = c->streamed ? v.s_pos : nullptr; a.n_tiles = n_tiles; a.xs_stride = c->xs_stride; a.cb = v.cb; a.sb = v.sb; a.t2fmt = v.t2fmt; a.out_kind = c->cfg.out_dtype;
   a.softmax_scale = c->softmax_scale; a.score_scale = c->score_scale;
   a.q_bs = q_bs; a.o_bs = o_bs; a.trim = trim;
-  if (c->es == 2) { a.n_q = 1; a.cq = m; } else { a.n_q = m; a.cq = 1; }
+  if (c->es == 2) { a.n_q = 1; a.cq = m; } else { a.n_q = m; a.cq = 1; }   // 16-bit rows: the tokens as columns of one workgroup
   EvPair* pe = nullptr;
   EvPair* pe2 = nullptr;
   EvPair* pf = nullptr;

@@ -197,6 +197,37 @@ def test_prop1_t1_placement_is_bit_invisible(mode, kv_dtype, D, Hq, Hkv):
     assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
 
 
+@pytest.mark.parametrize("kv_dtype,D,Hq,Hkv,t2", [("bf16", 128, 10, 2, "int8_row"), ("f16", 64, 8, 2, "int4_g32")])
+def test_prop1_holds_for_chunks_of_query_tokens(kv_dtype, D, Hq, Hkv, t2):
+    """Zero-error offloading on the chunk path (several query tokens as columns of one launch): with rows in T1 the
+    outputs of every query token and the scores have the same bits as with those rows left in T0."""
+    from gpu_common import Pair
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, kv_dtype=kv_dtype,
+                       context=700, decode_steps=8, sigma=1.2, t2_format=t2)
+    rng = np.random.default_rng(13)
+    tiers = _random_tiers(rng, cfg.batch, cfg.context, frac=(0.3, 0.45, 0.2, 0.05))
+    twin = np.where(tiers == 1, 0, tiers).astype(np.uint8)
+    outs = []
+    for tt in (tiers, twin):
+        print(f"[case] prop1 chunk {kv_dtype} t1_rows={(tt == 1).sum()}", flush=True)
+        p = Pair(cfg, prefetch_mode="lazy")
+        p.gpu.set_tiers(tt)
+        p.gpu.migrate()
+        res, step = [], 0
+        for T in (5, 3):
+            for l in range(cfg.n_layers):
+                ks, vs = zip(*[p.wl.step_kv(step + j, l) for j in range(T)])
+                p.gpu.append(l, torch.cat(ks, dim=1), torch.cat(vs, dim=1))
+            for l in range(cfg.n_layers):
+                q = torch.stack([p.wl.step_q(step + j, l) for j in range(T)], dim=1).contiguous()
+                res.append(p.gpu.attend_and_score_chunk(l, q).cpu().reshape(-1))
+            step += T
+        outs.append((torch.cat(res), p.gpu.get_scores().copy()))
+        p.close()
+    assert torch.equal(outs[0][0].view(torch.uint8), outs[1][0].view(torch.uint8))
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
+
+
 @pytest.mark.parametrize("mode", ["wait", "lazy"])
 def test_rows_returning_to_t1_reuse_their_host_copy(mode):
     """A row that goes T1 -> T0 -> T1 is not transferred a second time (its bits in the pinned store are still
@@ -639,6 +670,13 @@ def test_whole_steps_and_classify(mode, scorer):
     ("wait", "f32", 64, 8, 2, "int8_row", "vatp", 2),
     ("lazy", "f16", 128, 7, 1, "int8_row", "attention", 3),
     ("lazy", "bf16", 64, 2, 1, "int8_row", "attention", 66),      # list lengths from the device counters
+    # the chunk launch on the matrix cores: int4 codes, both element types, groups of 1 .. 8 heads
+    ("lazy", "bf16", 128, 8, 1, "int4_g32", "attention", 2),      # G = 8: 4 tokens per launch
+    ("lazy", "f16", 64, 4, 1, "int4_g32", "vatp", 2),             # G = 4, 64-byte code rows: 8 tokens per launch
+    ("wait", "bf16", 64, 3, 3, "int8_row", "attention", 2),       # G = 1: the 9-token chunk in one launch
+    ("lazy", "bf16", 128, 12, 2, "int4_g32", "attention", 2),     # G = 6: 5 tokens per launch, 30 columns
+    ("lazy", "f16", 128, 10, 2, "int8_row", "attention", 2),      # G = 5, binary16
+    ("lazy", "bf16", 64, 6, 2, "int4_g32", "attention", 3),       # G = 3, 32-byte code rows
 ])
 def test_chunks_of_query_tokens(mode, kv_dtype, D, Hq, Hkv, t2, scorer, batch):
     """Several query tokens per sequence at once: chunks of 6, 1 and 9 tokens appended to every layer and attended
