@@ -153,6 +153,64 @@ def score_increment_vatp(alpha: np.ndarray, vnorm: np.ndarray, score_scale: floa
     return float(score_scale) * inc
 
 
+def key_redundancy(K: np.ndarray, k_before: np.ndarray = None) -> np.ndarray:
+    """Redundancy of every key row with respect to its neighbour (the "Redundancy" scorer of
+    Sec. "Ablation: Importance Scoring Methods": tokens with high cosine similarity to
+    neighbours are penalised; the paper gives no formula).  This build's reading:
+
+        rho_i = max(0, <k_i, k_{i-1}> / (||k_i|| ||k_{i-1}||)),
+
+    the cosine similarity of a position's key row with the key row of the position before it
+    (the neighbour that exists when the token is appended), of the same layer and kv head,
+    clamped below at 0; 0 for the first position and whenever either row is all zero.
+    Taken once, from the rows as appended; it stays with the position like the value norm.
+
+    K [..., n, d]; k_before [..., d] is the row in front of K[..., 0, :] (None: there is none).
+    Returns [..., n]."""
+    K = np.asarray(K, dtype=np.float64)
+    n = K.shape[-2]
+    rho = np.zeros(K.shape[:-1], dtype=np.float64)
+    for i in range(n):
+        if i == 0:
+            if k_before is None:
+                continue
+            prev = np.asarray(k_before, dtype=np.float64)
+        else:
+            prev = K[..., i - 1, :]
+        cur = K[..., i, :]
+        dot = (cur * prev).sum(axis=-1)
+        den = np.sqrt((cur * cur).sum(axis=-1)) * np.sqrt((prev * prev).sum(axis=-1))
+        cos = np.where(den > 0.0, dot / np.where(den > 0.0, den, 1.0), 0.0)
+        rho[..., i] = np.maximum(cos, 0.0)
+    return rho
+
+
+def score_increment_redundancy(alpha: np.ndarray, rho: np.ndarray, live: np.ndarray, score_scale: float,
+                               weight: float, vnorm: np.ndarray = None) -> np.ndarray:
+    """One layer's contribution under the redundancy-penalised scorers of the scoring ablation
+    ("Redundancy (attn - redundancy)" and, with vnorm, "Combined (attn x val - redundancy)").
+    This build's reading: per query head, the attention weight on a position (times the value
+    norm for the combined scorer) minus weight * rho / n_live, rho being the position's key
+    redundancy in the kv head that query head reads and n_live the number of positions the
+    query attends to; so a head's attention mass (1) and its penalty mass (at most `weight`)
+    are on the same scale at any cache length.  Evicted positions receive nothing.
+
+    alpha [B, Hq, n], rho [B, Hkv, n], live [B, n] bool, vnorm [B, Hkv, n] or None -> [B, n]:
+    score_scale * sum_h (alpha[b,h,i] * (vnorm[b,h//G,i] or 1) - weight * rho[b,h//G,i] / n_live[b])."""
+    alpha = np.asarray(alpha, dtype=np.float64)
+    rho = np.asarray(rho, dtype=np.float64)
+    B, Hq, n = alpha.shape
+    G = Hq // rho.shape[1]
+    inc = np.zeros((B, n), dtype=np.float64)
+    for b in range(B):
+        n_live = int(np.sum(live[b]))
+        for h in range(Hq):
+            gain = alpha[b, h] * (vnorm[b, h // G] if vnorm is not None else 1.0)
+            pen = float(weight) * rho[b, h // G] / max(n_live, 1)
+            inc[b] += np.where(live[b], gain - pen, 0.0)
+    return float(score_scale) * inc
+
+
 def eviction_error_bound(alpha_full: np.ndarray, V: np.ndarray, evicted: np.ndarray) -> float:
     """Right-hand side of Eq. 4: 2 * sum_{i in E} alpha_i ||v_i||."""
     V = np.asarray(V, dtype=np.float64)
@@ -305,13 +363,22 @@ def tier_counts_alg1(m: int, policy_ppm, n_already_evicted: int = 0):
     return n_hbm, survivors - n_hbm - n_cmp, n_cmp, n_already_evicted + n_evict
 
 
+def score_order(bits: int) -> int:
+    """Unsigned 32-bit integer that orders binary32 bit patterns like the values they encode
+    (-0 directly below +0; NaNs are not scores)."""
+    return (~bits & 0xFFFFFFFF) if (bits & 0x80000000) else (bits | 0x80000000)
+
+
 def classify_sequence(score_f32: np.ndarray, tier_prev: np.ndarray, n: int,
                       n_prompt: int, k_sink: int, k_window: int, policy_ppm, count_rule: int = 0) -> np.ndarray:
     """New tier of each of the n positions of one sequence.
 
-    Candidates are ranked ascending by the key (live, score_bits, position):
-    live = 0 for an already evicted position, score_bits = the binary32 pattern
-    of its (non-negative) score as an unsigned integer.  Lowest n3 -> T3, next
+    Candidates are ranked ascending by the key (live, score_order, position):
+    live = 0 for an already evicted position; score_order puts binary32 scores in
+    the order of their values (total order on the bit patterns: for a score with
+    the sign bit clear the pattern with that bit set, else the complemented
+    pattern; for the non-negative scores of Eq. 1 this is the order of the
+    patterns themselves).  Penalised scorers can go below zero.  Lowest n3 -> T3, next
     n2 -> T2, next n1 -> T1, top n0 -> T0; protected positions -> T0.
     The sort is written out with Python's sorted() on explicit tuples.
     """
@@ -324,7 +391,7 @@ def classify_sequence(score_f32: np.ndarray, tier_prev: np.ndarray, n: int,
         return tier_new
     evicted = int(np.sum(tier_prev[lo:hi] == T3))
     n0, n1, n2, n3 = (tier_counts_alg1 if count_rule == 1 else tier_counts)(m, policy_ppm, evicted)
-    keys = [((0 if tier_prev[i] == T3 else 1), int(bits[i]), i) for i in range(lo, hi)]
+    keys = [((0 if tier_prev[i] == T3 else 1), score_order(int(bits[i])), i) for i in range(lo, hi)]
     order = [k[2] for k in sorted(keys)]
     for rank, i in enumerate(order):
         if rank < n3:
@@ -358,7 +425,7 @@ class OracleCache:
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens,
                  kv_dtype="bf16", t2_format="int8_row", n_prompt=0, k_sink=4, k_window=128,
-                 score_scale=None, softmax_scale=None, layers=None, scorer="attention"):
+                 score_scale=None, softmax_scale=None, layers=None, scorer="attention", redundancy_weight=1.0):
         self.L, self.B, self.Hq, self.Hkv, self.d = n_layers, batch, n_q_heads, n_kv_heads, head_dim
         self.G = n_q_heads // n_kv_heads
         assert self.G * n_kv_heads == n_q_heads
@@ -377,10 +444,16 @@ class OracleCache:
         self.tier = np.zeros((batch, max_tokens), dtype=np.uint8)
         self.tier_pending = None
         self.score = np.zeros((batch, max_tokens), dtype=np.float64)
-        # "attention": Eq. 1.  "vatp": the value-aware variant of the scoring ablation.
-        assert scorer in ("attention", "vatp")
+        # "attention": Eq. 1.  The others are the variants of the scoring ablation: "vatp" (attention x value
+        # norm), "redundancy" (attention - redundancy), "combined" (attention x value norm - redundancy).
+        assert scorer in ("attention", "vatp", "redundancy", "combined")
         self.scorer = scorer
-        self.vnorm = {l: np.zeros(shape[:3], dtype=np.float64) for l in self.layers} if scorer == "vatp" else None
+        self.redundancy_weight = float(redundancy_weight)
+        self.vnorm = {l: np.zeros(shape[:3], dtype=np.float64) for l in self.layers} if scorer in ("vatp", "combined") else None
+        self.last_k = {}
+        self.rho = {l: np.zeros(shape[:3], dtype=np.float64) for l in self.layers} if scorer in ("redundancy", "combined") else None
+        # sum of the magnitudes of what was added and what was taken off (the scale of a penalised score's rounding)
+        self.score_mag = np.zeros((batch, max_tokens), dtype=np.float64)
 
     # -- Algorithm 1: the cache grows by the generated token --------------------
     def append(self, layer, k, v):
@@ -391,6 +464,11 @@ class OracleCache:
         n_new = k.shape[1]
         if n0 + n_new > self.max_tokens:
             raise OverflowError("append beyond max_tokens")
+        if self.rho is not None:
+            # against the row appended just before, as it was appended (it may have been compressed or evicted since)
+            before = self.last_k[layer] if n0 > 0 else None
+            self.rho[layer][:, :, n0:n0 + n_new] = key_redundancy(k.transpose(0, 2, 1, 3), before)
+            self.last_k[layer] = k[:, -1].copy()
         self.K[layer][:, :, n0:n0 + n_new] = k.transpose(0, 2, 1, 3)
         self.V[layer][:, :, n0:n0 + n_new] = v.transpose(0, 2, 1, 3)
         if self.vnorm is not None:
@@ -403,11 +481,25 @@ class OracleCache:
         n = self.length[layer]
         live = self.tier[:, :n] != T3
         out, alpha = attend_gqa(q, self.K[layer][:, :, :n], self.V[layer][:, :, :n], live, self.softmax_scale)
-        if self.scorer == "vatp":
-            self.score[:, :n] += score_increment_vatp(alpha, self.vnorm[layer][:, :, :n], self.score_scale)
-        else:
-            self.score[:, :n] += score_increment(alpha, self.score_scale)
+        self._add_scores(layer, alpha, live, n)
         return out
+
+    def _add_scores(self, layer, alpha, live, n):
+        """The layer call's contribution to the first n positions' scores, by the configured scorer."""
+        if self.scorer == "vatp":
+            inc = score_increment_vatp(alpha, self.vnorm[layer][:, :, :n], self.score_scale)
+            mag = inc
+        elif self.scorer in ("redundancy", "combined"):
+            vn = self.vnorm[layer][:, :, :n] if self.scorer == "combined" else None
+            inc = score_increment_redundancy(alpha, self.rho[layer][:, :, :n], live, self.score_scale,
+                                             self.redundancy_weight, vn)
+            gain = score_increment_redundancy(alpha, self.rho[layer][:, :, :n], live, self.score_scale, 0.0, vn)
+            mag = gain + (gain - inc)
+        else:
+            inc = score_increment(alpha, self.score_scale)
+            mag = inc
+        self.score[:, :n] += inc
+        self.score_mag[:, :n] += mag
 
     def attend_and_score_chunk(self, layer, q):
         """Several query tokens at once: q [B, T, Hq, d] belongs to the last T appended positions,
@@ -425,10 +517,7 @@ class OracleCache:
             m = n - T + j + 1
             live = self.tier[:, :m] != T3
             o, alpha = attend_gqa(q[:, j], self.K[layer][:, :, :m], self.V[layer][:, :, :m], live, self.softmax_scale)
-            if self.scorer == "vatp":
-                self.score[:, :m] += score_increment_vatp(alpha, self.vnorm[layer][:, :, :m], self.score_scale)
-            else:
-                self.score[:, :m] += score_increment(alpha, self.score_scale)
+            self._add_scores(layer, alpha, live, m)
             out[:, j] = o
         return out
 

@@ -552,6 +552,125 @@ def test_vatp_norm_is_the_appended_rows_and_survives_compression():
     assert np.allclose(before[0, 0, :6], np.linalg.norm(v[0, :, 0].astype(np.float64), axis=-1), rtol=1e-15)
 
 
+# ---------------------------------------------------------------- redundancy-penalised scorers (scoring ablation)
+def test_key_redundancy_by_hand():
+    # rows: e1, 2*e1 (cosine 1 with its neighbour), e2 (cosine 0), -e2 (cosine -1 -> clamped to 0),
+    # (3, 4) after (0, -1): cosine -0.8 -> 0; (4, 3) after (3, 4): 24/25; a zero row and the row after it: 0
+    K = np.array([[1, 0], [2, 0], [0, 1], [0, -1], [3, 4], [4, 3], [0, 0], [1, 1]], np.float64)
+    rho = O.key_redundancy(K)
+    assert np.allclose(rho, [0, 1, 0, 0, 0, 24 / 25, 0, 0], atol=1e-15)
+    # with the row in front of the first one given: cosine of (1, 0) and (1, 1) is 1/sqrt(2)
+    rho2 = O.key_redundancy(K, k_before=np.array([1.0, 1.0]))
+    assert np.isclose(rho2[0], 1 / math.sqrt(2), rtol=1e-15) and np.allclose(rho2[1:], rho[1:])
+
+
+def test_key_redundancy_matches_brute_force_and_ignores_row_scale():
+    r = np.random.default_rng(17)
+    K = r.normal(size=(2, 3, 11, 6))
+    rho = O.key_redundancy(K)
+    for b in range(2):
+        for h in range(3):
+            for i in range(11):
+                if i == 0:
+                    want = 0.0
+                else:
+                    dot = sum(K[b, h, i, e] * K[b, h, i - 1, e] for e in range(6))
+                    na = math.sqrt(sum(K[b, h, i, e] ** 2 for e in range(6))); nb = math.sqrt(sum(K[b, h, i - 1, e] ** 2 for e in range(6)))
+                    want = max(0.0, dot / (na * nb))
+                assert abs(rho[b, h, i] - want) < 1e-14
+    K2 = K * r.uniform(0.1, 9.0, size=K.shape[:-1] + (1,))          # positive factor per row: cosines unchanged
+    assert np.allclose(O.key_redundancy(K2), rho, rtol=1e-12, atol=1e-15)
+    assert rho.min() >= 0.0 and rho.max() <= 1.0 + 1e-15
+
+
+def test_redundancy_scorer_hand_worked_case():
+    # one head, three positions with equal logits (weights 1/3 each); redundancies 0, 1, 0.5; weight 0.6:
+    # increment_i = 1/3 - 0.6 * rho_i / 3  ->  1/3, 2/15, 7/30
+    alpha = np.full((1, 1, 3), 1 / 3)
+    rho = np.array([[[0.0, 1.0, 0.5]]])
+    live = np.ones((1, 3), bool)
+    inc = O.score_increment_redundancy(alpha, rho, live, 1.0, 0.6)
+    assert np.allclose(inc[0], [1 / 3, 2 / 15, 7 / 30], atol=1e-15)
+    # the combined scorer with value norms 3, 1, 2: 1 - 0, 1/3 - 0.2, 2/3 - 0.1
+    inc = O.score_increment_redundancy(alpha, rho, live, 1.0, 0.6, vnorm=np.array([[[3.0, 1.0, 2.0]]]))
+    assert np.allclose(inc[0], [1.0, 1 / 3 - 0.2, 2 / 3 - 0.1], atol=1e-15)
+    # an evicted position receives nothing, and the others' penalty is spread over the two that are left
+    live = np.array([[True, False, True]])
+    alpha = np.array([[[0.5, 0.0, 0.5]]])
+    inc = O.score_increment_redundancy(alpha, rho, live, 2.0, 0.6)
+    assert np.allclose(inc[0], [2 * 0.5, 0.0, 2 * (0.5 - 0.6 * 0.5 / 2)], atol=1e-15)
+
+
+def test_redundancy_scorer_reduces_to_the_plain_ones_and_has_the_closed_form_mass():
+    r = np.random.default_rng(23)
+    B, Hq, Hkv, n = 2, 6, 2, 13
+    x = r.normal(size=(B, Hq, n))
+    live = r.random((B, n)) < 0.8
+    live[:, 0] = True
+    a = np.where(live[:, None, :], np.exp(x), 0.0)
+    alpha = a / a.sum(-1, keepdims=True)
+    rho = r.random((B, Hkv, n)); vn = r.random((B, Hkv, n)) + 0.5
+    # weight 0: Eq. 1, and the value-aware scorer
+    assert np.allclose(O.score_increment_redundancy(alpha, rho, live, 0.25, 0.0), O.score_increment(alpha, 0.25), rtol=1e-14, atol=0)
+    assert np.allclose(O.score_increment_redundancy(alpha, rho, live, 0.25, 0.0, vnorm=vn), O.score_increment_vatp(alpha, vn, 0.25), rtol=1e-14, atol=0)
+    # total added per sequence: score_scale * (Hq - weight * G * sum over kv heads of the mean redundancy of the live positions)
+    G = Hq // Hkv
+    inc = O.score_increment_redundancy(alpha, rho, live, 0.25, 0.7)
+    for b in range(B):
+        mean_rho = sum(rho[b, h][live[b]].mean() for h in range(Hkv))
+        assert np.isclose(inc[b].sum(), 0.25 * (Hq - 0.7 * G * mean_rho), rtol=1e-13)
+    assert np.all(inc[~live] == 0.0)
+
+
+def test_redundancy_cache_appending_in_pieces_is_appending_at_once():
+    # the neighbour of a piece's first row is the last row appended before it, as appended -- even if that
+    # position has been compressed or evicted in the meantime
+    r = np.random.default_rng(29)
+    k = O.round_to_bf16(r.normal(size=(2, 10, 2, 8)).astype(np.float32)); v = O.round_to_bf16(r.normal(size=(2, 10, 2, 8)).astype(np.float32))
+    c1 = O.OracleCache(1, 2, 4, 2, 8, max_tokens=16, kv_dtype="bf16", scorer="redundancy", k_sink=0, k_window=0)
+    c1.append(0, k, v)
+    c2 = O.OracleCache(1, 2, 4, 2, 8, max_tokens=16, kv_dtype="bf16", scorer="combined", k_sink=0, k_window=0)
+    c2.append(0, k[:, :4], v[:, :4])
+    tiers = np.zeros((2, 4), np.uint8); tiers[0, 3] = O.T3; tiers[1, 3] = O.T2
+    c2.set_tiers(tiers); c2.migrate()
+    c2.append(0, k[:, 4:9], v[:, 4:9]); c2.append(0, k[:, 9:], v[:, 9:])
+    assert np.array_equal(c1.rho[0], c2.rho[0])
+    assert np.allclose(c1.rho[0][:, :, :10], O.key_redundancy(k.transpose(0, 2, 1, 3).astype(np.float64)), rtol=0, atol=0)
+
+
+def test_score_order_is_the_order_of_the_values():
+    r = np.random.default_rng(31)
+    vals = np.concatenate([r.normal(size=300) * 10.0 ** r.integers(-30, 5, size=300), [0.0, -0.0, 1e-45, -1e-45, 3.0e38, -3.0e38]]).astype(np.float32)
+    bits = vals.view(np.uint32)
+    keys = [O.score_order(int(u)) for u in bits]
+    order = sorted(range(len(vals)), key=lambda i: keys[i])
+    sorted_vals = vals[order].astype(np.float64)
+    assert np.all(np.diff(sorted_vals) >= 0.0)
+    assert O.score_order(0x80000000) + 1 == O.score_order(0x00000000)          # -0 directly below +0
+    # non-negative scores (Eq. 1) rank exactly as their bit patterns do
+    nn = np.abs(vals).view(np.uint32)
+    assert sorted(range(len(nn)), key=lambda i: (O.score_order(int(nn[i])), i)) == sorted(range(len(nn)), key=lambda i: (int(nn[i]), i))
+
+
+def test_classify_with_scores_below_zero_matches_a_plain_sort():
+    r = np.random.default_rng(37)
+    n = 60
+    score = (r.normal(size=n) * 0.1).astype(np.float32)
+    score[10] = score[20]                                             # a tie: the lower position ranks lower
+    tier_prev = np.zeros(n, np.uint8); tier_prev[[5, 6]] = O.T3
+    ppm = (300_000, 400_000, 200_000, 100_000)
+    got = O.classify_sequence(score, tier_prev, n, 0, 2, 8, ppm)
+    lo, hi = 2, n - 8
+    m = hi - lo
+    n0, n1, n2, n3 = O.tier_counts(m, ppm, 2)
+    cand = sorted(range(lo, hi), key=lambda i: (tier_prev[i] != O.T3, float(score[i]), i))
+    want = np.zeros(n, np.uint8)
+    for rank, i in enumerate(cand):
+        want[i] = O.T3 if rank < n3 else O.T2 if rank < n3 + n2 else O.T1 if rank < n3 + n2 + n1 else O.T0
+    assert np.array_equal(got, want)
+    assert (got[[5, 6]] == O.T3).all()
+
+
 # ---------------------------------------------------------------- multi-token queries (causal chunk)
 def test_chunk_of_one_is_the_single_token_call():
     c1, data = _mk_cache()
