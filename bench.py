@@ -414,8 +414,9 @@ def main():
     ap.add_argument("--delta", type=int, default=0, help="re-tier every DELTA steps (default: the workload's own)")
     ap.add_argument("--k-window", type=int, default=-1, help="protected recent window (default: the workload's own)")
     ap.add_argument("--bounce-mib", type=int, default=0, help="size of each T1 bounce ring in MiB (default: the library's own)")
-    ap.add_argument("--scorer", default="attention", choices=["attention", "vatp"],
-                    help="cumulative attention (Eq. 1, the paper's method) or the value-aware variant of its scoring ablation")
+    ap.add_argument("--scorer", default="attention", choices=["attention", "vatp", "redundancy", "combined"],
+                    help="cumulative attention (Eq. 1, the paper's method) or a variant of its scoring ablation: value-aware, "
+                         "redundancy-penalised, or both")
     ap.add_argument("--count-rule", default="total", choices=["total", "alg1"],
                     help="band sizes as fixed fractions of all candidates, or Algorithm 1's floors (evicts again at every event)")
     args = ap.parse_args()
@@ -536,7 +537,7 @@ def main():
                                f"T2 {cfg.t2_format}, re-tier every {cfg.reclassify_every} steps, prefetch {args.mode}"
                                + (f", k_window {cfg.k_window}" if args.k_window >= 0 else "")
                                + (", Algorithm-1 count rule" if rule else "")
-                               + (", value-aware scorer" if SCORER != "attention" else ""),
+                               + (f", {SCORER} scorer" if SCORER != "attention" else ""),
                    "untimed_pre_roll_steps": (1 + SETTLE_EVENTS) * delta + warmup,
                    "score_driven_events_before_timing": SETTLE_EVENTS},
         "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),

@@ -83,8 +83,16 @@ typedef enum { TKV_PREFETCH_WAIT = 0, TKV_PREFETCH_LAZY = 1, TKV_PREFETCH_STREAM
  *  VATP: the value-aware variant of the paper's scoring ablation (Sec. "Ablation: Importance Scoring Methods"): each
  *        head's weight is multiplied by the Euclidean norm of the value row that head reads at the position.  The norm
  *        is taken once, from the row as appended (binary32, fixed summation order); it does not follow the row
- *        through later compression.  Costs 4 bytes per (layer, sequence, kv head, position) of device memory. */
-typedef enum { TKV_SCORE_ATTENTION = 0, TKV_SCORE_VATP = 1 } tkv_scorer;
+ *        through later compression.  Costs 4 bytes per (layer, sequence, kv head, position) of device memory.
+ *  REDUNDANCY: "attn - redundancy" of the same ablation.  The paper gives no formula for the redundancy term; this
+ *        library's reading: rho of a position in a (layer, kv head) is the cosine similarity of its key row with the key
+ *        row appended just before it, clamped below at 0 (0 for the first position or an all-zero row), taken once from
+ *        the rows as appended.  Per query head a layer call adds the attention weight minus
+ *        redundancy_weight * rho / (positions the query attends to); evicted positions receive nothing.  Scores can go
+ *        below zero; tkv_classify ranks binary32 scores by value.  Costs 4 bytes per (layer, sequence, kv head,
+ *        position) plus one key row per (layer, sequence, kv head).
+ *  COMBINED: "attn x val - redundancy": the VATP term minus the same penalty (both arrays). */
+typedef enum { TKV_SCORE_ATTENTION = 0, TKV_SCORE_VATP = 1, TKV_SCORE_REDUNDANCY = 2, TKV_SCORE_COMBINED = 3 } tkv_scorer;
 
 typedef struct {
   int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64, 128}; n_q_heads % n_kv_heads == 0,
@@ -114,6 +122,7 @@ typedef struct {
                                           tkv_decode_step with one pair of HIP events (tkv_get_stats) */
   int32_t scorer;                      /* tkv_scorer */
   int32_t device;                      /* HIP device ordinal */
+  float redundancy_weight;             /* weight of the redundancy penalty (REDUNDANCY, COMBINED); 0 -> 1 */
   void* (*dev_alloc)(size_t bytes, void* ctx); /* device memory, 256-byte aligned; NULL -> hipMalloc */
   void (*dev_free)(void* p, void* ctx);
   void* (*pin_alloc)(size_t bytes, void* ctx); /* pinned host memory; NULL -> hipHostMalloc */

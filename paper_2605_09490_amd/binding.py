@@ -18,7 +18,7 @@ TKV_OK, TKV_EINVAL, TKV_ENOMEM, TKV_ECAPACITY, TKV_ESTATE, TKV_EDEVICE = 0, -1, 
 TKV_F32, TKV_BF16, TKV_F16 = 0, 1, 2
 TKV_T2_INT8_ROW, TKV_T2_INT4_G32 = 0, 1
 TKV_PREFETCH_WAIT, TKV_PREFETCH_LAZY, TKV_PREFETCH_STREAM = 0, 1, 2
-TKV_SCORE_ATTENTION, TKV_SCORE_VATP = 0, 1
+TKV_SCORE_ATTENTION, TKV_SCORE_VATP, TKV_SCORE_REDUNDANCY, TKV_SCORE_COMBINED = 0, 1, 2, 3
 TKV_COUNT_TOTAL, TKV_COUNT_ALG1 = 0, 1
 STATUS_NAMES = {0: "TKV_OK", -1: "TKV_EINVAL", -2: "TKV_ENOMEM", -3: "TKV_ECAPACITY", -4: "TKV_ESTATE", -5: "TKV_EDEVICE"}
 
@@ -36,6 +36,7 @@ class tkv_config(C.Structure):
         ("t0_rows", C.c_int32), ("staging_rows", C.c_int32), ("t2_rows", C.c_int32),
         ("host_rows", C.c_int64), ("bounce_bytes", C.c_int64),
         ("prefetch_mode", C.c_int32), ("profile", C.c_int32), ("scorer", C.c_int32), ("device", C.c_int32),
+        ("redundancy_weight", C.c_float),
         ("dev_alloc", ALLOC_FN), ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN),
         ("alloc_ctx", C.c_void_p),
     ]
@@ -138,7 +139,7 @@ class TieredKV:
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, kv_dtype="bf16",
                  t2_format="int8_row", out_dtype="f32", n_prompt=0, k_sink=4, k_window=128, score_scale=0.0, softmax_scale=0.0,
                  t0_rows=0, staging_rows=0, t2_rows=0, host_rows=0, bounce_bytes=0, prefetch_mode="wait",
-                 profile=False, device=0, use_torch_allocator=True, scorer="attention"):
+                 profile=False, device=0, use_torch_allocator=True, scorer="attention", redundancy_weight=0.0):
         self.lib = load_library()
         self.device = torch.device("cuda", device)
         self.shape = (n_layers, batch, n_q_heads, n_kv_heads, head_dim)
@@ -162,7 +163,9 @@ class TieredKV:
         cfg.host_rows, cfg.bounce_bytes = host_rows, bounce_bytes
         cfg.prefetch_mode = {"wait": TKV_PREFETCH_WAIT, "lazy": TKV_PREFETCH_LAZY, "stream": TKV_PREFETCH_STREAM}[prefetch_mode]
         cfg.profile = 1 if profile else 0
-        cfg.scorer = {"attention": TKV_SCORE_ATTENTION, "vatp": TKV_SCORE_VATP}[scorer]
+        cfg.scorer = {"attention": TKV_SCORE_ATTENTION, "vatp": TKV_SCORE_VATP, "redundancy": TKV_SCORE_REDUNDANCY,
+                      "combined": TKV_SCORE_COMBINED}[scorer]
+        cfg.redundancy_weight = float(redundancy_weight)
         cfg.device = device
         if use_torch_allocator:
             # PyTorch supplies device and pinned memory; the library only sees raw pointers

@@ -1679,6 +1679,7 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
   if (is_tile) {
     // 64 list entries per workgroup; thread (e, hg) sums the softmax weights of kv heads hg, hg+4, ... (all G members
     // of each), then the four partial sums of an entry are added in the fixed order hg = 0, 1, 2, 3
+    const float pen = a.red ? a.red_w * (float)G / (float)(nF + nQ + nS) : 0.f;
     float acc = 0.f;
     if (pos >= 0) {
       for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
@@ -1695,6 +1696,8 @@ __global__ __launch_bounds__(256) void k_attn_finish(const AttnArgs a, int n_til
 #pragma unroll
           for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[kvh * G + g]) * LOG2E) * IL[kvh * G + g];
         }
+        // redundancy-penalised scorers: the G heads of the group each take red_w * rho / (positions attended) off
+        if (a.red) acc = fmaf(-pen, a.red[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
       }
     }
     __syncthreads();          // sm_pm is free now: reuse it for the partial sums
@@ -1776,6 +1779,7 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
       const int nFj = nF - (nq - 1 - jt);                                   // what the query sees of list F
       const int cfz = (nF - (a.n_q - 1 - jt / a.cq) * a.cq + TB - 1) / TB;  // F tiles in its group's layout
       const bool seen = is_q || (is_f && sl < nFj);         // wave-divergent at most in a list's last tile
+      const float pen = a.red ? a.red_w * (float)G / (float)(nFj + nQ) : 0.f;
       const int col = is_q ? cfz * TB + (sl - cf * TB) : sl;
       float acc = 0.f;
       if (seen) {
@@ -1792,6 +1796,7 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
 #pragma unroll
             for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
           }
+          if (a.red) acc = fmaf(-pen, a.red[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
         }
       }
       __syncthreads();

@@ -93,12 +93,14 @@ __global__ void k_append_step(DevView v, const char* __restrict__ k, const char*
   *(u32x4*)(v.fpV + dst) = *(const u32x4*)(vv + (size_t)i * 16);
 }
 static void launch_vnorm(const DevView& v, const void* rows, long long n_rows, int n_new, int lb0, int pos0, hipStream_t st);
+static void launch_redundancy(const DevView& v, const void* rows, long long n_rows, int n_new, int lb0, int pos0, hipStream_t st);
 
 hipError_t launch_append_step(const DevView& v, const void* k, const void* v_, int pos, hipStream_t st) {
   hipLaunchKernelGGL(k_append_assign, dim3(v.B), dim3(256), 0, st, v, pos, 1);
   const long long total = (long long)v.L * v.B * v.Hkv * (v.D * v.es / 16);
   hipLaunchKernelGGL(k_append_step, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, (const char*)k, (const char*)v_, pos);
   if (v.vnorm) launch_vnorm(v, v_, (long long)v.L * v.B * v.Hkv, 1, 0, pos, st);
+  if (v.red) launch_redundancy(v, k, (long long)v.L * v.B * v.Hkv, 1, 0, pos, st);
   return hipGetLastError();
 }
 
@@ -109,16 +111,22 @@ hipError_t launch_append(const DevView& v, int layer, const void* k, const void*
   const int blocks = (int)((total + 255) / 256);
   hipLaunchKernelGGL(k_append_rows, dim3(blocks), dim3(256), 0, st, v, layer, (const char*)k, (const char*)v_, pos0, n_new);
   if (v.vnorm) launch_vnorm(v, v_, (long long)v.B * n_new * v.Hkv, n_new, layer * v.B, pos0, st);
+  if (v.red) launch_redundancy(v, k, (long long)v.B * n_new * v.Hkv, n_new, layer * v.B, pos0, st);
   return hipGetLastError();
 }
 
 // ---- classify: radix select of the band boundaries ------------------------------------------------------
-// key = already-evicted-first | score bits | position : 1 + 31 + 24 bits, all distinct.
+// key = already-evicted-first | score in value order | position : 1 + 32 + 24 bits, all distinct.  A binary32
+// pattern with the sign bit clear gets it set, one with the sign bit set is complemented: unsigned order of the
+// results is the order of the values (the penalised scorers go below zero; for non-negative scores it is the order
+// of the patterns themselves).
 __device__ __forceinline__ uint64_t rank_key(uint8_t tier_prev, float score, int pos) {
   const uint64_t live = tier_prev == 3 ? 0ull : 1ull;
-  const uint64_t bits = __builtin_bit_cast(uint32_t, score) & 0x7fffffffu;
-  return (live << 55) | (bits << 24) | (uint64_t)pos;
+  const uint32_t u = __builtin_bit_cast(uint32_t, score);
+  const uint64_t ord = (u & 0x80000000u) ? (uint32_t)~u : (u | 0x80000000u);
+  return (live << 56) | (ord << 24) | (uint64_t)pos;
 }
+constexpr int RANK_KEY_TOP_SHIFT = 56;   // the radix select walks the key in 8-bit digits from here down (the top one has 1 bit)
 
 __device__ void band_counts(const Ppm& p, long long m, long long evicted, long long out[4]) {
   if (p.rule == 1) {
@@ -174,13 +182,13 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_classify(DevView v, int n, Ppm
     if (k <= 0) { if (t == 0) sh_thr[q] = 0ull; continue; }
     if (k >= m) { if (t == 0) sh_thr[q] = ~0ull; continue; }
     if (t == 0) { sh_prefix = 0ull; sh_k = (int)k; }
-    for (int shift = 48; shift >= 0; shift -= 8) {
+    for (int shift = RANK_KEY_TOP_SHIFT; shift >= 0; shift -= 8) {
       if (t < 256) hist[t] = 0;
       __syncthreads();
       const unsigned long long prefix = sh_prefix;
       for (int i = lo + t; i < hi; i += PLAN_THREADS) {
         const uint64_t key = rank_key(tier[i], score[i], i);
-        if (shift == 48 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(key >> shift) & 255], 1);
+        if (shift == RANK_KEY_TOP_SHIFT || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(key >> shift) & 255], 1);
       }
       __syncthreads();
       if (t < 64) {
@@ -536,6 +544,59 @@ __global__ void k_vnorm(DevView v, const char* __restrict__ rows, long long n_ro
 static void launch_vnorm(const DevView& v, const void* rows, long long n_rows, int n_new, int lb0, int pos0, hipStream_t st) {
   const long long total = n_rows * (v.D / 8);
   hipLaunchKernelGGL(k_vnorm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, (const char*)rows, n_rows, n_new, lb0, pos0);
+}
+
+// Redundancy-penalised scorers: the clamped cosine of every appended key row with the key row appended before it
+// (the previous new row, or for the first new row the row kept from the last append; 0 for position 0 and for
+// all-zero rows).  rows: dense [n_rows][D] as for k_vnorm; D / 8 lanes per row: each accumulates the dot product and the
+// two squared norms over its 8 elements in order, then the lanes' sums are added pairwise (1, 2, 4, 8 apart).
+__global__ void k_redundancy(DevView v, const char* __restrict__ rows, long long n_rows, int n_new, int lb0, int pos0) {
+  const int lpr = v.D / 8;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long r = i / lpr;
+  const int c = (int)(i % lpr);
+  float dot = 0.f, na = 0.f, nb = 0.f;
+  bool has_prev = false;
+  if (r < n_rows) {
+    const int kvh = (int)(r % v.Hkv), j = (int)((r / v.Hkv) % n_new);
+    const long long lb = lb0 + r / ((long long)n_new * v.Hkv);
+    float x[8], y[8];
+    load8(rows + (size_t)r * v.D * v.es, c * 8, v.kt, x);
+    has_prev = j > 0 || pos0 > 0;
+    if (j > 0) load8(rows + (size_t)(r - v.Hkv) * v.D * v.es, c * 8, v.kt, y);
+    else if (pos0 > 0) load8(v.last_k + ((size_t)lb * v.Hkv + kvh) * v.D * v.es, c * 8, v.kt, y);
+    if (has_prev) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { dot = fmaf(x[e], y[e], dot); na = fmaf(x[e], x[e], na); nb = fmaf(y[e], y[e], nb); }
+    }
+  }
+  for (int o = 1; o < lpr; o <<= 1) { dot += __shfl_xor(dot, o); na += __shfl_xor(na, o); nb += __shfl_xor(nb, o); }
+  if (r < n_rows && c == 0) {
+    const int kvh = (int)(r % v.Hkv), j = (int)((r / v.Hkv) % n_new);
+    const long long lb = lb0 + r / ((long long)n_new * v.Hkv);
+    const float den = sqrtf(na) * sqrtf(nb);
+    const float rho = (has_prev && den > 0.f) ? fmaxf(dot / den, 0.f) : 0.f;
+    if (pos0 + j < v.Nmax) v.red[((size_t)lb * v.Hkv + kvh) * v.Nmax + pos0 + j] = rho;
+  }
+}
+// ... and the last new row of every (layer, sequence, kv head) kept for the next append (a launch of its own: the
+// kernel above still reads the previous one)
+__global__ void k_keep_last_key(DevView v, const char* __restrict__ rows, long long n_groups, int n_new, int lb0) {
+  const int cpr = v.D * v.es / 16;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_groups * cpr) return;
+  const long long gidx = i / cpr;                     // (lb - lb0, kvh)
+  const int c = (int)(i % cpr), kvh = (int)(gidx % v.Hkv);
+  const long long lbr = gidx / v.Hkv;
+  const long long r = (lbr * n_new + (n_new - 1)) * v.Hkv + kvh;
+  *(u32x4*)(v.last_k + (((size_t)(lb0 + lbr)) * v.Hkv + kvh) * v.D * v.es + (size_t)c * 16) =
+      *(const u32x4*)(rows + (size_t)r * v.D * v.es + (size_t)c * 16);
+}
+static void launch_redundancy(const DevView& v, const void* rows, long long n_rows, int n_new, int lb0, int pos0, hipStream_t st) {
+  const long long total = n_rows * (v.D / 8);
+  hipLaunchKernelGGL(k_redundancy, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, v, (const char*)rows, n_rows, n_new, lb0, pos0);
+  const long long groups = n_rows / n_new, t2 = groups * (v.D * v.es / 16);
+  hipLaunchKernelGGL(k_keep_last_key, dim3((unsigned)((t2 + 255) / 256)), dim3(256), 0, st, v, (const char*)rows, groups, n_new, lb0);
 }
 
 // -> T2: encode the current stored row.  D/8 lanes per row (8 elements each), 64/(D/8) rows per wave.

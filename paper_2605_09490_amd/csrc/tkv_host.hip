@@ -427,7 +427,8 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   if (cfg->t0_rows < 0 || cfg->staging_rows < 0 || cfg->t2_rows < 0 || cfg->host_rows < 0 || cfg->bounce_bytes < 0)
     return bad("tkv_create: capacities must be >= 0");
   if (cfg->prefetch_mode < TKV_PREFETCH_WAIT || cfg->prefetch_mode > TKV_PREFETCH_STREAM) return bad("tkv_create: prefetch_mode");
-  if (cfg->scorer != TKV_SCORE_ATTENTION && cfg->scorer != TKV_SCORE_VATP) return bad("tkv_create: scorer");
+  if (cfg->scorer < TKV_SCORE_ATTENTION || cfg->scorer > TKV_SCORE_COMBINED) return bad("tkv_create: scorer");
+  if (!(cfg->redundancy_weight >= 0.f)) return bad("tkv_create: redundancy_weight must be >= 0");
   if (!(cfg->score_scale >= 0.f) || !(cfg->softmax_scale >= 0.f)) return bad("tkv_create: scales must be >= 0");
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr) || (cfg->pin_alloc == nullptr) != (cfg->pin_free == nullptr))
     return bad("tkv_create: allocator callbacks must come in alloc/free pairs");
@@ -482,7 +483,9 @@ tkv_status tkv_create(const tkv_config* cfg, tkv_cache** out) {
   ok = ok && dalloc(c, v.mvd_src, BN) && dalloc(c, v.mvd_dst, BN);
   ok = ok && dalloc(c, v.g_seq, BN) && dalloc(c, v.g_src, BN) && dalloc(c, v.g_dst, BN);
   ok = ok && dalloc(c, c->d_host_base, (size_t)B);
-  if (cfg->scorer == TKV_SCORE_VATP) ok = ok && dalloc(c, v.vnorm, (size_t)L * B * Hkv * N);
+  if (cfg->scorer == TKV_SCORE_VATP || cfg->scorer == TKV_SCORE_COMBINED) ok = ok && dalloc(c, v.vnorm, (size_t)L * B * Hkv * N);
+  if (cfg->scorer == TKV_SCORE_REDUNDANCY || cfg->scorer == TKV_SCORE_COMBINED)
+    ok = ok && dalloc(c, v.red, (size_t)L * B * Hkv * N) && dalloc(c, v.last_k, (size_t)L * B * Hkv * D * v.es);
   v.host_base = c->d_host_base;
   {
     // one attention workgroup per compute unit: that many per (sequence, kv head) pair, as far as the pairs go round
@@ -685,6 +688,8 @@ static tkv_status attend_one(tkv_cache* c, int32_t layer, const void* q, void* o
   a.q = q; a.out = out;
   a.f_loc = use_old ? v.f_loc_old : v.f_loc; a.f_pos = v.f_pos; a.q_loc = v.q_loc; a.q_pos = v.q_pos;
   a.vnorm = v.vnorm ? v.vnorm + lrows * v.Nmax : nullptr;
+  a.red = v.red ? v.red + lrows * v.Nmax : nullptr;
+  a.red_w = c->cfg.redundancy_weight > 0.f ? c->cfg.redundancy_weight : 1.0f;
   a.cnt = v.cnt; a.score = v.score; a.xs = c->xs; a.part_ml = c->part_ml; a.part_o = c->part_o;
   if (m > 1) { a.xs = c->xs_chunk; a.part_ml = c->ml_chunk; a.part_o = c->po_chunk; }
   if (noalloc) {

@@ -78,6 +78,9 @@ struct DevView {
   int* h_clr;               // [B][Nmax] scratch: host rows of the positions that leave T1 in the plan being committed
   float* vnorm;             // [L][B][Hkv][Nmax] value-aware scorer: Euclidean norm of every appended value row, by position
                             // (NULL with the attention-only scorer)
+  float* red;               // [L][B][Hkv][Nmax] redundancy-penalised scorers: clamped cosine of every appended key row with
+                            // the key row appended before it, by position (else NULL)
+  char* last_k;             // [L][B][Hkv][D] the key row appended last, in the KV type (with red)
 };
 
 struct AttnArgs {
@@ -96,6 +99,8 @@ struct AttnArgs {
   int second;       // != 0: that second launch; its list lengths are nS, its logits follow the first launch's tiles
   const int* s_pos; // [B][Nmax] positions of the T1 list (streamed T1), for the finishing kernel
   const float* vnorm; // [B][Hkv][Nmax] this layer's value-row norms (value-aware scorer), else NULL
+  const float* red;   // [B][Hkv][Nmax] this layer's key redundancies (redundancy-penalised scorers), else NULL
+  float red_w;        // weight of the redundancy penalty
   int n_tiles;      // max over the sequences of F tiles + Q tiles (+ T1 tiles)
   int q_bs, o_bs;   // query heads between consecutive sequences in q and in out: Hq, or n_q * Hq for the tokens of a chunk
   int trim;         // entries at the end of list F this call leaves out (the chunk's later tokens); nF[] has them

@@ -18,17 +18,18 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 class Pair:
     """One GPU cache and one oracle cache fed with identical stored values."""
 
-    def __init__(self, cfg, prefetch_mode="wait", preload=True, scorer="attention", **gpu_kw):
+    def __init__(self, cfg, prefetch_mode="wait", preload=True, scorer="attention", redundancy_weight=1.0, **gpu_kw):
         self.cfg = cfg
         self.wl = Workload(cfg, device="cuda")
         self.score_scale = cfg.score_scale if cfg.score_scale is not None else 1.0 / (cfg.n_layers * cfg.n_q_heads)
         self.gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                                 kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt,
                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale,
-                                prefetch_mode=prefetch_mode, scorer=scorer, **gpu_kw)
+                                prefetch_mode=prefetch_mode, scorer=scorer, redundancy_weight=redundancy_weight, **gpu_kw)
         self.orc = O.OracleCache(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
                                  kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, n_prompt=cfg.n_prompt,
-                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale, scorer=scorer)
+                                 k_sink=cfg.k_sink, k_window=cfg.k_window, score_scale=self.score_scale, scorer=scorer,
+                                 redundancy_weight=redundancy_weight)
         self.steps_done = 0
         if preload:
             for l in range(cfg.n_layers):
@@ -99,12 +100,14 @@ def assert_t2_rows_exact(p, tiers, layers=None, seqs=None, kv_heads=None, what="
     return rows
 
 
-def assert_scores_close(got32, ref64, n, total_mass, what=""):
+def assert_scores_close(got32, ref64, n, total_mass, what="", mag64=None):
     """|s_gpu - s_ref| <= 1e-4 * s_ref + 1e-9 * (total mass added so far) / n  (the floor only guards
-    weights that underflowed)."""
+    weights that underflowed).  A penalised score is a difference: there the relative part is taken of mag64, the sum
+    of the magnitudes of what was added and what was taken off (the oracle tracks it), which is s_ref itself for the
+    scorers that only add."""
     got = got32[:, :n].astype(np.float64)
     ref = ref64[:, :n]
-    bound = TOL_SCORE_REL * ref + 1e-9 * total_mass / max(n, 1)
+    bound = TOL_SCORE_REL * (ref if mag64 is None else mag64[:, :n]) + 1e-9 * total_mass / max(n, 1)
     bad = np.abs(got - ref) > bound
     assert not bad.any(), (f"{what}: {bad.sum()} scores off, worst rel "
                            f"{(np.abs(got - ref) / np.maximum(ref, 1e-300)).max():.3e}")

@@ -71,7 +71,8 @@ def test_create_rejects_bad_configs_before_touching_the_device():
     assert status(t2_format=2) == tkv.TKV_EINVAL
     assert status(k_window=-1) == tkv.TKV_EINVAL
     assert status(prefetch_mode=5) == tkv.TKV_EINVAL
-    assert status(scorer=2) == tkv.TKV_EINVAL
+    assert status(scorer=4) == tkv.TKV_EINVAL
+    assert status(scorer=2, redundancy_weight=-1.0) == tkv.TKV_EINVAL
     assert lib.tkv_create(None, None) == tkv.TKV_EINVAL
     assert b"tkv_create" in lib.tkv_last_error(None)
     lib.tkv_destroy(None)

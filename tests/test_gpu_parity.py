@@ -27,8 +27,8 @@ def _total(p, cfg, calls, n, scorer):
     """What the underflow floor of the score tolerance is a fraction of: the total a sequence's scores have received.
     Attention scorer: the closed form (one unit per query head and call).  Value-aware scorer: every unit is weighted by
     a value-row norm, so the total is the reference's own sum over the sequence (the largest over the batch)."""
-    if scorer == "vatp":
-        return float(p.orc.score[:, :n].sum(axis=1).max())
+    if scorer != "attention":
+        return float(p.orc.score_mag[:, :n].sum(axis=1).max())
     return _mass(cfg, calls)
 
 
@@ -381,7 +381,7 @@ def _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, host_rows=None, all_t1_rows=False
             assert_out_close(got, ref, kv_dtype, f"round {rnd} layer {l}")
         n += 1
         tiers = np.concatenate([tiers, np.zeros((cfg.batch, 1), np.uint8)], axis=1)
-    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _mass(cfg, calls))
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _mass(cfg, calls), mag64=p.orc.score_mag)
     p.gpu.wait_prefetch()
     st = p.gpu.get_stats()
     assert st["tier_count"] == [int(c) for c in np.bincount(tiers[:, :n - 1].ravel(), minlength=4) + np.array([cfg.batch, 0, 0, 0])]
@@ -618,7 +618,58 @@ def test_value_aware_scorer_walk(mode, kv_dtype, D, Hq, Hkv, t2):
     _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, layers=3, scorer="vatp")
 
 
-@pytest.mark.parametrize("mode,scorer", [("lazy", "vatp"), ("stream", "vatp"), ("stream", "attention")])
+@pytest.mark.parametrize("mode,kv_dtype,D,Hq,Hkv,t2,scorer,weight", [
+    ("lazy", "bf16", 128, 10, 2, "int8_row", "redundancy", 1.0),
+    ("wait", "f16", 64, 8, 2, "int4_g32", "combined", 2.5),
+    ("stream", "bf16", 128, 14, 2, "int8_row", "redundancy", 0.4),
+    ("lazy", "f32", 64, 6, 2, "int8_row", "combined", 1.0),
+])
+def test_redundancy_scorers_walk(mode, kv_dtype, D, Hq, Hkv, t2, scorer, weight):
+    """The plan walk with the redundancy-penalised scorers of the scoring ablation ("attn - redundancy", "attn x val -
+    redundancy"): the penalty is the clamped cosine of a key row with the row appended before it (taken at append,
+    whatever happens to either row later), spread over the positions a query attends to.  The walk's appended rows
+    are random, so half of the cosines are clamped to zero and the rest are small: scores against the oracle's."""
+    _plan_walk(mode, kv_dtype, D, Hq, Hkv, t2, layers=3, scorer=scorer, redundancy_weight=weight)
+
+
+def test_redundancy_of_crafted_key_rows():
+    """Key rows whose neighbours are copies, scaled copies, opposed, orthogonal or zero: after one attention call per
+    layer the scores are the oracle's (cosines 1, 1, 0 (clamped), 0, 0), also across an append boundary where the
+    neighbour is the row kept from the previous append, and after that neighbour has been evicted."""
+    from gpu_common import Pair, assert_scores_close, to_f64
+    cfg = small_config(n_layers=2, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, kv_dtype="bf16", context=40,
+                       decode_steps=4, sigma=1.0, k_window=4, k_sink=2)
+    p = Pair(cfg, prefetch_mode="lazy", preload=False, scorer="redundancy", redundancy_weight=3.0)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    base = torch.randn((cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim), generator=g)
+    other = torch.randn((cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim), generator=g)
+    orth = other - (other * base).sum(-1, keepdim=True) / (base * base).sum(-1, keepdim=True) * base
+    rows = [base, base, 2.0 * base, -base, orth, torch.zeros_like(base), base, 0.5 * base]
+    k = torch.cat(rows + [torch.randn((cfg.batch, 32, cfg.n_kv_heads, cfg.head_dim), generator=g)], dim=1).to(torch.bfloat16).cuda()
+    v = torch.randn(k.shape, generator=g).to(torch.bfloat16).cuda()
+    for l in range(cfg.n_layers):
+        p.append(l, k[:, :5].contiguous(), v[:, :5].contiguous())      # the boundary falls between "-base" and "orth" ...
+    tiers = np.zeros((cfg.batch, 5), np.uint8); tiers[:, 4] = 3      # ... and "orth"'s own row is evicted afterwards
+    tiers[:, 3] = 3                                                   # as is the neighbour the next append compares with
+    p.force_tiers(tiers)
+    for l in range(cfg.n_layers):
+        p.append(l, k[:, 5:].contiguous(), v[:, 5:].contiguous())
+    n = k.shape[1]
+    calls = 0
+    for l in range(cfg.n_layers):
+        q = torch.randn((cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=g).to(torch.bfloat16).cuda()
+        p.attend(l, q); calls += 1
+    rho = p.orc.rho[0][:, :, :8]
+    want = np.array([0, 1, 1, 0, 0, 0, 0, 1], np.float64)
+    assert np.allclose(rho, want[None, None, :], atol=2e-2)          # bf16 rounding of the crafted rows
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, float(p.orc.score_mag[:, :n].sum(axis=1).max()),
+                        "crafted neighbours", mag64=p.orc.score_mag)
+    assert (p.orc.score[:, :n] < 0).any()                             # the penalty really takes scores below zero
+    p.close()
+
+
+@pytest.mark.parametrize("mode,scorer", [("lazy", "vatp"), ("stream", "vatp"), ("stream", "attention"),
+                                         ("lazy", "redundancy"), ("wait", "combined")])
 def test_whole_steps_and_classify(mode, scorer):
     """Whole decode steps (one append launch for all layers, so the norms of the new rows of every layer come from one
     launch) with re-tiering by the value-aware scores: the plan is the oracle's for the GPU's score array, bit for bit,
@@ -641,7 +692,7 @@ def test_whole_steps_and_classify(mode, scorer):
         if step % 4 == 3:
             n = p.gpu.layer_length(0)
             s_gpu = p.gpu.get_scores()
-            assert_scores_close(s_gpu, p.orc.score, n, _total(p, cfg, calls, n, scorer), f"step {step}")
+            assert_scores_close(s_gpu, p.orc.score, n, _total(p, cfg, calls, n, scorer), f"step {step}", mag64=p.orc.score_mag)
             p.gpu.classify(pol)
             plan = p.gpu.get_pending_tiers()[:, :n]
             assert np.array_equal(plan, p.orc.classify(pol, score_f32=s_gpu)[:, :n])
@@ -677,6 +728,8 @@ def test_whole_steps_and_classify(mode, scorer):
     ("lazy", "bf16", 128, 12, 2, "int4_g32", "attention", 2),     # G = 6: 5 tokens per launch, 30 columns
     ("lazy", "f16", 128, 10, 2, "int8_row", "attention", 2),      # G = 5, binary16
     ("lazy", "bf16", 64, 6, 2, "int4_g32", "attention", 3),       # G = 3, 32-byte code rows
+    ("lazy", "bf16", 128, 10, 2, "int8_row", "redundancy", 2),    # the penalty per query token: its own count of positions
+    ("wait", "f32", 64, 8, 2, "int8_row", "combined", 2),
 ])
 def test_chunks_of_query_tokens(mode, kv_dtype, D, Hq, Hkv, t2, scorer, batch):
     """Several query tokens per sequence at once: chunks of 6, 1 and 9 tokens appended to every layer and attended
@@ -706,7 +759,7 @@ def test_chunks_of_query_tokens(mode, kv_dtype, D, Hq, Hkv, t2, scorer, batch):
                 assert_out_close(got[:, j], ref[:, j], kv_dtype, f"chunk {T} layer {l} query {j}")
         step += T
         n += T
-    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _total(p, cfg, calls, n, scorer))
+    assert_scores_close(p.gpu.get_scores(), p.orc.score, n, _total(p, cfg, calls, n, scorer), mag64=p.orc.score_mag)
     # 16 positions were appended since the plan: a chunk of 17 would reach into re-tiered positions
     q17 = torch.zeros((cfg.batch, 17, Hq, D), dtype=q.dtype, device=q.device)
     with pytest.raises(tkv.TkvError) as e:
