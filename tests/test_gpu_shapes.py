@@ -63,6 +63,63 @@ def test_32b_shape():
     _run_shape(dataclasses.replace(CONFIGS["32b"], n_layers=1, decode_steps=3), "lazy")
 
 
+def test_prod_shape_all_64_sequences_one_workgroup_per_pair():
+    """The production-batch launch as the bench runs it: 64 sequences x 4 kv heads = 256 pairs, so every pair gets ONE
+    workgroup (S = 1) whose eight waves share all F tiles and all int4 Q tiles of a 16384-token list.  The GPU runs
+    the whole batch; four of its sequences (first, last, two in between) are checked against an oracle that holds
+    just those four (sequences are independent): outputs, scores after a forced four-tier plan, and a chunk of three
+    query tokens through the matrix-core launch at the same shape."""
+    import paper_2605_09490_amd as tkv
+    from gpu_common import assert_out_close, assert_scores_close, to_f64
+    from oracle import tkv_oracle as O
+    from tkv_synth import Workload
+    cfg = dataclasses.replace(CONFIGS["prod"], n_layers=1, decode_steps=5)
+    pick = [0, 21, 42, 63]
+    print(f"[case] prod-shaped, all {cfg.batch} sequences, ctx={cfg.context}, checking sequences {pick}", flush=True)
+    wl = Workload(cfg, device="cuda")
+    gpu = tkv.TieredKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
+                       kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, k_sink=cfg.k_sink, k_window=cfg.k_window,
+                       prefetch_mode="lazy")
+    orc = O.OracleCache(cfg.n_layers, len(pick), cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens,
+                        kv_dtype=cfg.kv_dtype, t2_format=cfg.t2_format, k_sink=cfg.k_sink, k_window=cfg.k_window)
+    k, v = wl.context_kv(0)
+    gpu.append(0, k, v)
+    orc.append(0, to_f64(k[pick]), to_f64(v[pick]))
+    del k, v
+    n = cfg.context
+    rng = np.random.default_rng(3)
+    tiers = rng.choice(4, size=(cfg.batch, n), p=(0.4, 0.37, 0.2, 0.03)).astype(np.uint8)
+    tiers[:, :4] = 0
+    tiers[:, n - 128:] = 0
+    gpu.set_tiers(tiers); gpu.migrate()
+    orc.set_tiers(tiers[pick]); orc.migrate()
+    calls = 0
+    for step in range(2):
+        ks, vs = wl.step_kv(step, 0)
+        q = wl.step_q(step, 0)
+        gpu.append(0, ks, vs)
+        orc.append(0, to_f64(ks[pick]), to_f64(vs[pick]))
+        out = gpu.attend_and_score(0, q)
+        ref = orc.attend_and_score(0, to_f64(q[pick]))
+        assert_out_close(to_f64(out[pick]), ref, cfg.kv_dtype, f"step {step}")
+        calls += 1
+    T = 3
+    ks, vs = zip(*[wl.step_kv(2 + j, 0) for j in range(T)])
+    kc, vc = torch.cat(ks, dim=1), torch.cat(vs, dim=1)
+    gpu.append(0, kc, vc)
+    orc.append(0, to_f64(kc[pick]), to_f64(vc[pick]))
+    q = torch.stack([wl.step_q(2 + j, 0) for j in range(T)], dim=1).contiguous()
+    out = gpu.attend_and_score_chunk(0, q)
+    ref = orc.attend_and_score_chunk(0, to_f64(q[pick]))
+    for j in range(T):
+        assert_out_close(to_f64(out[pick, j]), ref[:, j], cfg.kv_dtype, f"chunk query {j}")
+    calls += T
+    nn = gpu.layer_length(0)
+    ss = 1.0 / (cfg.n_layers * cfg.n_q_heads)
+    assert_scores_close(gpu.get_scores()[pick], orc.score, nn, calls * cfg.n_q_heads * ss)
+    gpu.close()
+
+
 def test_prod_shape_subset_of_sequences():
     # 16384-token context, int4-g32 T2; 4 of the 64 sequences (sequences are independent units of work)
     _run_shape(dataclasses.replace(CONFIGS["prod"], n_layers=1, batch=4, decode_steps=2), "lazy", steps_after=1)
