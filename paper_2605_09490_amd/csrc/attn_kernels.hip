@@ -1747,7 +1747,7 @@ template <int D, int G>
 __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int n_tiles) {
   constexpr int MAXQ = 16;
   __shared__ float M[MAXQ][128], IL[MAXQ][128];
-  __shared__ float sm_part[256];
+  __shared__ float sm_part[4 * 256];
   const int t = threadIdx.x, b = blockIdx.y, nq = a.n_q * a.cq, ns = a.S_total;
   int nF, nQ;
   if (a.B <= ATTN_ARG_SEQS) { nF = a.nF[b]; nQ = a.nQ[b]; }
@@ -1775,34 +1775,48 @@ __global__ __launch_bounds__(256) void k_attn_finish_chunk(const AttnArgs a, int
     if (is_f) pos = a.f_pos[(size_t)b * a.Nmax + sl];
     else if (is_q) pos = a.q_pos[(size_t)b * a.Nmax + (sl - cf * TB)];
     float score = (hg == 0 && pos >= 0) ? a.score[(size_t)b * a.Nmax + pos] : 0.f;
-    for (int jt = 0; jt < nq; ++jt) {
-      const int nFj = nF - (nq - 1 - jt);                                   // what the query sees of list F
-      const int cfz = (nF - (a.n_q - 1 - jt / a.cq) * a.cq + TB - 1) / TB;  // F tiles in its group's layout
-      const bool seen = is_q || (is_f && sl < nFj);         // wave-divergent at most in a list's last tile
-      const float pen = a.red ? a.red_w * (float)G / (float)(nFj + nQ) : 0.f;
-      const int col = is_q ? cfz * TB + (sl - cf * TB) : sl;
-      float acc = 0.f;
-      if (seen) {
-        for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
-          float x[G];
+    // four tokens at a time: their sums are independent (all loads in flight together), only the additions into the
+    // score go in token order
+    for (int j0 = 0; j0 < nq; j0 += 4) {
+      float acc[4];
+      bool seen[4];
 #pragma unroll
-          for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)(b * nq + jt) * a.Hq + kvh * G + g) * a.xs_stride + col];
-          if (a.vnorm) {
-            float w = 0.f;
+      for (int u = 0; u < 4; ++u) {
+        const int jt = j0 + u;
+        acc[u] = 0.f; seen[u] = false;
+        if (jt >= nq) continue;
+        const int nFj = nF - (nq - 1 - jt);                                   // what the query sees of list F
+        const int cfz = (nF - (a.n_q - 1 - jt / a.cq) * a.cq + TB - 1) / TB;  // F tiles in its group's layout
+        seen[u] = is_q || (is_f && sl < nFj);               // wave-divergent at most in a list's last tile
+        const float pen = a.red ? a.red_w * (float)G / (float)(nFj + nQ) : 0.f;
+        const int col = is_q ? cfz * TB + (sl - cf * TB) : sl;
+        if (seen[u]) {
+          for (int kvh = hg; kvh < a.Hkv; kvh += 4) {
+            float x[G];
 #pragma unroll
-            for (int g = 0; g < G; ++g) w += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
-            acc = fmaf(w, a.vnorm[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
-          } else {
+            for (int g = 0; g < G; ++g) x[g] = a.xs[((size_t)(b * nq + jt) * a.Hq + kvh * G + g) * a.xs_stride + col];
+            if (a.vnorm) {
+              float w = 0.f;
 #pragma unroll
-            for (int g = 0; g < G; ++g) acc += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
+              for (int g = 0; g < G; ++g) w += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
+              acc[u] = fmaf(w, a.vnorm[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc[u]);
+            } else {
+#pragma unroll
+              for (int g = 0; g < G; ++g) acc[u] += __builtin_amdgcn_exp2f((x[g] - M[jt][kvh * G + g]) * LOG2E) * IL[jt][kvh * G + g];
+            }
+            if (a.red) acc[u] = fmaf(-pen, a.red[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc[u]);
           }
-          if (a.red) acc = fmaf(-pen, a.red[((size_t)b * a.Hkv + kvh) * a.Nmax + pos], acc);
         }
       }
       __syncthreads();
-      sm_part[hg * 64 + e] = acc;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sm_part[u * 256 + hg * 64 + e] = acc[u];
       __syncthreads();
-      if (hg == 0 && seen) score = score + a.score_scale * (((sm_part[e] + sm_part[64 + e]) + sm_part[128 + e]) + sm_part[192 + e]);
+      if (hg == 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (seen[u]) score = score + a.score_scale * (((sm_part[u * 256 + e] + sm_part[u * 256 + 64 + e]) + sm_part[u * 256 + 128 + e]) + sm_part[u * 256 + 192 + e]);
+      }
     }
     if (hg == 0 && pos >= 0) a.score[(size_t)b * a.Nmax + pos] = score;
   } else {
