@@ -203,8 +203,12 @@ tkv_status tkv_attend_and_score_noalloc(tkv_cache* c, int32_t layer, const void*
  * appended): q device [batch, n_q, n_q_heads, head_dim], out the same shape.  Query j belongs to position
  * n - n_q + j of the layer's n positions and attends to the positions up to and including its own (Eq. 2 sums
  * i = 1..t for the token at t); each query adds its weights to the scores (Eq. 1), in the order j = 0 .. n_q-1, which
- * is what n_q single-token steps would have done.  One launch of the decode kernels per query token: the cache is
- * read n_q times.  ESTATE unless all n_q positions were appended after the last tkv_migrate (they are then in T0). */
+ * is what n_q single-token steps would have done.  With 16-bit rows the tokens of a chunk ride as extra columns of
+ * one launch (up to 32 / group size of them, at most 16; longer chunks go in groups), so the cache is read once per
+ * group; the first call allocates scratch for one such group from the handle's allocator.  binary32 rows and
+ * TKV_PREFETCH_STREAM take the decode kernels once per token.  Outputs and scores agree with single-token steps to
+ * binary32 rounding (the summation order differs), not bit for bit; T1 placement stays bit-invisible (Prop. 1).
+ * ESTATE unless all n_q positions were appended after the last tkv_migrate (they are then in T0). */
 tkv_status tkv_attend_and_score_chunk(tkv_cache* c, int32_t layer, const void* q, void* out, int32_t n_q, void* hip_stream);
 
 /* One decode step of Algorithm 1's loop body for all layers, in layer order: for every layer l,
