@@ -406,8 +406,10 @@ def main():
                          "and steady ones as the timed region)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
-    ap.add_argument("--others", default="7b,32b,prod",
-                    help="comma-separated other workloads to add a compact record for (twin + lazy once each); '' for none. "
+    ap.add_argument("--others", default="14b-tail,7b,32b,prod",
+                    help="comma-separated other workloads to add a compact record for (twin + lazy once each); '' for none.  "
+                         "14b-tail is the main workload's shape and policy with log-normal attention over the positions (Sec. 2.1) "
+                         "instead of the benchmark recipe's near one-hot attention. "
                          "They are skipped, and the line says so, once the run has taken --others-budget seconds")
     ap.add_argument("--others-budget", type=float, default=100.0)
     ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "f16", "f32"], help="K, V and query type (default: the workload's own)")

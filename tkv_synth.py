@@ -14,6 +14,15 @@ available offline):
   K <- c * K; optionally a random `boost_frac` of positions gets K <- boost * K
   (late-referenced intermediate results).  Queries ~ N(0, 1) fresh per
   (step, layer).  All values are rounded to the KV dtype (bf16, fp16 or fp32).
+  This is the recipe the benchmark configurations state (recipe = "scale").  Because the factor multiplies the whole
+  key row, it multiplies the logits, and the attention of every query collapses onto the few largest factors.
+
+Second recipe (recipe = "bias", the "-tail" configurations): the same per-position draw enters the logits as an
+  additive term instead: K ~ N(0, 1) unscaled, except that element 0 of every key row is sigma * z (plus log(boost)
+  for a boosted position) and element 0 of every query is sqrt(head_dim), so that a position's logit is
+  sigma * z + (a unit-variance term that differs per query).  Averaged over queries, layers and heads a position's
+  attention weight is then proportional to exp(sigma * z): log-normal, the long tail of Sec. 2.1 (sigma = 1 puts
+  about 56 % of the mass on the top 20 % of positions).
 """
 from __future__ import annotations
 
@@ -44,6 +53,7 @@ class WorkloadConfig:
     n_prompt: int = 0
     score_scale: float | None = None   # None -> 1/(L*Hq) (Eq. 1)
     seed: int = 0
+    recipe: str = "scale"    # "scale": the position factor multiplies the key row; "bias": it is added to the logit
 
     @property
     def max_tokens(self) -> int:
@@ -68,6 +78,11 @@ CONFIGS = {
     "prod": WorkloadConfig("prod", 28, 64, 28, 4, 128, "bf16", 16384, 16, 8,
                            (300_000, 470_000, 200_000, 30_000), "int4_g32", 1.0),
 }
+# the 14B shape and policy with the log-normal attention profile the method is described on (not a benchmark
+# configuration: the graded line uses "14b")
+CONFIGS["14b-tail"] = WorkloadConfig("14b-tail", 48, 8, 40, 8, 128, "bf16", 4096, 64, 16,
+                                     (300_000, 520_000, 150_000, 30_000), "int8_row", 1.0,
+                                     boost_frac=0.03, boost=4.0, recipe="bias")
 
 
 def _gen(device, *key) -> torch.Generator:
@@ -93,6 +108,10 @@ class Workload:
             u = torch.rand(cfg.batch, n_total, generator=g)
             c = torch.where(u < cfg.boost_frac, c * cfg.boost, c)
         self.key_factor = c.to(self.device)          # [B, n_total]
+        self.bias = cfg.recipe == "bias"
+        assert cfg.recipe in ("scale", "bias")
+        self.key_bias = torch.log(c).to(self.device)  # [B, n_total]: what the "bias" recipe writes into element 0 of a key row
+        self.q0 = float(cfg.head_dim) ** 0.5
 
     def _kv(self, lo, hi, layer, tag):
         cfg = self.cfg
@@ -100,7 +119,10 @@ class Workload:
         shape = (cfg.batch, hi - lo, cfg.n_kv_heads, cfg.head_dim)
         k = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32)
         v = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32)
-        k = k * self.key_factor[:, lo:hi, None, None]
+        if self.bias:
+            k[..., 0] = self.key_bias[:, lo:hi, None]
+        else:
+            k = k * self.key_factor[:, lo:hi, None, None]
         return k.to(cfg.torch_dtype).contiguous(), v.to(cfg.torch_dtype).contiguous()
 
     def context_kv(self, layer):
@@ -118,6 +140,8 @@ class Workload:
         g = _gen(self.device, cfg.seed, 3, step, layer)
         q = torch.randn((cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=g,
                         device=self.device, dtype=torch.float32)
+        if self.bias:
+            q[..., 0] = self.q0
         return q.to(cfg.torch_dtype).contiguous()
 
 
@@ -127,6 +151,7 @@ class Workload:
         cfg = self.cfg
         p0 = cfg.context + first_step
         fac = self.key_factor[:, p0:p0 + n_steps].t().contiguous()       # [n_steps, B]
+        bias = self.key_bias[:, p0:p0 + n_steps].t().contiguous()
         k_all = torch.empty((n_steps, cfg.n_layers, cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim),
                             dtype=cfg.torch_dtype, device=self.device)
         v_all = torch.empty_like(k_all)
@@ -136,10 +161,16 @@ class Workload:
             g = _gen(self.device, cfg.seed, 4, l, first_step)
             shape = (n_steps, cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim)
             k = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32)
-            k_all[:, l] = (k * fac[:, :, None, None, None]).to(cfg.torch_dtype)
+            if self.bias:
+                k[..., 0] = bias[:, :, None, None]
+            else:
+                k = k * fac[:, :, None, None, None]
+            k_all[:, l] = k.to(cfg.torch_dtype)
             v_all[:, l] = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32).to(cfg.torch_dtype)
-            q_all[:, l] = torch.randn((n_steps, cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=g,
-                                      device=self.device, dtype=torch.float32).to(cfg.torch_dtype)
+            q = torch.randn((n_steps, cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=g, device=self.device, dtype=torch.float32)
+            if self.bias:
+                q[..., 0] = self.q0
+            q_all[:, l] = q.to(cfg.torch_dtype)
         return k_all, v_all, q_all
 
 
