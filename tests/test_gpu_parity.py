@@ -674,9 +674,21 @@ def test_whole_steps_and_classify(mode, scorer):
     """Whole decode steps (one append launch for all layers, so the norms of the new rows of every layer come from one
     launch) with re-tiering by the value-aware scores: the plan is the oracle's for the GPU's score array, bit for bit,
     and the scores agree with the oracle's to the usual tolerance."""
+    _whole_steps(mode, scorer)
+
+
+@pytest.mark.parametrize("mode,scorer", [("lazy", "attention"), ("wait", "redundancy")])
+def test_whole_steps_and_classify_with_a_log_normal_attention_profile(mode, scorer):
+    """The same with inputs whose attention is spread log-normally over the positions (the profile the method is
+    described on) instead of collapsing onto a few: every candidate carries a distinct, non-negligible score, so the
+    band boundaries are decided among close values rather than among ties at zero."""
+    _whole_steps(mode, scorer, recipe="bias")
+
+
+def _whole_steps(mode, scorer, **cfg_kw):
     from gpu_common import assert_scores_close
     cfg = small_config(n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, head_dim=128, kv_dtype="bf16", context=700,
-                       decode_steps=12, sigma=1.0, k_window=16)
+                       decode_steps=12, sigma=1.0, k_window=16, **cfg_kw)
     p = _pair(cfg, prefetch_mode=mode, scorer=scorer)
     pol = (300000, 400000, 200000, 100000)
     calls = 0
