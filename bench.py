@@ -30,6 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 LINK_PEAK_GBPS = 64.0       # PCIe Gen5 x16, one direction
 SETTLE_EVENTS = 2           # score-driven re-tiering events before anything is timed
+TAIL_STEPS = 12             # timed steps left behind the timed region's last re-tiering event (when the region is that long)
 
 
 def log(*a):
@@ -93,7 +94,13 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0, tigh
     del k, v
     delta = cfg.reclassify_every
     pre = delta + SETTLE_EVENTS * delta
-    total = pre + warmup + steps + profile_steps
+    # Where the events fall in the timed region: one every Delta steps as in any run, phased so that the last one
+    # has TAIL_STEPS steps behind it before the closing synchronize.  The transfers of an event take about that long
+    # beside attention; in a run that goes on they overlap the following steps, and a timed region that happened to
+    # end right behind an event would charge their whole duration to it.  `phase` extra untimed steps set that up.
+    first_event = (steps - TAIL_STEPS) % delta or delta
+    phase = (-first_event - pre - warmup) % delta
+    total = pre + phase + warmup + steps + profile_steps
     assert total <= cfg.decode_steps
     k_all, v_all, q_all = wl.decode_inputs(0, total)
     out_all = torch.empty((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
@@ -150,7 +157,7 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0, tigh
             res.update({"first_event_ms": ev_all_ms, "first_event_bytes": ev_bytes})
         else:
             res.update({"settle_event_ms": ev_all_ms, "settle_event_bytes": ev_bytes})
-    loop(warmup)
+    loop(phase + warmup)
     torch.cuda.synchronize()
     gpu.wait_prefetch()
     counts[0] = list(gpu.get_stats()["tier_count"])
@@ -164,7 +171,10 @@ def run_job(cfg, policy, mode, steps, warmup, profile_steps, label, rule=0, tigh
     gpu.set_profile(0)
     gpu.wait_prefetch()
     st2 = gpu.get_stats()
+    last_event = first_event + delta * ((steps - first_event) // delta) if first_event <= steps else 0
     res.update({"wall_s": t1 - t0, "bytes": nbytes, "ms_per_step": (t1 - t0) * 1e3 / steps,
+                "phase_steps": phase, "first_event_after_step": first_event if first_event <= steps else None,
+                "steps_after_last_event": steps - last_event,
                 "tier_count": st2["tier_count"], "events": st2["n_migrate"] - st1["n_migrate"],
                 "h2d_bytes": st2["h2d_bytes"] - st1["h2d_bytes"], "h2d_ms": st2["h2d_ms"] - st1["h2d_ms"],
                 "d2h_bytes": st2["d2h_bytes"] - st1["d2h_bytes"], "d2h_ms": st2["d2h_ms"] - st1["d2h_ms"],
@@ -366,7 +376,7 @@ def compact_record(name, steps, rule):
     base = CONFIGS[name]
     delta = base.reclassify_every
     warm = 2
-    cfg = dataclasses.replace(base, decode_steps=(1 + SETTLE_EVENTS) * delta + warm + steps + delta)
+    cfg = dataclasses.replace(base, decode_steps=(2 + SETTLE_EVENTS) * delta + warm + steps + delta)
     pol = cfg.policy_ppm
     twin_pol = (pol[0] + pol[1], 0, pol[2], pol[3])
     release_memory()
@@ -439,7 +449,7 @@ def main():
     delta = args.delta or base.reclassify_every
     if args.profile_steps < 0:
         args.profile_steps = delta
-    cfg = dataclasses.replace(base, decode_steps=(1 + SETTLE_EVENTS) * delta + warmup + args.steps + args.profile_steps,
+    cfg = dataclasses.replace(base, decode_steps=(2 + SETTLE_EVENTS) * delta + warmup + args.steps + args.profile_steps,
                               reclassify_every=delta,
                               kv_dtype=args.kv_dtype or base.kv_dtype,
                               k_window=base.k_window if args.k_window < 0 else args.k_window)
@@ -454,11 +464,12 @@ def main():
     other_mode = "wait" if args.mode == "lazy" else "lazy"
     stream = args.mode == "stream"
     # Job order: the all-HBM twin (same tier counts, T1 share kept in T0) and the other prefetch mode run first, then
-    # the job `value` is taken from, then all three once more.  The overhead is a difference of two wall times and the
-    # clock of a GPU that has just left idle drifts, so kinds are compared on the faster of their two runs; `value`
+    # the job `value` is taken from, then all three twice more.  The overhead is a difference of two wall times of a few
+    # tens of milliseconds whose run-to-run spread (1-1.5 %) is a good part of the effect itself, and the clock of a
+    # GPU that has just left idle drifts, so kinds are compared on the median of their three runs; `value`
     # itself is always the one designated run (the first of the measured mode).
     kinds = [args.mode] if args.no_twin else (["twin", args.mode] if stream else
-                                              ["twin", other_mode, args.mode, "twin", other_mode, args.mode])
+                                              ["twin", other_mode, args.mode] * 3)
     runs = {k: [] for k in kinds}
     runs_all_in = {k: [] for k in kinds}     # timed loop + the initial tiering with its cold fill
     events = {}
@@ -483,8 +494,9 @@ def main():
         release_memory()
     extra = {}
     if not args.no_twin:
-        best = {k: min(v) for k, v in runs.items()}
-        best_all = {k: min(v) for k, v in runs_all_in.items()}
+        import statistics
+        best = {k: statistics.median(v) for k, v in runs.items()}
+        best_all = {k: statistics.median(v) for k, v in runs_all_in.items()}
         twin_step = best["twin"] / args.steps
 
         def per_event_ms(kind):
@@ -502,8 +514,9 @@ def main():
             **({} if stream else {f"prefetch_overhead_pct_{other_mode}": amortised(other_mode),
                                   f"prefetch_overhead_timed_region_pct_{other_mode}":
                                       round(100.0 * (best[other_mode] - best["twin"]) / best["twin"], 2)}),
-            "overhead_definition": "(timed-region wall time - the all-in-HBM twin's) per re-tiering event in the region, over "
-                                   "Delta twin steps; *_timed_region_pct is the plain ratio over the --steps timed steps",
+            "overhead_definition": "(timed-region wall time - the all-in-HBM twin's, medians of three runs each) per re-tiering "
+                                   "event in the region, over Delta twin steps; *_timed_region_pct is the plain ratio over "
+                                   "the --steps timed steps",
             "ms_per_step_runs": {k: [round(w * 1e3 / args.steps, 4) for w in v] for k, v in runs.items()},
         }
     value = main_res["bytes"] / main_res["wall_s"] / 1e9
@@ -540,7 +553,9 @@ def main():
                                + (f", k_window {cfg.k_window}" if args.k_window >= 0 else "")
                                + (", Algorithm-1 count rule" if rule else "")
                                + (f", {SCORER} scorer" if SCORER != "attention" else ""),
-                   "untimed_pre_roll_steps": (1 + SETTLE_EVENTS) * delta + warmup,
+                   "untimed_pre_roll_steps": (1 + SETTLE_EVENTS) * delta + main_res["phase_steps"] + warmup,
+                   "first_event_after_timed_step": main_res["first_event_after_step"],
+                   "timed_steps_after_last_event": main_res["steps_after_last_event"],
                    "score_driven_events_before_timing": SETTLE_EVENTS},
         "hbm_peak_frac": round(value / HBM_PEAK_GBPS, 4),
         "decode_steps_per_s": round(1e3 / main_res["ms_per_step"], 1),
