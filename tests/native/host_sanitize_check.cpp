@@ -38,7 +38,8 @@ static void run_mode(int mode) {
   cfg.n_layers = L; cfg.batch = B; cfg.n_q_heads = Hq; cfg.n_kv_heads = Hkv; cfg.head_dim = D; cfg.max_tokens = NMAX;
   cfg.kv_dtype = TKV_BF16; cfg.out_dtype = TKV_F32; cfg.t2_format = mode == 1 ? TKV_T2_INT4_G32 : TKV_T2_INT8_ROW;
   cfg.k_sink = 4; cfg.k_window = 16; cfg.prefetch_mode = mode;
-  cfg.scorer = mode == 1 ? TKV_SCORE_VATP : TKV_SCORE_ATTENTION;
+  cfg.scorer = mode == 1 ? TKV_SCORE_VATP : mode == 2 ? TKV_SCORE_COMBINED : TKV_SCORE_REDUNDANCY;
+  cfg.redundancy_weight = mode == 0 ? 0.f : 1.5f;       // 0: the default weight
   cfg.host_rows = 480;                       // small: the store is rewritten every few plans
   tkv_cache* c = nullptr;
   CHECK(tkv_create(&cfg, &c) == TKV_OK && c);
